@@ -1,0 +1,428 @@
+"""Pins for the CPU oracle: each test ties it to something other than itself
+(the paper's printed numbers, a library routine, a closed form, an invariant,
+or scalar brute force), so that a plausible mistake in it fails at least one.
+CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import echokv_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rnd(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+def make_case(H_q, H_kv, d, m, L, seed=0, T_q=1):
+    D = H_kv * d
+    r = np.random.default_rng(seed)
+    K_a, V_a = r.standard_normal((L, D)), r.standard_normal((L, D))
+    K_r, V_r = r.standard_normal((L, m)), r.standard_normal((L, m))
+    W_K = r.standard_normal((D + m, D - m)) / math.sqrt(D + m)
+    W_V = r.standard_normal((D + m, D - m)) / math.sqrt(D + m)
+    Q = r.standard_normal((T_q, H_q, d))
+    return dict(K_a=K_a, V_a=V_a, K_r=K_r, V_r=V_r, W_K=W_K, W_V=W_V), Q
+
+
+def sdpa(Q, K, V, H_kv, scale=None, causal_from=None):
+    """Library attention (torch CPU, fp64).  Q [T,H_q,d]; K,V [L,D]."""
+    T, H_q, d = Q.shape
+    L = K.shape[0]
+    G = H_q // H_kv
+    q = torch.from_numpy(Q).permute(1, 0, 2)[None]                    # [1,H_q,T,d]
+    k = torch.from_numpy(K).reshape(L, H_kv, d).permute(1, 0, 2)
+    v = torch.from_numpy(V).reshape(L, H_kv, d).permute(1, 0, 2)
+    k = k.repeat_interleave(G, dim=0)[None]
+    v = v.repeat_interleave(G, dim=0)[None]
+    mask = None
+    if causal_from is not None:
+        j = torch.arange(L)[None, :]
+        i = torch.arange(T)[:, None]
+        mask = j <= (causal_from + i)
+    o = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=mask,
+                                                         scale=scale)
+    return o[0].permute(1, 0, 2).numpy()
+
+
+# ---- P11: integers and ratios the paper prints --------------------------------
+def load_table():
+    rows = []
+    with open(os.path.join(GOLDEN, "paper_predictor_table.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                t = line.split()
+                rows.append((float(t[0]), int(t[1]), int(t[2]), int(t[3]), int(t[4]),
+                             float(t[5]), float(t[6])))
+    return rows
+
+
+def test_paper_table_dims_ratio_params():
+    rows = load_table()
+    assert len(rows) == 3
+    for target, S, m, d_in, d_out, params_m, eff in rows:
+        assert orc.predictor_dims(1024, m) == (d_in, d_out)
+        ratio = orc.compression_ratio(1024, m, S)
+        assert abs(ratio - eff) <= 0.006          # printed to two digits
+        assert abs(ratio - target) <= 0.02
+        n = orc.predictor_param_count(32, S, 1024, m)
+        assert abs(n / 1e6 - params_m) <= 0.07    # printed to one decimal
+    assert orc.compression_ratio(1024, 384, 2) == 0.6875
+    assert orc.compression_ratio(1024, 64, 4) == 0.296875
+
+
+# ---- P1: full retention is ordinary attention ---------------------------------
+@pytest.mark.parametrize("H_q,H_kv,d", [(4, 4, 8), (8, 2, 16), (6, 3, 4)])
+def test_full_retention_is_standard_attention(H_q, H_kv, d):
+    L = 37
+    c, Q = make_case(H_q, H_kv, d, H_kv * d, L, seed=3)
+    o, lse = orc.echokv_decode(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"],
+                               None, None, H_kv)
+    ref = sdpa(Q, c["K_r"], c["V_r"], H_kv)[0]
+    np.testing.assert_allclose(o, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_scale_argument_and_default():
+    c, Q = make_case(4, 2, 8, 8, 21, seed=5)
+    args = (c["K_a"], c["V_a"], c["K_r"], c["V_r"], c["W_K"], c["W_V"], 2)
+    o_def, _ = orc.echokv_decode(Q[0], *args)
+    o_exp, _ = orc.echokv_decode(Q[0], *args, scale=1 / math.sqrt(8))
+    o_neg, _ = orc.echokv_decode(Q[0], *args, scale=-1.0)
+    np.testing.assert_allclose(o_def, o_exp, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(o_def, o_neg, rtol=0, atol=1e-15)
+    o_other, _ = orc.echokv_decode(Q[0], *args, scale=0.9)
+    K_t = orc.reconstruct(c["K_a"], c["K_r"], c["W_K"])
+    V_t = orc.reconstruct(c["V_a"], c["V_r"], c["W_V"])
+    np.testing.assert_allclose(o_other, sdpa(Q, K_t, V_t, 2, scale=0.9)[0],
+                               rtol=1e-12, atol=1e-13)
+
+
+# ---- P2: selector weights copy known heads exactly -----------------------------
+def test_selector_weights_reproduce_copied_columns():
+    H_kv, d, m, L = 4, 8, 16, 19
+    D = H_kv * d
+    c, Q = make_case(8, H_kv, d, m, L, seed=7)
+    # output column c copies: first half from anchor columns (reversed order),
+    # second half from retained columns (input index D + r).
+    src = [D - 1 - i for i in range((D - m) // 2)] + \
+          [D + (i % m) for i in range((D - m) - (D - m) // 2)]
+    W = np.zeros((D + m, D - m))
+    for col, s in enumerate(src):
+        W[s, col] = 1.0
+    K_t = orc.reconstruct(c["K_a"], c["K_r"], W)
+    assert np.array_equal(K_t[:, :m], c["K_r"])                 # retained first
+    X = np.concatenate([c["K_a"], c["K_r"]], axis=1)
+    assert np.array_equal(K_t[:, m:], X[:, src])                 # exact copies
+    # and the attention over it is attention over the hand-assembled cache
+    V_t = orc.reconstruct(c["V_a"], c["V_r"], W)
+    o, _ = orc.echokv_decode(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"], W, W, H_kv)
+    np.testing.assert_allclose(o, sdpa(Q[:1], K_t, V_t, H_kv)[0], rtol=1e-12, atol=1e-13)
+
+
+def test_input_order_is_anchor_then_local():
+    # a W that reads only input row D+1 must pick retained column 1
+    H_kv, d, m, L = 2, 4, 4, 5
+    D = H_kv * d
+    c, _ = make_case(2, H_kv, d, m, L, seed=9)
+    W = np.zeros((D + m, D - m)); W[D + 1, 0] = 1.0; W[2, 1] = 1.0
+    C = orc.reconstruct(c["K_a"], c["K_r"], W)
+    assert np.array_equal(C[:, m + 0], c["K_r"][:, 1])
+    assert np.array_equal(C[:, m + 1], c["K_a"][:, 2])
+    assert np.array_equal(orc.predictor_input(c["K_a"], c["K_r"])[:, :D], c["K_a"])
+
+
+# ---- P3: softmax rows ----------------------------------------------------------
+def test_softmax_rows_sum_to_one_and_lse():
+    c, Q = make_case(4, 2, 8, 8, 50, seed=11, T_q=3)
+    K_t = orc.reconstruct(c["K_a"], c["K_r"], c["W_K"])
+    V_t = orc.reconstruct(c["V_a"], c["V_r"], c["W_V"])
+    o, lse, P = orc.attention_rows(Q, K_t, V_t, 2)
+    np.testing.assert_allclose(P.sum(axis=2), 1.0, rtol=0, atol=1e-12)
+    Kh = K_t.reshape(50, 2, 8)
+    for h in range(4):
+        s = Q[:, h, :] @ Kh[:, h // 2, :].T / math.sqrt(8)
+        np.testing.assert_allclose(np.exp(s - lse[:, h:h + 1]), P[:, h, :],
+                                   rtol=1e-11, atol=1e-14)
+
+
+# ---- P4: brute force == vectorised --------------------------------------------
+@pytest.mark.parametrize("m", [0, 4, 8])
+def test_brute_force_matches_vectorised_decode(m):
+    H_q, H_kv, d, L = 4, 2, 4, 7
+    c, Q = make_case(H_q, H_kv, d, m, L, seed=13 + m)
+    args = (c["K_a"], c["V_a"], c["K_r"], c["V_r"],
+            c["W_K"] if m < 8 else None, c["W_V"] if m < 8 else None, H_kv)
+    o1, l1 = orc.echokv_decode(Q[0], *args)
+    if m == 8:
+        args = args[:4] + (np.zeros((16, 0)), np.zeros((16, 0)), H_kv)
+    o2, l2 = orc.brute_force_decode(Q[0], *args)
+    np.testing.assert_allclose(o1, o2, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(l1, l2, rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("q_pos0", [0, 3])
+def test_brute_force_matches_vectorised_prefill(q_pos0):
+    H_q, H_kv, d, m, T_q = 4, 2, 4, 4, 4
+    L = q_pos0 + T_q
+    c, Q = make_case(H_q, H_kv, d, m, L, seed=17, T_q=T_q)
+    args = (c["K_a"], c["V_a"], c["K_r"], c["V_r"], c["W_K"], c["W_V"], H_kv, q_pos0)
+    o1, l1 = orc.echokv_prefill(Q, *args)
+    o2, l2 = orc.brute_force_prefill(Q, *args)
+    np.testing.assert_allclose(o1, o2, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(l1, l2, rtol=1e-12, atol=1e-13)
+
+
+# ---- P5: re-association through the linear predictor ---------------------------
+def test_reassociation_identity():
+    H_q, H_kv, d, m, L = 6, 3, 8, 8, 33
+    D, G = H_kv * d, 2
+    c, Q = make_case(H_q, H_kv, d, m, L, seed=19)
+    o, lse = orc.echokv_decode(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"],
+                               c["W_K"], c["W_V"], H_kv)
+    XK = np.concatenate([c["K_a"], c["K_r"]], axis=1)
+    XV = np.concatenate([c["V_a"], c["V_r"]], axis=1)
+    for h in range(H_q):
+        g = h // G
+        if g * d < m:      # retained head: plain attention on stored dims
+            s = c["K_r"][:, g * d:(g + 1) * d] @ Q[0, h] / math.sqrt(d)
+            p = np.exp(s - s.max()); p /= p.sum()
+            ref = p @ c["V_r"][:, g * d:(g + 1) * d]
+        else:              # absorbed weights: s = X (W q), o = (p X) W
+            cols = slice(g * d - m, (g + 1) * d - m)
+            s = XK @ (c["W_K"][:, cols] @ Q[0, h]) / math.sqrt(d)
+            p = np.exp(s - s.max()); p /= p.sum()
+            ref = (p @ XV) @ c["W_V"][:, cols]
+        np.testing.assert_allclose(o[h], ref, rtol=1e-11, atol=1e-12)
+
+
+# ---- P6: zero weights ------------------------------------------------------------
+def test_zero_weights_zero_rebuilt_heads():
+    H_q, H_kv, d, m, L = 4, 4, 8, 16, 23
+    c, Q = make_case(H_q, H_kv, d, m, L, seed=23)
+    Z = np.zeros_like(c["W_K"])
+    o, lse = orc.echokv_decode(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"], Z, Z, H_kv)
+    assert np.all(o[2:] == 0.0)                                   # heads 2,3 rebuilt
+    np.testing.assert_allclose(lse[2:], math.log(L), rtol=1e-13)  # uniform softmax
+    ref = sdpa(Q[:, :2], c["K_r"], c["V_r"], 2)[0]
+    np.testing.assert_allclose(o[:2], ref, rtol=1e-12, atol=1e-13)
+
+
+# ---- P7: shift and permutation invariance -----------------------------------------
+def test_token_permutation_invariance():
+    c, Q = make_case(4, 2, 8, 8, 29, seed=29)
+    perm = np.random.default_rng(1).permutation(29)
+    a = orc.echokv_decode(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"],
+                          c["W_K"], c["W_V"], 2)
+    b = orc.echokv_decode(Q[0], c["K_a"][perm], c["V_a"][perm], c["K_r"][perm],
+                          c["V_r"][perm], c["W_K"], c["W_V"], 2)
+    np.testing.assert_allclose(a[0], b[0], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(a[1], b[1], rtol=1e-12, atol=1e-13)
+
+
+def test_score_shift_invariance():
+    # adding c * q/|q|^2 / scale to every key of a head shifts every score by c
+    H_kv, d, L = 1, 8, 17
+    c, Q = make_case(1, H_kv, d, d, L, seed=31)
+    q = Q[0, 0]
+    shift = 2.5
+    K2 = c["K_r"] + (shift * math.sqrt(d)) * q[None, :] / (q @ q)
+    o1, l1 = orc.echokv_decode(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"], None, None, 1)
+    o2, l2 = orc.echokv_decode(Q[0], c["K_a"], c["V_a"], K2, c["V_r"], None, None, 1)
+    np.testing.assert_allclose(o1, o2, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(l2 - l1, shift, rtol=1e-11)
+
+
+# ---- P8: split-K merge ---------------------------------------------------------------
+@pytest.mark.parametrize("cuts", [[0, 40], [0, 1, 40], [0, 13, 14, 31, 40]])
+def test_split_merge_invariance(cuts):
+    H_q, H_kv, d, m, L = 4, 2, 8, 8, 40
+    c, Q = make_case(H_q, H_kv, d, m, L, seed=37)
+    o, lse = orc.echokv_decode(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"],
+                               c["W_K"], c["W_V"], H_kv)
+    ms, ls, os_ = [], [], []
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        sl = slice(a, b)
+        po, plse = orc.echokv_decode(Q[0], c["K_a"][sl], c["V_a"][sl], c["K_r"][sl],
+                                     c["V_r"][sl], c["W_K"], c["W_V"], H_kv)
+        # a partial in (max, sumexp, unnormalised o) form with max := lse, sum := 1
+        ms.append(plse); ls.append(np.ones_like(plse)); os_.append(po)
+    for h in range(H_q):
+        mo, ml = orc.merge_partials([x[h] for x in ms], [x[h] for x in ls],
+                                    np.stack([x[h] for x in os_]))
+        np.testing.assert_allclose(mo, o[h], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(ml, lse[h], rtol=1e-12)
+
+
+def test_merge_partials_closed_form():
+    # two splits with one token each: softmax over two scores, by hand
+    s0, s1 = 0.3, -1.1
+    v0, v1 = np.array([1.0, 2.0]), np.array([-3.0, 0.5])
+    o, lse = orc.merge_partials([s0, s1], [1.0, 1.0], np.stack([v0, v1]))
+    w0 = 1 / (1 + math.exp(s1 - s0))
+    np.testing.assert_allclose(o, w0 * v0 + (1 - w0) * v1, rtol=1e-14)
+    assert abs(lse - math.log(math.exp(s0) + math.exp(s1))) < 1e-14
+
+
+# ---- P9: prefill ----------------------------------------------------------------------
+def test_prefill_rows_equal_decode_on_prefix():
+    H_q, H_kv, d, m, T_q, q_pos0 = 4, 2, 8, 8, 5, 6
+    L = q_pos0 + T_q
+    c, Q = make_case(H_q, H_kv, d, m, L, seed=41, T_q=T_q)
+    o, lse = orc.echokv_prefill(Q, c["K_a"], c["V_a"], c["K_r"], c["V_r"],
+                                c["W_K"], c["W_V"], H_kv, q_pos0)
+    for i in range(T_q):
+        n = q_pos0 + i + 1
+        od, ld = orc.echokv_decode(Q[i], c["K_a"][:n], c["V_a"][:n], c["K_r"][:n],
+                                   c["V_r"][:n], c["W_K"], c["W_V"], H_kv)
+        np.testing.assert_allclose(o[i], od, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(lse[i], ld, rtol=1e-12)
+
+
+def test_prefill_first_query_returns_first_value_and_matches_library():
+    H_q, H_kv, d, m, T_q = 4, 2, 8, 8, 6
+    c, Q = make_case(H_q, H_kv, d, m, T_q, seed=43, T_q=T_q)
+    o, _ = orc.echokv_prefill(Q, c["K_a"], c["V_a"], c["K_r"], c["V_r"],
+                              c["W_K"], c["W_V"], H_kv, 0)
+    V_t = orc.reconstruct(c["V_a"], c["V_r"], c["W_V"]).reshape(T_q, H_kv, d)
+    for h in range(H_q):
+        np.testing.assert_allclose(o[0, h], V_t[0, h // 2], rtol=1e-13, atol=1e-14)
+    K_t = orc.reconstruct(c["K_a"], c["K_r"], c["W_K"])
+    ref = sdpa(Q, K_t, V_t.reshape(T_q, -1), H_kv, causal_from=0)
+    np.testing.assert_allclose(o, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_prefill_rejects_chunk_not_in_cache():
+    c, Q = make_case(2, 2, 4, 4, 5, seed=1, T_q=4)
+    with pytest.raises(ValueError):
+        orc.echokv_prefill(Q, c["K_a"], c["V_a"], c["K_r"], c["V_r"],
+                           c["W_K"], c["W_V"], 2, 3)
+
+
+# ---- P10: grouped-query head map -------------------------------------------------------
+def test_gqa_head_map():
+    H_q, H_kv, d, m, L = 8, 2, 8, 8, 15
+    c, Q = make_case(H_q, H_kv, d, m, L, seed=47)
+    Q[0, 1] = Q[0, 3]          # same group (0)
+    Q[0, 4] = Q[0, 3]          # other group (1)
+    o, _ = orc.echokv_decode(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"],
+                             c["W_K"], c["W_V"], H_kv)
+    assert np.array_equal(o[1], o[3])
+    assert not np.allclose(o[4], o[3])
+    # G = 1 with the KV heads repeated equals the grouped result
+    K_t = orc.reconstruct(c["K_a"], c["K_r"], c["W_K"]).reshape(L, H_kv, d)
+    V_t = orc.reconstruct(c["V_a"], c["V_r"], c["W_V"]).reshape(L, H_kv, d)
+    K_rep = np.repeat(K_t, 4, axis=1).reshape(L, -1)
+    V_rep = np.repeat(V_t, 4, axis=1).reshape(L, -1)
+    o_mha, _, _ = orc.attention_rows(Q, K_rep, V_rep, H_q)
+    np.testing.assert_allclose(o, o_mha[0], rtol=1e-13, atol=1e-14)
+
+
+# ---- cache layout ----------------------------------------------------------------------
+def test_cache_append_keeps_prefix_only():
+    D, m = 8, 3
+    anchor = np.zeros((10, D)); target = np.zeros((10, m))
+    new = np.arange(2 * D, dtype=float).reshape(2, D) + 1
+    n1 = orc.cache_append(anchor, 4, 1, new)
+    n2 = orc.cache_append(target, 4, 1, new)
+    assert n1 == n2 == 3
+    assert np.array_equal(anchor[5:7], new) and np.array_equal(target[5:7], new[:, :m])
+    assert not anchor[:5].any() and not anchor[7:].any() and not target[7:].any()
+
+
+# ---- P12 + generator wiring ------------------------------------------------------------
+def test_synthetic_retained_prefix_is_predictable_from_anchor():
+    from paper_2603_22910_amd import synth
+    w = synth.CONFIGS[0]
+    inp = synth.generate(w)
+    assert inp.K_a.shape == (512, 512) and inp.K_r.shape == (512, 256)
+    assert inp.W_K.shape == (768, 256) and inp.q.shape == (1, 8, 64)
+    assert abs(inp.W_K.double().numpy().std() - 1 / math.sqrt(768)) < 2e-3
+    g2 = synth.generate(w)
+    assert torch.equal(g2.K_r, inp.K_r) and torch.equal(g2.q, inp.q)
+    # retained dims = anchor @ M1 + 0.1 * noise: a least-squares fit from the
+    # anchor (more tokens than dims) leaves a residual of std 0.1*sqrt(1 - D/L)
+    big = synth.generate(w.scaled(seq_lens=(2048,)))
+    A = big.V_a.double().numpy(); R = big.V_r.double().numpy()
+    assert abs(R.var() - 1.01) < 0.05
+    M, *_ = np.linalg.lstsq(A, R, rcond=None)
+    resid = (R - A @ M).std()
+    assert abs(resid - 0.1 * math.sqrt(1 - 512 / 2048)) < 0.01
+
+
+def test_synthetic_ragged_lengths_and_pool_layout():
+    from paper_2603_22910_amd import synth
+    w = synth.CONFIGS[4]
+    lens = synth.draw_lengths(w)
+    assert len(lens) == 32 and min(lens) >= 1024 and max(lens) <= 65536
+    assert lens == synth.draw_lengths(w)
+    small = synth.generate(w.scaled(n_q_heads=4, n_kv_heads=4, head_dim=16, n_retained=32,
+                                    batch=5, len_lo=8, len_hi=600, prefill_len=40,
+                                    prefill_q=24))
+    assert small.n_decode == 5 and len(small.seq_len) == 6 and small.q_pos0 == 16
+    for b in range(6):
+        assert small.seq_start[b] % synth.ROW_ALIGN == 0
+        end = small.seq_start[b] + small.seq_len[b]
+        assert end <= small.seq_start[b] + small.seq_cap[b]
+        assert not small.K_a[end:small.seq_start[b] + small.seq_cap[b]].any()
+    assert small.q_prefill.shape == (24, 4, 16)
+
+
+# ---- mutants: each planted mistake must be caught by a pin above ------------------------
+def _decode_with(recon):
+    def run(q, K_a, V_a, K_r, V_r, W_K, W_V, H_kv):
+        K_t, V_t = recon(K_a, K_r, W_K), recon(V_a, V_r, W_V)
+        o, lse, _ = orc.attention_rows(np.asarray(q)[None], K_t, V_t, H_kv)
+        return o[0], lse[0]
+    return run
+
+
+def _mut_local_first(C_a, C_r, W):        # wrong input order [local ; anchor]
+    X = np.concatenate([C_r, C_a], axis=1)
+    return np.concatenate([C_r, X @ W], axis=1)
+
+
+def _mut_drop_first(C_a, C_r, W):         # wrong output order [drop ; local]
+    X = np.concatenate([C_a, C_r], axis=1)
+    return np.concatenate([X @ W, C_r], axis=1)
+
+
+@pytest.mark.parametrize("mutant", [_mut_local_first, _mut_drop_first])
+def test_mutants_fail_brute_force_pin(mutant):
+    H_q, H_kv, d, m, L = 4, 2, 4, 4, 7
+    c, Q = make_case(H_q, H_kv, d, m, L, seed=53)
+    args = (c["K_a"], c["V_a"], c["K_r"], c["V_r"], c["W_K"], c["W_V"], H_kv)
+    good, _ = orc.brute_force_decode(Q[0], *args)
+    bad, _ = _decode_with(mutant)(Q[0], *args)
+    assert np.abs(good - bad).max() > 1e-3
+
+
+def test_mutant_transposed_weight_fails_selector_pin():
+    H_kv, d, m, L = 2, 4, 4, 5
+    D = H_kv * d
+    c, _ = make_case(2, H_kv, d, m, L, seed=59)
+    W = np.zeros((D + m, D - m)); W[D + 1, 0] = 1.0
+    good = orc.reconstruct(c["K_a"], c["K_r"], W)
+    Wt_like = np.zeros((D + m, D - m)); Wt_like[0, (D + 1) % (D - m)] = 1.0  # indices swapped
+    bad = orc.reconstruct(c["K_a"], c["K_r"], Wt_like)
+    assert not np.array_equal(good, bad)
+    assert np.array_equal(good[:, m], c["K_r"][:, 1])
+
+
+def test_mutant_wrong_head_map_fails_gqa_pin():
+    # interleaved map h % H_kv instead of h // G
+    H_q, H_kv, d, L = 4, 2, 4, 9
+    c, Q = make_case(H_q, H_kv, d, H_kv * d, L, seed=61)
+    o, _ = orc.echokv_decode(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"], None, None, H_kv)
+    ref = sdpa(Q, c["K_r"], c["V_r"], H_kv)[0]
+    Kh = c["K_r"].reshape(L, H_kv, d); Vh = c["V_r"].reshape(L, H_kv, d)
+    wrong = np.zeros_like(o)
+    for h in range(H_q):
+        g = h % H_kv
+        s = Kh[:, g] @ Q[0, h] / math.sqrt(d); p = np.exp(s - s.max()); p /= p.sum()
+        wrong[h] = p @ Vh[:, g]
+    np.testing.assert_allclose(o, ref, rtol=1e-12, atol=1e-13)
+    assert np.abs(wrong - ref).max() > 1e-3
