@@ -1,0 +1,144 @@
+/* echokv.h -- C ABI of libechokv: EchoKV attention over a compressed KV cache
+ * on AMD MI355X (gfx950).
+ *
+ * The method (paper Sec. "Network Architecture"): layers are grouped; the first
+ * layer of a group (the ANCHOR) keeps its full flattened K/V of width
+ * D = H_kv * d (Eq. 1); every other layer of the group (a TARGET) keeps only
+ * the first m flattened dims (Eq. 2) and the dropped dims [m, D) are predicted
+ * per token by a linear map from [anchor row ; retained row] (Eq. 3, Eq. 4).
+ * Attention then runs over [retained ; predicted] reshaped to heads (Eq. 6,
+ * Eq. 7).  The predicted dims are recomputed at every use and never stored.
+ *
+ * Conventions
+ *  - Plain C, no exceptions; every entry point returns an echokv_status.
+ *  - "device" pointers are HIP device memory on the current device; "HOST"
+ *    pointers are ordinary host memory read (or, for seq_len in
+ *    echokv_cache_append, written) during the call only.
+ *  - The library allocates no device memory and frees none.  Cache, weights,
+ *    queries, outputs and workspace are owned by the caller.
+ *  - All argument checks run before the first HIP call and leave every buffer
+ *    and every host array untouched on failure.
+ *  - Work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream);
+ *    results are valid once that stream has been synchronised.  Two calls that
+ *    share a workspace must be ordered on one stream.
+ *  - Flattening is head-major: flattened dim g*d + i is feature i of KV head g.
+ *    Query head h reads KV head h / (H_q / H_kv).
+ *  - Row-major everywhere; a "row" is one token.
+ */
+#ifndef ECHOKV_H
+#define ECHOKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ECHOKV_OK = 0,
+  ECHOKV_ERR_NULL = 1,        /* a required pointer is NULL */
+  ECHOKV_ERR_SHAPE = 2,       /* inconsistent or out-of-range sizes */
+  ECHOKV_ERR_DTYPE = 3,       /* unknown dtype code */
+  ECHOKV_ERR_CAPACITY = 4,    /* append past a sequence's reserved rows */
+  ECHOKV_ERR_WORKSPACE = 5,   /* workspace missing or too small */
+  ECHOKV_ERR_UNSUPPORTED = 6, /* legal in the method, not built (e.g. m % d != 0) */
+  ECHOKV_ERR_HIP = 7          /* a HIP runtime call or launch failed */
+} echokv_status;
+
+typedef enum { ECHOKV_BF16 = 0, ECHOKV_F32 = 1 } echokv_dtype;
+
+/* flags for echokv_shape.flags */
+#define ECHOKV_FLAG_UNFUSED 1u /* decode: materialise the predicted dims in the
+                                  workspace, then attend (comparison path) */
+
+/* One (anchor, target) layer pair. */
+typedef struct {
+  int32_t n_q_heads;   /* H_q */
+  int32_t n_kv_heads;  /* H_kv; H_q % H_kv == 0 */
+  int32_t head_dim;    /* d; 64 or 128 */
+  int32_t n_retained;  /* m, flattened dims the target keeps; 0 < m <= D, m % d == 0 */
+  int32_t dtype;       /* echokv_dtype of cache, weights and queries */
+  int32_t out_dtype;   /* echokv_dtype of `out`; accumulation is always fp32 */
+  float softmax_scale; /* <= 0 selects 1/sqrt(d) (Appendix "Analysis of QK-KL
+                          Divergence Loss", softmax(QK^T/sqrt(d))) */
+  uint32_t flags;      /* ECHOKV_FLAG_* */
+} echokv_shape;
+
+/* One layer's K and V cache: a token-major pool shared by `batch` sequences.
+ * Sequence b owns rows [seq_start[b], seq_start[b] + seq_cap[b]) of which the
+ * first seq_len[b] are valid.  width == D for an anchor layer (Eq. 1) and
+ * width == m for a target layer (Eq. 2). */
+typedef struct {
+  void *k;                  /* device [pool_tokens, width] */
+  void *v;                  /* device [pool_tokens, width] */
+  int32_t width;
+  int32_t batch;
+  int64_t pool_tokens;
+  const int64_t *seq_start; /* HOST [batch] */
+  int32_t *seq_len;         /* HOST [batch]; echokv_cache_append adds n_new */
+  const int32_t *seq_cap;   /* HOST [batch] */
+} echokv_layer_cache;
+
+/* Text for a status code (static storage, never NULL). */
+const char *echokv_status_string(int status);
+
+/* Write new tokens into one layer's cache (Eq. 1 for an anchor, Eq. 2 for a
+ * target; dropping at write time as in Sec. "Throughput Analysis").
+ *   k_new, v_new : device [sum_b n_new[b], D], full width, rows packed by
+ *                  sequence in batch order; columns [dst->width, D) are read
+ *                  by nobody and stored nowhere.
+ *   n_new        : HOST [batch], tokens to add to each sequence (0 allowed).
+ * On success seq_len[b] += n_new[b].  ERR_CAPACITY if any sequence would pass
+ * seq_cap[b]; nothing is written in that case. */
+int echokv_cache_append(const echokv_shape *shape, echokv_layer_cache *dst,
+                        const void *k_new, const void *v_new,
+                        const int32_t *n_new, void *hip_stream);
+
+/* Rebuild the full-width K and V rows of tokens [tok_begin, tok_end) of
+ * sequence `seq` (Eq. 3 then Eq. 6): out row = [retained m dims ; [anchor row ;
+ * retained row] W].
+ *   w_k, w_v     : device [D + m, D - m] row-major, no bias; may be NULL iff m == D.
+ *   k_out, v_out : device [tok_end - tok_begin, D] in shape->dtype. */
+int echokv_reconstruct(const echokv_shape *shape, const echokv_layer_cache *anchor,
+                       const echokv_layer_cache *target, const void *w_k,
+                       const void *w_v, int32_t seq, int32_t tok_begin,
+                       int32_t tok_end, void *k_out, void *v_out, void *hip_stream);
+
+/* Bytes of workspace that echokv_decode_attn (batch sequences holding
+ * total_tokens cached tokens in all) or echokv_prefill_attn (one sequence with
+ * total_tokens cached tokens, max_q queries) need.  Returns 0 on a bad shape. */
+size_t echokv_workspace_bytes(const echokv_shape *shape, int32_t batch,
+                              int64_t total_tokens, int32_t max_q);
+
+/* Decode step for the target layer (Eq. 7 with one query per sequence):
+ * out[b, h, :] = softmax_j(scale * q[b,h,:] . Kt[b,j,h/G,:]) Vt[b,j,h/G,:]
+ * over the seq_len[b] cached tokens, where Kt/Vt heads below m/d are read
+ * from the target cache and the others are predicted on the fly (Eq. 3, 6).
+ *   q       : device [batch, H_q, d]
+ *   out     : device [batch, H_q, d] in shape->out_dtype
+ *   lse_out : device [batch, H_q] fp32 log-sum-exp of the scaled scores, or NULL
+ * anchor and target must describe the same sequences (equal batch, seq_len).
+ * Every seq_len[b] must be >= 1. */
+int echokv_decode_attn(const echokv_shape *shape, const echokv_layer_cache *anchor,
+                       const echokv_layer_cache *target, const void *w_k,
+                       const void *w_v, const void *q, void *out, float *lse_out,
+                       void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Causal chunk of T_q queries of sequence `seq` (Eq. 7 with a causal mask):
+ * query i sits at position q_pos0 + i and attends cached tokens
+ * 0 .. q_pos0 + i inclusive, all read from the compressed cache (predicted
+ * where dropped).  Requires seq_len[seq] >= q_pos0 + T_q: the chunk's own K/V
+ * have been appended already.
+ *   q   : device [T_q, H_q, d];  out : device [T_q, H_q, d];
+ *   lse_out : device [T_q, H_q] fp32 or NULL. */
+int echokv_prefill_attn(const echokv_shape *shape, const echokv_layer_cache *anchor,
+                        const echokv_layer_cache *target, const void *w_k,
+                        const void *w_v, int32_t seq, const void *q, int32_t T_q,
+                        int32_t q_pos0, void *out, float *lse_out, void *workspace,
+                        size_t workspace_bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ECHOKV_H */

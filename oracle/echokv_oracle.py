@@ -158,6 +158,25 @@ def echokv_decode(q, K_a, V_a, K_r, V_r, W_K, W_V, n_kv_heads: int,
     return o[0], lse[0]
 
 
+def echokv_decode_head(q_h, K_a, V_a, K_r, V_r, W_K, W_V, g: int, d: int,
+                       scale: Optional[float] = None):
+    """One query head against KV head g only (for spot checks at sizes where the
+    whole layer is too slow): the head's d columns of K_tilde / V_tilde are the
+    stored ones if g*d < m, else columns [g*d - m, g*d - m + d) of the predictor
+    output (Eq. 3, Eq. 6); then Eq. 7 for that head.  Returns (out [d], lse)."""
+    m = K_r.shape[1]
+    lo = g * d
+    if lo < m:
+        K_g = np.asarray(K_r, F64)[:, lo:lo + d]
+        V_g = np.asarray(V_r, F64)[:, lo:lo + d]
+    else:
+        cols = slice(lo - m, lo - m + d)
+        K_g = predictor_input(K_a, K_r) @ np.asarray(W_K, F64)[:, cols]
+        V_g = predictor_input(V_a, V_r) @ np.asarray(W_V, F64)[:, cols]
+    o, lse, _ = attention_rows(np.asarray(q_h, F64)[None, None, :], K_g, V_g, 1, scale)
+    return o[0, 0], lse[0, 0]
+
+
 def echokv_prefill(Q, K_a, V_a, K_r, V_r, W_K, W_V, n_kv_heads: int, q_pos0: int,
                    scale: Optional[float] = None):
     """Causal chunk: query i sits at position q_pos0 + i and attends cached

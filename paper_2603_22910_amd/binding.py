@@ -1,0 +1,185 @@
+"""ctypes binding over libechokv.so: argument marshalling only.
+
+Function names mirror the C ABI in include/echokv.h.  Tensors are torch tensors
+used as device buffers; `stream` defaults to torch's current HIP stream.  There
+is no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_LIB = None
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libechokv.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_CAPACITY, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = range(8)
+BF16, F32 = 0, 1
+FLAG_UNFUSED = 1
+
+EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
+           "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn")
+
+
+class EchoKVError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: status {code} ({status_string(code)})")
+
+
+class Shape(C.Structure):
+    _fields_ = [("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("n_retained", C.c_int32), ("dtype", C.c_int32), ("out_dtype", C.c_int32),
+                ("softmax_scale", C.c_float), ("flags", C.c_uint32)]
+
+
+class LayerCacheC(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("width", C.c_int32), ("batch", C.c_int32),
+                ("pool_tokens", C.c_int64), ("seq_start", C.POINTER(C.c_int64)),
+                ("seq_len", C.POINTER(C.c_int32)), ("seq_cap", C.POINTER(C.c_int32))]
+
+
+def load() -> C.CDLL:
+    """Load libechokv.so (built in-tree by build.build_library)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not found: build it with "
+                           "`python -m paper_2603_22910_amd.build` (needs hipcc); "
+                           "there is no CPU fallback")
+    lib = C.CDLL(LIB_PATH)
+    lib.echokv_status_string.restype = C.c_char_p
+    lib.echokv_status_string.argtypes = [C.c_int]
+    lib.echokv_workspace_bytes.restype = C.c_size_t
+    lib.echokv_workspace_bytes.argtypes = [C.POINTER(Shape), C.c_int32, C.c_int64, C.c_int32]
+    lib.echokv_cache_append.restype = C.c_int
+    lib.echokv_cache_append.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC), C.c_void_p,
+                                        C.c_void_p, C.POINTER(C.c_int32), C.c_void_p]
+    lib.echokv_reconstruct.restype = C.c_int
+    lib.echokv_reconstruct.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
+                                       C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_int32,
+                                       C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.echokv_decode_attn.restype = C.c_int
+    lib.echokv_decode_attn.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
+                                       C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.echokv_prefill_attn.restype = C.c_int
+    lib.echokv_prefill_attn.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
+                                        C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_int32,
+                                        C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_size_t, C.c_void_p]
+    _LIB = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load().echokv_status_string(int(code)).decode()
+
+
+def make_shape(n_q_heads: int, n_kv_heads: int, head_dim: int, n_retained: int, dtype: str,
+               out_dtype: Optional[str] = None, softmax_scale: float = 0.0,
+               flags: int = 0) -> Shape:
+    code = {"bf16": BF16, "f32": F32}
+    return Shape(n_q_heads, n_kv_heads, head_dim, n_retained, code[dtype],
+                 code[out_dtype or dtype], float(softmax_scale), int(flags))
+
+
+class LayerCache:
+    """One layer's K/V pool plus the host-side sequence table.
+
+    k, v: torch tensors [pool_tokens, width] on the GPU (or None when width == 0).
+    The sequence arrays live in NumPy so the C side can read and update them.
+    """
+
+    def __init__(self, k, v, width: int, pool_tokens: int, seq_start: Sequence[int],
+                 seq_len: Sequence[int], seq_cap: Sequence[int]):
+        self.k, self.v = k, v
+        self.width = int(width)
+        self.pool_tokens = int(pool_tokens)
+        self.seq_start = np.ascontiguousarray(seq_start, dtype=np.int64)
+        self.seq_len = np.ascontiguousarray(seq_len, dtype=np.int32)
+        self.seq_cap = np.ascontiguousarray(seq_cap, dtype=np.int32)
+
+    @property
+    def batch(self) -> int:
+        return int(self.seq_start.shape[0])
+
+    def view(self, first: int, count: int) -> "LayerCache":
+        """The same pool restricted to sequences [first, first+count) (shares the arrays)."""
+        c = LayerCache.__new__(LayerCache)
+        c.k, c.v, c.width, c.pool_tokens = self.k, self.v, self.width, self.pool_tokens
+        c.seq_start = self.seq_start[first:first + count]
+        c.seq_len = self.seq_len[first:first + count]
+        c.seq_cap = self.seq_cap[first:first + count]
+        return c
+
+    def as_c(self) -> LayerCacheC:
+        return LayerCacheC(
+            _ptr(self.k), _ptr(self.v), self.width, self.batch, self.pool_tokens,
+            self.seq_start.ctypes.data_as(C.POINTER(C.c_int64)),
+            self.seq_len.ctypes.data_as(C.POINTER(C.c_int32)),
+            self.seq_cap.ctypes.data_as(C.POINTER(C.c_int32)))
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return int(t.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+def _check(rc: int, where: str):
+    if rc != OK:
+        raise EchoKVError(rc, where)
+
+
+def workspace_bytes(shape: Shape, batch: int, total_tokens: int, max_q: int = 1) -> int:
+    return int(load().echokv_workspace_bytes(C.byref(shape), batch, total_tokens, max_q))
+
+
+def cache_append(shape: Shape, dst: LayerCache, k_new, v_new, n_new: Sequence[int], stream=None):
+    n = np.ascontiguousarray(n_new, dtype=np.int32)
+    c = dst.as_c()
+    _check(load().echokv_cache_append(C.byref(shape), C.byref(c), _ptr(k_new), _ptr(v_new),
+                                      n.ctypes.data_as(C.POINTER(C.c_int32)), _stream(stream)),
+           "echokv_cache_append")
+
+
+def reconstruct(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, seq: int,
+                tok_begin: int, tok_end: int, k_out, v_out, stream=None):
+    a, t = anchor.as_c(), target.as_c()
+    _check(load().echokv_reconstruct(C.byref(shape), C.byref(a), C.byref(t), _ptr(w_k), _ptr(w_v),
+                                     seq, tok_begin, tok_end, _ptr(k_out), _ptr(v_out),
+                                     _stream(stream)), "echokv_reconstruct")
+
+
+def decode_attn(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, q, out,
+                lse_out, workspace, stream=None):
+    a, t = anchor.as_c(), target.as_c()
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().echokv_decode_attn(C.byref(shape), C.byref(a), C.byref(t), _ptr(w_k), _ptr(w_v),
+                                     _ptr(q), _ptr(out), _ptr(lse_out), _ptr(workspace), nbytes,
+                                     _stream(stream)), "echokv_decode_attn")
+
+
+def prefill_attn(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, seq: int, q,
+                 T_q: int, q_pos0: int, out, lse_out, workspace, stream=None):
+    a, t = anchor.as_c(), target.as_c()
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().echokv_prefill_attn(C.byref(shape), C.byref(a), C.byref(t), _ptr(w_k), _ptr(w_v),
+                                      seq, _ptr(q), T_q, q_pos0, _ptr(out), _ptr(lse_out),
+                                      _ptr(workspace), nbytes, _stream(stream)),
+           "echokv_prefill_attn")

@@ -1,0 +1,492 @@
+// libechokv: C-ABI entry points.  Host side only validates, plans and launches;
+// every step of the path runs in the HIP kernels included below.
+#include "../../include/echokv.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "common.h"
+#include "stream_kernels.h"
+#include "fused_decode.h"
+#include "prefill_kernels.h"
+
+using namespace echokv;
+
+namespace {
+
+struct Dims {
+  int H_q, H_kv, d, D, m, d_in, d_out, G, es, oes;
+  bool bf16, out_bf16;
+  float scale;
+};
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+int check_shape(const echokv_shape* s, Dims* o) {
+  if (!s) return ECHOKV_ERR_NULL;
+  if (s->dtype != ECHOKV_BF16 && s->dtype != ECHOKV_F32) return ECHOKV_ERR_DTYPE;
+  if (s->out_dtype != ECHOKV_BF16 && s->out_dtype != ECHOKV_F32) return ECHOKV_ERR_DTYPE;
+  if (s->n_q_heads <= 0 || s->n_kv_heads <= 0 || s->head_dim <= 0) return ECHOKV_ERR_SHAPE;
+  if (s->n_q_heads % s->n_kv_heads) return ECHOKV_ERR_SHAPE;
+  if (s->n_kv_heads > 4096 || s->n_q_heads > 65536) return ECHOKV_ERR_SHAPE;
+  const int64_t D = (int64_t)s->n_kv_heads * s->head_dim;
+  if (s->n_retained < 0 || s->n_retained > D) return ECHOKV_ERR_SHAPE;
+  if (s->head_dim != 64 && s->head_dim != 128) return ECHOKV_ERR_UNSUPPORTED;
+  if (s->n_retained % s->head_dim) return ECHOKV_ERR_UNSUPPORTED;
+  if (!std::isfinite(s->softmax_scale)) return ECHOKV_ERR_SHAPE;
+  o->H_q = s->n_q_heads; o->H_kv = s->n_kv_heads; o->d = s->head_dim;
+  o->D = (int)D; o->m = s->n_retained; o->d_in = o->D + o->m; o->d_out = o->D - o->m;
+  o->G = o->H_q / o->H_kv;
+  o->bf16 = s->dtype == ECHOKV_BF16; o->out_bf16 = s->out_dtype == ECHOKV_BF16;
+  o->es = o->bf16 ? 2 : 4; o->oes = o->out_bf16 ? 2 : 4;
+  o->scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / std::sqrt((float)o->d);
+  return ECHOKV_OK;
+}
+
+int check_cache(const echokv_layer_cache* c, int width) {
+  if (!c) return ECHOKV_ERR_NULL;
+  if (c->width != width) return ECHOKV_ERR_SHAPE;
+  if (c->batch <= 0 || c->pool_tokens <= 0) return ECHOKV_ERR_SHAPE;
+  if (!c->seq_start || !c->seq_len || !c->seq_cap) return ECHOKV_ERR_NULL;
+  if (width > 0 && (!c->k || !c->v)) return ECHOKV_ERR_NULL;
+  for (int b = 0; b < c->batch; ++b) {
+    if (c->seq_start[b] < 0 || c->seq_len[b] < 0 || c->seq_cap[b] < c->seq_len[b])
+      return ECHOKV_ERR_SHAPE;
+    if (c->seq_start[b] + (int64_t)c->seq_cap[b] > c->pool_tokens) return ECHOKV_ERR_SHAPE;
+  }
+  return ECHOKV_OK;
+}
+
+int check_pair(const Dims& dm, const echokv_layer_cache* a, const echokv_layer_cache* t) {
+  int rc = check_cache(a, dm.D);
+  if (rc) return rc;
+  rc = check_cache(t, dm.m);
+  if (rc) return rc;
+  if (a->batch != t->batch) return ECHOKV_ERR_SHAPE;
+  for (int b = 0; b < a->batch; ++b)
+    if (a->seq_len[b] != t->seq_len[b]) return ECHOKV_ERR_SHAPE;
+  return ECHOKV_OK;
+}
+
+inline int slots_for(int64_t tokens) { return (int)((tokens + kSlotTokens - 1) / kSlotTokens); }
+
+// Workspace plan: [partial o][partial (max,sum)][K_hat][V_hat]
+struct WsPlan {
+  size_t off_po, off_pml, off_kh, off_vh, total;
+};
+WsPlan plan_ws(const Dims& dm, int64_t part_slots, int64_t recon_rows) {
+  WsPlan p;
+  size_t o = 0;
+  p.off_po = o;  o += align_up((size_t)part_slots * dm.H_q * dm.d * 4);
+  p.off_pml = o; o += align_up((size_t)part_slots * dm.H_q * 2 * 4);
+  p.off_kh = o;  o += align_up((size_t)recon_rows * dm.d_out * dm.es);
+  p.off_vh = o;  o += align_up((size_t)recon_rows * dm.d_out * dm.es);
+  p.total = o;
+  return p;
+}
+
+constexpr int kPrefillQChunk = kMaxSeqPerLaunch;   // queries per launch, streaming prefill
+
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) return ECHOKV_ERR_HIP; } while (0)
+#define LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return ECHOKV_ERR_HIP; } while (0)
+
+// Fill tbase for a tile size; returns the tile count.
+int fill_tiles(SeqMeta& mt, int tile_tokens) {
+  int acc = 0;
+  for (int b = 0; b < mt.n; ++b) { mt.tbase[b] = acc; acc += (mt.len[b] + tile_tokens - 1) / tile_tokens; }
+  mt.tbase[mt.n] = acc;
+  return acc;
+}
+int fill_slots(SeqMeta& mt) {
+  int acc = 0;
+  for (int b = 0; b < mt.n; ++b) { mt.sbase[b] = acc; acc += slots_for(mt.len[b]); }
+  mt.sbase[mt.n] = acc;
+  return acc;
+}
+
+template <typename T>
+int launch_attn_split(const Dims& dm, AttnArgs<T> a, SeqMeta& mt, int n_kv_heads, hipStream_t st) {
+  const int tiles = fill_tiles(mt, a.split_tokens);
+  const int GT = (dm.G % 4 == 0) ? 4 : (dm.G % 2 == 0) ? 2 : 1;
+  dim3 grid(tiles, n_kv_heads * (dm.G / GT));
+  constexpr int LPR64 = 64 * (int)sizeof(T) / 16, LPR128 = 128 * (int)sizeof(T) / 16;
+#define ATTN_CASE(LPR_, GT_) \
+  hipLaunchKernelGGL((attn_split_kernel<T, LPR_, GT_>), grid, dim3(256), 0, st, a, mt)
+  if (dm.d == 64) {
+    if (GT == 4) ATTN_CASE(LPR64, 4); else if (GT == 2) ATTN_CASE(LPR64, 2); else ATTN_CASE(LPR64, 1);
+  } else {
+    if (GT == 4) ATTN_CASE(LPR128, 4); else if (GT == 2) ATTN_CASE(LPR128, 2); else ATTN_CASE(LPR128, 1);
+  }
+#undef ATTN_CASE
+  LAUNCH_CHECK();
+  return ECHOKV_OK;
+}
+
+template <typename T>
+int launch_recon_fma(const Dims& dm, GemmArgs<T> g, SeqMeta& mt, hipStream_t st) {
+  const int tiles = fill_tiles(mt, 64);
+  dim3 grid(tiles, (dm.d_out + 63) / 64, 2);
+  hipLaunchKernelGGL((recon_fma_kernel<T>), grid, dim3(256), 0, st, g, mt);
+  LAUNCH_CHECK();
+  return ECHOKV_OK;
+}
+
+int pick_split_tokens(int64_t total_tokens, int n_heads_blocks) {
+  // enough chunks to fill 256 CUs a few times over, but few partials
+  int st = 2048;
+  while (st > kSlotTokens && (total_tokens / st) * n_heads_blocks < 2048) st >>= 1;
+  return st;
+}
+
+template <typename T, typename TO>
+int merge_launch(const Dims& dm, const float* po, const float* pml, void* out, float* lse,
+                 int64_t out_seq0, int n_stream, int stream_step, int fused_step,
+                 SeqMeta& mt, hipStream_t st) {
+  MergeArgs<TO> ma;
+  ma.part_o = po; ma.part_ml = pml; ma.out = (TO*)out; ma.lse = lse;
+  ma.H_q = dm.H_q; ma.G = dm.G; ma.d = dm.d;
+  ma.n_stream_kv_heads = n_stream; ma.stream_step = stream_step; ma.fused_step = fused_step;
+  ma.out_seq0 = out_seq0;
+  hipLaunchKernelGGL((merge_kernel<TO>), dim3(dm.H_q, mt.n), dim3(256), 0, st, ma, mt);
+  LAUNCH_CHECK();
+  return ECHOKV_OK;
+}
+
+template <typename T>
+int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
+                const echokv_layer_cache* tg, const void* w_k, const void* w_v, const void* q,
+                void* out, float* lse, char* ws, hipStream_t st) {
+  const int n_ret_heads = dm.m / dm.d, n_rec_heads = dm.H_kv - n_ret_heads;
+  const bool fused = !(flags & ECHOKV_FLAG_UNFUSED) && fused_decode_supported<T>(dm.d, dm.G);
+  for (int b0 = 0; b0 < an->batch; b0 += kMaxSeqPerLaunch) {
+    SeqMeta mt;
+    mt.n = std::min(kMaxSeqPerLaunch, an->batch - b0);
+    int64_t tokens = 0;
+    for (int b = 0; b < mt.n; ++b) {
+      mt.start[b] = an->seq_start[b0 + b]; mt.len[b] = an->seq_len[b0 + b]; tokens += mt.len[b];
+    }
+    const int slots = fill_slots(mt);
+    const WsPlan wp = plan_ws(dm, slots, fused ? 0 : (int64_t)slots * kSlotTokens);
+    float* po = (float*)(ws + wp.off_po);
+    float* pml = (float*)(ws + wp.off_pml);
+    const T* qq = (const T*)q + (int64_t)b0 * dm.H_q * dm.d;
+    int stream_step = 1, fused_step = 1;
+
+    if (n_ret_heads > 0) {
+      AttnArgs<T> a;
+      a.k = (const T*)tg->k; a.v = (const T*)tg->v; a.ld = dm.m; a.col0 = 0; a.head0 = 0;
+      a.row_mode = 0; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
+      a.split_tokens = pick_split_tokens(tokens, n_ret_heads);
+      a.part_o = po; a.part_ml = pml;
+      stream_step = a.split_tokens / kSlotTokens;
+      int rc = launch_attn_split<T>(dm, a, mt, n_ret_heads, st);
+      if (rc) return rc;
+    }
+    if (n_rec_heads > 0) {
+      if (fused) {
+        int rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.scale,
+                                        (const T*)an->k, (const T*)an->v, (const T*)tg->k,
+                                        (const T*)tg->v, (const T*)w_k, (const T*)w_v, qq, po,
+                                        pml, mt, &fused_step, st);
+        if (rc) return rc;
+      } else {
+        GemmArgs<T> g;
+        g.xa[0] = (const T*)an->k; g.xa[1] = (const T*)an->v;
+        g.xr[0] = (const T*)tg->k; g.xr[1] = (const T*)tg->v;
+        g.w[0] = (const T*)w_k; g.w[1] = (const T*)w_v;
+        g.out[0] = (T*)(ws + wp.off_kh); g.out[1] = (T*)(ws + wp.off_vh);
+        g.D = dm.D; g.m = dm.m; g.d_out = dm.d_out; g.ldo = dm.d_out; g.col0 = 0;
+        g.rows_from_slots = 1;
+        int rc = launch_recon_fma<T>(dm, g, mt, st);
+        if (rc) return rc;
+        AttnArgs<T> a;
+        a.k = g.out[0]; a.v = g.out[1]; a.ld = dm.d_out; a.col0 = 0; a.head0 = n_ret_heads;
+        a.row_mode = 1; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
+        a.split_tokens = pick_split_tokens(tokens, n_rec_heads);
+        a.part_o = po; a.part_ml = pml;
+        fused_step = a.split_tokens / kSlotTokens;
+        rc = launch_attn_split<T>(dm, a, mt, n_rec_heads, st);
+        if (rc) return rc;
+      }
+    }
+    int rc = dm.out_bf16
+        ? merge_launch<T, bf16_t>(dm, po, pml, out, lse, b0, n_ret_heads, stream_step, fused_step, mt, st)
+        : merge_launch<T, float>(dm, po, pml, out, lse, b0, n_ret_heads, stream_step, fused_step, mt, st);
+    if (rc) return rc;
+  }
+  return ECHOKV_OK;
+}
+
+template <typename T>
+int reconstruct_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_layer_cache* tg,
+                     const void* w_k, const void* w_v, int seq, int tok_begin, int tok_end,
+                     void* k_out, void* v_out, hipStream_t st) {
+  const int64_t rows = tok_end - tok_begin;
+  const int64_t row0 = an->seq_start[seq] + tok_begin;
+  if (dm.m > 0) {
+    Copy2dArgs c;
+    c.src[0] = (const char*)tg->k + row0 * dm.m * dm.es;
+    c.src[1] = (const char*)tg->v + row0 * dm.m * dm.es;
+    c.dst[0] = (char*)k_out; c.dst[1] = (char*)v_out;
+    c.src_row_bytes = (int64_t)dm.m * dm.es; c.dst_row_bytes = (int64_t)dm.D * dm.es;
+    c.copy_bytes = (int64_t)dm.m * dm.es; c.rows = rows;
+    hipLaunchKernelGGL(copy2d_kernel, dim3((unsigned)std::min<int64_t>(rows, 8192), 2), dim3(256), 0, st, c);
+    LAUNCH_CHECK();
+  }
+  if (dm.d_out > 0) {
+    SeqMeta mt;
+    mt.n = 1; mt.start[0] = row0; mt.len[0] = (int)rows; mt.sbase[0] = 0; mt.sbase[1] = slots_for(rows);
+    if (recon_mfma_supported<T>()) {
+      return launch_recon_mfma<T>(dm.D, dm.m, (const T*)an->k, (const T*)an->v, (const T*)tg->k,
+                                  (const T*)tg->v, (const T*)w_k, (const T*)w_v, (T*)k_out,
+                                  (T*)v_out, dm.D, dm.m, mt, st);
+    }
+    GemmArgs<T> g;
+    g.xa[0] = (const T*)an->k; g.xa[1] = (const T*)an->v;
+    g.xr[0] = (const T*)tg->k; g.xr[1] = (const T*)tg->v;
+    g.w[0] = (const T*)w_k; g.w[1] = (const T*)w_v;
+    g.out[0] = (T*)k_out; g.out[1] = (T*)v_out;
+    g.D = dm.D; g.m = dm.m; g.d_out = dm.d_out; g.ldo = dm.D; g.col0 = dm.m; g.rows_from_slots = 0;
+    return launch_recon_fma<T>(dm, g, mt, st);
+  }
+  return ECHOKV_OK;
+}
+
+// Prefill: predicted dims of the whole visible context are rebuilt once into
+// the workspace (every query tile reuses them), then causal attention runs
+// over retained heads (from the cache) and predicted heads (from the workspace).
+template <typename T>
+int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_layer_cache* tg,
+                 const void* w_k, const void* w_v, int seq, const void* q, int T_q, int q_pos0,
+                 void* out, float* lse, char* ws, hipStream_t st) {
+  const int n_ret_heads = dm.m / dm.d, n_rec_heads = dm.H_kv - n_ret_heads;
+  const int Ltot = q_pos0 + T_q;
+  const int64_t row0 = an->seq_start[seq];
+  const int qchunk = std::min(T_q, kPrefillQChunk);
+  const WsPlan wp = plan_ws(dm, (int64_t)qchunk * slots_for(Ltot),
+                            n_rec_heads ? (int64_t)slots_for(Ltot) * kSlotTokens : 0);
+  float* po = (float*)(ws + wp.off_po);
+  float* pml = (float*)(ws + wp.off_pml);
+  T* kh = (T*)(ws + wp.off_kh);
+  T* vh = (T*)(ws + wp.off_vh);
+  if (n_rec_heads > 0) {
+    SeqMeta mt;
+    mt.n = 1; mt.start[0] = row0; mt.len[0] = Ltot; mt.sbase[0] = 0; mt.sbase[1] = slots_for(Ltot);
+    if (recon_mfma_supported<T>()) {
+      int rc = launch_recon_mfma<T>(dm.D, dm.m, (const T*)an->k, (const T*)an->v, (const T*)tg->k,
+                                    (const T*)tg->v, (const T*)w_k, (const T*)w_v, kh, vh,
+                                    dm.d_out, 0, mt, st);
+      if (rc) return rc;
+    } else {
+      GemmArgs<T> g;
+      g.xa[0] = (const T*)an->k; g.xa[1] = (const T*)an->v;
+      g.xr[0] = (const T*)tg->k; g.xr[1] = (const T*)tg->v;
+      g.w[0] = (const T*)w_k; g.w[1] = (const T*)w_v;
+      g.out[0] = kh; g.out[1] = vh;
+      g.D = dm.D; g.m = dm.m; g.d_out = dm.d_out; g.ldo = dm.d_out; g.col0 = 0; g.rows_from_slots = 0;
+      int rc = launch_recon_fma<T>(dm, g, mt, st);
+      if (rc) return rc;
+    }
+  }
+  if (prefill_mfma_supported<T>(dm.d)) {
+    return launch_prefill_mfma<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.scale, dm.out_bf16,
+                                  (const T*)tg->k + row0 * dm.m, (const T*)tg->v + row0 * dm.m,
+                                  kh, vh, (const T*)q, T_q, q_pos0, out, lse, st);
+  }
+  // streaming path: each query is a virtual sequence of length q_pos0 + i + 1
+  for (int i0 = 0; i0 < T_q; i0 += kPrefillQChunk) {
+    SeqMeta mt;
+    mt.n = std::min(kPrefillQChunk, T_q - i0);
+    int64_t tokens = 0;
+    for (int i = 0; i < mt.n; ++i) { mt.start[i] = row0; mt.len[i] = q_pos0 + i0 + i + 1; tokens += mt.len[i]; }
+    fill_slots(mt);
+    const T* qq = (const T*)q + (int64_t)i0 * dm.H_q * dm.d;
+    int stream_step = 1, fused_step = 1;
+    if (n_ret_heads > 0) {
+      AttnArgs<T> a;
+      a.k = (const T*)tg->k; a.v = (const T*)tg->v; a.ld = dm.m; a.col0 = 0; a.head0 = 0;
+      a.row_mode = 0; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
+      a.split_tokens = pick_split_tokens(tokens, n_ret_heads);
+      a.part_o = po; a.part_ml = pml;
+      stream_step = a.split_tokens / kSlotTokens;
+      int rc = launch_attn_split<T>(dm, a, mt, n_ret_heads, st);
+      if (rc) return rc;
+    }
+    if (n_rec_heads > 0) {
+      AttnArgs<T> a;
+      a.k = kh; a.v = vh; a.ld = dm.d_out; a.col0 = 0; a.head0 = n_ret_heads;
+      a.row_mode = 2; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
+      a.split_tokens = pick_split_tokens(tokens, n_rec_heads);
+      a.part_o = po; a.part_ml = pml;
+      fused_step = a.split_tokens / kSlotTokens;
+      int rc = launch_attn_split<T>(dm, a, mt, n_rec_heads, st);
+      if (rc) return rc;
+    }
+    int rc = dm.out_bf16
+        ? merge_launch<T, bf16_t>(dm, po, pml, out, lse, i0, n_ret_heads, stream_step, fused_step, mt, st)
+        : merge_launch<T, float>(dm, po, pml, out, lse, i0, n_ret_heads, stream_step, fused_step, mt, st);
+    if (rc) return rc;
+  }
+  return ECHOKV_OK;
+}
+
+size_t decode_ws_bytes(const Dims& dm, int batch, int64_t total_tokens, bool unfused) {
+  const int64_t slots = total_tokens / kSlotTokens + batch;
+  return plan_ws(dm, slots, unfused ? slots * kSlotTokens : 0).total;
+}
+size_t prefill_ws_bytes(const Dims& dm, int64_t Ltot, int max_q) {
+  const int qchunk = std::min(max_q, kPrefillQChunk);
+  return plan_ws(dm, (int64_t)qchunk * slots_for(Ltot), (int64_t)slots_for(Ltot) * kSlotTokens).total;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* echokv_status_string(int status) {
+  switch (status) {
+    case ECHOKV_OK: return "ok";
+    case ECHOKV_ERR_NULL: return "null pointer";
+    case ECHOKV_ERR_SHAPE: return "inconsistent or out-of-range shape";
+    case ECHOKV_ERR_DTYPE: return "unknown dtype";
+    case ECHOKV_ERR_CAPACITY: return "append exceeds reserved rows";
+    case ECHOKV_ERR_WORKSPACE: return "workspace missing or too small";
+    case ECHOKV_ERR_UNSUPPORTED: return "configuration not supported by this build";
+    case ECHOKV_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+size_t echokv_workspace_bytes(const echokv_shape* shape, int32_t batch, int64_t total_tokens,
+                              int32_t max_q) {
+  Dims dm;
+  if (check_shape(shape, &dm) != ECHOKV_OK || batch <= 0 || total_tokens <= 0 || max_q < 0) return 0;
+  size_t need = decode_ws_bytes(dm, batch, total_tokens, true);
+  if (max_q > 1) need = std::max(need, prefill_ws_bytes(dm, total_tokens, max_q));
+  return need;
+}
+
+int echokv_cache_append(const echokv_shape* shape, echokv_layer_cache* dst, const void* k_new,
+                        const void* v_new, const int32_t* n_new, void* hip_stream) {
+  Dims dm;
+  int rc = check_shape(shape, &dm);
+  if (rc) return rc;
+  if (!dst) return ECHOKV_ERR_NULL;
+  if (dst->width != dm.D && dst->width != dm.m) return ECHOKV_ERR_SHAPE;
+  rc = check_cache(dst, dst->width);
+  if (rc) return rc;
+  if (!n_new) return ECHOKV_ERR_NULL;
+  int64_t total = 0;
+  for (int b = 0; b < dst->batch; ++b) {
+    if (n_new[b] < 0) return ECHOKV_ERR_SHAPE;
+    if ((int64_t)dst->seq_len[b] + n_new[b] > dst->seq_cap[b]) return ECHOKV_ERR_CAPACITY;
+    total += n_new[b];
+  }
+  if (total > 0 && (!k_new || !v_new)) return ECHOKV_ERR_NULL;
+  if (total > INT32_MAX) return ECHOKV_ERR_SHAPE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (dst->width > 0) {
+    int64_t done = 0;
+    for (int b0 = 0; b0 < dst->batch; b0 += kMaxSeqPerLaunch) {
+      SeqMeta mt;
+      mt.n = std::min(kMaxSeqPerLaunch, dst->batch - b0);
+      int acc = 0;
+      for (int b = 0; b < mt.n; ++b) {
+        mt.start[b] = dst->seq_start[b0 + b]; mt.len[b] = dst->seq_len[b0 + b];
+        mt.tbase[b] = acc; acc += n_new[b0 + b];
+      }
+      mt.tbase[mt.n] = acc;
+      if (acc > 0) {
+        CopyArgs c;
+        c.src[0] = (const char*)k_new + done * dm.D * dm.es;
+        c.src[1] = (const char*)v_new + done * dm.D * dm.es;
+        c.dst[0] = (char*)dst->k; c.dst[1] = (char*)dst->v;
+        c.src_row_bytes = (int64_t)dm.D * dm.es; c.dst_row_bytes = (int64_t)dst->width * dm.es;
+        c.rows = acc;
+        hipLaunchKernelGGL(append_rows_kernel, dim3(std::min(acc, 16384), 2), dim3(256), 0, st, c, mt);
+        LAUNCH_CHECK();
+      }
+      done += acc;
+    }
+  }
+  for (int b = 0; b < dst->batch; ++b) dst->seq_len[b] += n_new[b];
+  return ECHOKV_OK;
+}
+
+int echokv_reconstruct(const echokv_shape* shape, const echokv_layer_cache* anchor,
+                       const echokv_layer_cache* target, const void* w_k, const void* w_v,
+                       int32_t seq, int32_t tok_begin, int32_t tok_end, void* k_out, void* v_out,
+                       void* hip_stream) {
+  Dims dm;
+  int rc = check_shape(shape, &dm);
+  if (rc) return rc;
+  rc = check_pair(dm, anchor, target);
+  if (rc) return rc;
+  if (seq < 0 || seq >= anchor->batch) return ECHOKV_ERR_SHAPE;
+  if (tok_begin < 0 || tok_end < tok_begin || tok_end > anchor->seq_len[seq]) return ECHOKV_ERR_SHAPE;
+  if (dm.d_out > 0 && (!w_k || !w_v)) return ECHOKV_ERR_NULL;
+  if (!k_out || !v_out) return ECHOKV_ERR_NULL;
+  if (tok_end == tok_begin) return ECHOKV_OK;
+  hipStream_t st = (hipStream_t)hip_stream;
+  return dm.bf16 ? reconstruct_impl<bf16_t>(dm, anchor, target, w_k, w_v, seq, tok_begin, tok_end, k_out, v_out, st)
+                 : reconstruct_impl<float>(dm, anchor, target, w_k, w_v, seq, tok_begin, tok_end, k_out, v_out, st);
+}
+
+int echokv_decode_attn(const echokv_shape* shape, const echokv_layer_cache* anchor,
+                       const echokv_layer_cache* target, const void* w_k, const void* w_v,
+                       const void* q, void* out, float* lse_out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+  Dims dm;
+  int rc = check_shape(shape, &dm);
+  if (rc) return rc;
+  rc = check_pair(dm, anchor, target);
+  if (rc) return rc;
+  if (dm.d_out > 0 && (!w_k || !w_v)) return ECHOKV_ERR_NULL;
+  if (!q || !out) return ECHOKV_ERR_NULL;
+  int64_t max_chunk_slots = 0;
+  for (int b0 = 0; b0 < anchor->batch; b0 += kMaxSeqPerLaunch) {
+    int64_t s = 0;
+    for (int b = b0; b < std::min(anchor->batch, b0 + kMaxSeqPerLaunch); ++b) {
+      if (anchor->seq_len[b] < 1) return ECHOKV_ERR_SHAPE;
+      s += slots_for(anchor->seq_len[b]);
+    }
+    max_chunk_slots = std::max(max_chunk_slots, s);
+  }
+  const bool unfused = (shape->flags & ECHOKV_FLAG_UNFUSED) ||
+                       !(dm.bf16 ? fused_decode_supported<bf16_t>(dm.d, dm.G)
+                                 : fused_decode_supported<float>(dm.d, dm.G));
+  const size_t need = plan_ws(dm, max_chunk_slots, unfused ? max_chunk_slots * kSlotTokens : 0).total;
+  if (!workspace || workspace_bytes < need) return ECHOKV_ERR_WORKSPACE;
+  if ((uintptr_t)workspace % 256) return ECHOKV_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  return dm.bf16 ? decode_impl<bf16_t>(dm, shape->flags, anchor, target, w_k, w_v, q, out, lse_out, (char*)workspace, st)
+                 : decode_impl<float>(dm, shape->flags, anchor, target, w_k, w_v, q, out, lse_out, (char*)workspace, st);
+}
+
+int echokv_prefill_attn(const echokv_shape* shape, const echokv_layer_cache* anchor,
+                        const echokv_layer_cache* target, const void* w_k, const void* w_v,
+                        int32_t seq, const void* q, int32_t T_q, int32_t q_pos0, void* out,
+                        float* lse_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Dims dm;
+  int rc = check_shape(shape, &dm);
+  if (rc) return rc;
+  rc = check_pair(dm, anchor, target);
+  if (rc) return rc;
+  if (seq < 0 || seq >= anchor->batch) return ECHOKV_ERR_SHAPE;
+  if (T_q <= 0 || q_pos0 < 0) return ECHOKV_ERR_SHAPE;
+  if ((int64_t)q_pos0 + T_q > anchor->seq_len[seq]) return ECHOKV_ERR_SHAPE;
+  if (dm.d_out > 0 && (!w_k || !w_v)) return ECHOKV_ERR_NULL;
+  if (!q || !out) return ECHOKV_ERR_NULL;
+  const size_t need = prefill_ws_bytes(dm, (int64_t)q_pos0 + T_q, T_q);
+  if (!workspace || workspace_bytes < need) return ECHOKV_ERR_WORKSPACE;
+  if ((uintptr_t)workspace % 256) return ECHOKV_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  return dm.bf16 ? prefill_impl<bf16_t>(dm, anchor, target, w_k, w_v, seq, q, T_q, q_pos0, out, lse_out, (char*)workspace, st)
+                 : prefill_impl<float>(dm, anchor, target, w_k, w_v, seq, q, T_q, q_pos0, out, lse_out, (char*)workspace, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,324 @@
+// Bandwidth-bound kernels of the EchoKV path: cache append (strided row copy),
+// split-K streaming decode attention over stored heads, and the split merge.
+// Also a plain FMA-tiled predictor GEMM used by the unfused comparison path
+// and by the fp32 configuration.
+#pragma once
+#include "common.h"
+
+namespace echokv {
+
+// ---------------------------------------------------------------------------
+// Row copy: dst[drow0(r) , 0:width) = src[r, 0:width) in 16-byte pieces.
+// Cache append keeps only the first `width` flattened dims of each new row
+// (Eq. 1 for an anchor layer, Eq. 2 for a target layer).
+// meta.tbase = prefix sum of new rows per sequence; destination row of new row
+// r of sequence b is start[b] + len[b] + (r - tbase[b]) (len = length BEFORE).
+// blockIdx.y selects K (0) or V (1).
+// ---------------------------------------------------------------------------
+struct CopyArgs {
+  const char* src[2];
+  char* dst[2];
+  int64_t src_row_bytes;
+  int64_t dst_row_bytes;   // == bytes copied per row
+  int32_t rows;
+};
+
+__global__ __launch_bounds__(256) void append_rows_kernel(CopyArgs a, SeqMeta meta) {
+  const int which = blockIdx.y;
+  const int pieces = (int)(a.dst_row_bytes >> 4);
+  for (int r = blockIdx.x; r < a.rows; r += gridDim.x) {
+    const int b = find_seq(meta.tbase, meta.n, r);
+    const int64_t drow = meta.start[b] + meta.len[b] + (r - meta.tbase[b]);
+    const uint4* s = reinterpret_cast<const uint4*>(a.src[which] + (int64_t)r * a.src_row_bytes);
+    uint4* d = reinterpret_cast<uint4*>(a.dst[which] + drow * a.dst_row_bytes);
+    for (int i = threadIdx.x; i < pieces; i += blockDim.x) d[i] = s[i];
+  }
+}
+
+// Plain 2-D copy of `rows` rows (used to place the retained dims in front of
+// the predicted ones, Eq. 6).  blockIdx.y selects K or V.
+struct Copy2dArgs {
+  const char* src[2];
+  char* dst[2];
+  int64_t src_row_bytes, dst_row_bytes, copy_bytes;
+  int64_t rows;
+};
+__global__ __launch_bounds__(256) void copy2d_kernel(Copy2dArgs a) {
+  const int which = blockIdx.y;
+  const int pieces = (int)(a.copy_bytes >> 4);
+  for (int64_t r = blockIdx.x; r < a.rows; r += gridDim.x) {
+    const uint4* s = reinterpret_cast<const uint4*>(a.src[which] + r * a.src_row_bytes);
+    uint4* d = reinterpret_cast<uint4*>(a.dst[which] + r * a.dst_row_bytes);
+    for (int i = threadIdx.x; i < pieces; i += blockDim.x) d[i] = s[i];
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Predictor product with ordinary FMAs (Eq. 3): for the tokens of each
+// sequence, out[row, col0 + c] = sum_k X[j,k] W[k,c], X = [anchor row ; retained row].
+// 64x64 output tile, 256 threads, 4x4 outputs each, fp32 accumulation.
+// blockIdx.z selects K (0) or V (1).  Output rows: out_row0[b] + j with
+// out_row0 = sbase[b]*kSlotTokens (workspace) or an explicit single offset.
+// ---------------------------------------------------------------------------
+template <typename T>
+struct GemmArgs {
+  const T* xa[2];   // anchor cache  [pool, D]
+  const T* xr[2];   // retained cache [pool, m]
+  const T* w[2];    // [d_in, d_out]
+  T* out[2];
+  int32_t D, m, d_out;
+  int64_t ldo;      // output row stride (elements)
+  int32_t col0;     // first output column (elements)
+  int32_t rows_from_slots;  // 1: output row = sbase[b]*kSlotTokens + j ; 0: row = j
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void recon_fma_kernel(GemmArgs<T> a, SeqMeta meta) {
+  constexpr int BM = 64, BN = 64, BK = 16;
+  __shared__ float sx[BK][BM + 4];
+  __shared__ float sw[BK][BN + 4];
+  const int which = blockIdx.z;
+  const int b = find_seq(meta.tbase, meta.n, blockIdx.x);
+  const int tile = blockIdx.x - meta.tbase[b];
+  const int L = meta.len[b];
+  const int j0 = tile * BM;
+  const int n0 = blockIdx.y * BN;
+  const int64_t row0 = meta.start[b];
+  const T* xa = a.xa[which];
+  const T* xr = a.xr[which];
+  const T* w = a.w[which];
+  const int d_in = a.D + a.m;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < d_in; k0 += BK) {
+    // X tile: 64 rows x 16 k ; thread loads 4 elements
+    {
+      const int r = threadIdx.x >> 2;          // 0..63
+      const int kk = (threadIdx.x & 3) * 4;    // 0,4,8,12
+      int j = j0 + r; if (j >= L) j = L - 1;
+      const int k = k0 + kk;
+      const T* src = (k < a.D) ? xa + (row0 + j) * (int64_t)a.D + k
+                               : xr + (row0 + j) * (int64_t)a.m + (k - a.D);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) sx[kk + i][r] = Elem<T>::to_f32(src[i]);
+    }
+    // W tile: 16 k x 64 n ; thread loads 4 elements
+    {
+      const int kk = threadIdx.x >> 4;         // 0..15
+      const int nn = (threadIdx.x & 15) * 4;
+      const T* src = w + (int64_t)(k0 + kk) * a.d_out + n0 + nn;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        sw[kk][nn + i] = (n0 + nn + i < a.d_out) ? Elem<T>::to_f32(src[i]) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < BK; ++kk) {
+      float xv[4], wv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { xv[i] = sx[kk][ty * 4 + i]; wv[i] = sw[kk][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn) acc[i][jn] = fmaf(xv[i], wv[jn], acc[i][jn]);
+    }
+    __syncthreads();
+  }
+  const int64_t orow0 = a.rows_from_slots ? (int64_t)meta.sbase[b] * kSlotTokens : 0;
+  T* out = a.out[which];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int j = j0 + ty * 4 + i;
+    if (j >= L) continue;
+#pragma unroll
+    for (int jn = 0; jn < 4; ++jn) {
+      const int c = n0 + tx * 4 + jn;
+      if (c < a.d_out) out[(orow0 + j) * a.ldo + a.col0 + c] = Elem<T>::from_f32(acc[i][jn]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Split-K streaming attention over heads that are stored somewhere as rows
+// (the target layer's retained heads, or materialised predicted heads):
+// scores, online softmax and P.V for GT query heads of one KV head over one
+// chunk of `split_tokens` tokens (Eq. 7).  Writes one partial
+// (max, sum-exp, unnormalised o) per (chunk, query head).
+//   LPR = lanes that share one row = d * sizeof(T) / 16.
+// grid.x = chunks (tbase), grid.y = kv heads handled * (G / GT).
+// ---------------------------------------------------------------------------
+template <typename T>
+struct AttnArgs {
+  const T* k; const T* v;   // row r, head g at k + r*ld + col0 + g_local*d
+  int64_t ld;
+  int32_t col0;             // column of the first head handled
+  int32_t head0;            // its KV head index (for the query / output head)
+  int32_t row_mode;         // 0: row = start[b] + j ; 1: sbase[b]*kSlotTokens + j ; 2: j
+  const T* q;               // [nseq, H_q, d]
+  int32_t H_q, G, d;
+  float scale;
+  int32_t split_tokens;     // multiple of kSlotTokens
+  float* part_o;            // [slots, H_q, d]
+  float* part_ml;           // [slots, H_q, 2]
+};
+
+template <typename T, int LPR, int GT>
+__global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs<T> a, SeqMeta meta) {
+  constexpr int VEC = Elem<T>::kVec;
+  constexpr int RPW = 64 / LPR;        // row groups per wave
+  constexpr int NRG = 4 * RPW;         // row groups per block
+  const int b = find_seq(meta.tbase, meta.n, blockIdx.x);
+  const int chunk = blockIdx.x - meta.tbase[b];
+  const int L = meta.len[b];
+  const int gchunks = a.G / GT;
+  const int hl = blockIdx.y / gchunks;           // local kv head
+  const int qh0 = (a.head0 + hl) * a.G + (blockIdx.y % gchunks) * GT;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rg = wave * RPW + lane / LPR;        // row group in block
+  const int li = lane % LPR;                     // lane within row
+  const int64_t row0 = a.row_mode == 0 ? meta.start[b]
+                     : a.row_mode == 1 ? (int64_t)meta.sbase[b] * kSlotTokens : 0;
+  const int col = a.col0 + hl * a.d + li * VEC;
+  const int jbeg = chunk * a.split_tokens;
+  const int jend = min(L, jbeg + a.split_tokens);
+
+  float qv[GT][VEC];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    load16<T>(a.q + ((int64_t)b * a.H_q + qh0 + g) * a.d + li * VEC, qv[g]);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) qv[g][i] *= a.scale;
+  }
+  float mx[GT], sm[GT], o[GT][VEC];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    mx[g] = -INFINITY; sm[g] = 0.f;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) o[g][i] = 0.f;
+  }
+  constexpr int UN = 4;
+  for (int j = jbeg + rg; j < jend; j += NRG * UN) {
+    float kv[UN][VEC], vv[UN][VEC];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      int jj = j + u * NRG; if (jj >= jend) jj = jend - 1;
+      load16<T>(a.k + (row0 + jj) * a.ld + col, kv[u]);
+      load16<T>(a.v + (row0 + jj) * a.ld + col, vv[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const bool live = (j + u * NRG) < jend;
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) s = fmaf(qv[g][i], kv[u][i], s);
+        s = wave_sum(s, LPR);
+        if (live) {
+          const float mn = fmaxf(mx[g], s);
+          const float corr = __expf(mx[g] - mn);
+          const float p = __expf(s - mn);
+          sm[g] = sm[g] * corr + p;
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) o[g][i] = fmaf(p, vv[u][i], o[g][i] * corr);
+          mx[g] = mn;
+        }
+      }
+    }
+  }
+  // merge the NRG row groups: first inside the wave, then across waves in LDS
+  __shared__ float s_m[4][GT], s_l[4][GT];
+  __shared__ float s_o[4][GT][LPR * VEC];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    float M = mx[g];
+    for (int off = LPR; off < 64; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+    const float w = (mx[g] == -INFINITY) ? 0.f : __expf(mx[g] - M);
+    float l = sm[g] * w;
+    for (int off = LPR; off < 64; off <<= 1) l += __shfl_xor(l, off, 64);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) {
+      float x = o[g][i] * w;
+      for (int off = LPR; off < 64; off <<= 1) x += __shfl_xor(x, off, 64);
+      o[g][i] = x;
+    }
+    if (lane < LPR) {
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) s_o[wave][g][li * VEC + i] = o[g][i];
+    }
+    if (lane == 0) { s_m[wave][g] = M; s_l[wave][g] = l; }
+  }
+  __syncthreads();
+  const int slot = meta.sbase[b] + chunk * (a.split_tokens / kSlotTokens);
+  for (int idx = threadIdx.x; idx < GT * a.d; idx += 256) {
+    const int g = idx / a.d, c = idx % a.d;
+    float M = fmaxf(fmaxf(s_m[0][g], s_m[1][g]), fmaxf(s_m[2][g], s_m[3][g]));
+    float l = 0.f, acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float e = (s_m[w][g] == -INFINITY) ? 0.f : __expf(s_m[w][g] - M);
+      l += s_l[w][g] * e; acc += s_o[w][g][c] * e;
+    }
+    const int64_t ph = (int64_t)slot * a.H_q + qh0 + g;
+    a.part_o[ph * a.d + c] = acc;
+    if (c == 0) { a.part_ml[ph * 2] = M; a.part_ml[ph * 2 + 1] = l; }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Merge of the split partials of one (sequence, query head): exact
+// re-association of the softmax-weighted sum.  Heads below `n_stream_heads`
+// (in KV-head units) were written every `stream_step` slots, the others every
+// `fused_step` slots.  grid = (H_q, nseq), 256 threads.
+// ---------------------------------------------------------------------------
+template <typename TO>
+struct MergeArgs {
+  const float* part_o; const float* part_ml;
+  TO* out; float* lse;      // lse may be null
+  int32_t H_q, G, d;
+  int32_t n_stream_kv_heads, stream_step, fused_step;
+  int64_t out_seq0;         // index of the launch's first sequence in out/lse
+};
+
+template <typename TO>
+__global__ __launch_bounds__(256) void merge_kernel(MergeArgs<TO> a, SeqMeta meta) {
+  const int h = blockIdx.x, b = blockIdx.y;
+  const int nslot = meta.sbase[b + 1] - meta.sbase[b];
+  const int step = (h / a.G < a.n_stream_kv_heads) ? a.stream_step : a.fused_step;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int dpl = a.d >> 6;   // dims per lane: 1 (d=64) or 2 (d=128)
+  float M = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
+  for (int s = wave * step; s < nslot; s += 4 * step) {
+    const int64_t ph = (int64_t)(meta.sbase[b] + s) * a.H_q + h;
+    const float ms = a.part_ml[ph * 2], ls = a.part_ml[ph * 2 + 1];
+    const float x0 = a.part_o[ph * a.d + lane * dpl];
+    const float x1 = (dpl == 2) ? a.part_o[ph * a.d + lane * dpl + 1] : 0.f;
+    const float mn = fmaxf(M, ms);
+    const float c0 = (M == -INFINITY) ? 0.f : __expf(M - mn);
+    const float c1 = (ms == -INFINITY) ? 0.f : __expf(ms - mn);
+    l = l * c0 + ls * c1; o0 = o0 * c0 + x0 * c1; o1 = o1 * c0 + x1 * c1;
+    M = mn;
+  }
+  __shared__ float s_m[4], s_l[4], s_o[4][128];
+  if (lane == 0) { s_m[wave] = M; s_l[wave] = l; }
+  s_o[wave][lane * dpl] = o0;
+  if (dpl == 2) s_o[wave][lane * dpl + 1] = o1;
+  __syncthreads();
+  if (threadIdx.x < a.d) {
+    const int c = threadIdx.x;
+    const float MM = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+    float ll = 0.f, acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float e = (s_m[w] == -INFINITY) ? 0.f : __expf(s_m[w] - MM);
+      ll += s_l[w] * e; acc += s_o[w][c] * e;
+    }
+    const int64_t oh = (a.out_seq0 + b) * a.H_q + h;
+    const float r = acc / ll;
+    if constexpr (sizeof(TO) == 2) a.out[oh * a.d + c] = f32_to_bf16(r);
+    else a.out[oh * a.d + c] = r;
+    if (c == 0 && a.lse) a.lse[oh] = MM + __logf(ll);
+  }
+}
+
+}  // namespace echokv

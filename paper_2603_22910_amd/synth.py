@@ -23,21 +23,24 @@ Recipe (all draws fp32 on the CPU, then rounded ONCE to the storage dtype):
              prefix is correlated with the anchor layer, as the method assumes)
   weights  : W_K, W_V ~ N(0, std 1/sqrt(d_in)), [d_in, d_out] row-major
   queries  : q ~ N(0,1), [B, H_q, d]; prefill chunk q_p ~ N(0,1), [T_q, H_q, d]
-Draw order per tensor is fixed (K_a, V_a, M1_K, E1_K, M1_V, E1_V, W_K, W_V, q,
-q_p), each from its own generator seeded by (seed, tag), in fixed row chunks,
-so a tensor does not change when another one's shape does.
+Every tensor has its own generator seeded by (seed, tag); the row-indexed ones
+(K_a, V_a, E1) are drawn in fixed chunks of _CHUNK_ROWS rows, each chunk from
+its own generator seeded by (seed, tag, chunk index), so a tensor does not
+change when another one's shape does and chunks can be drawn in parallel.
 """
 from __future__ import annotations
 
+import concurrent.futures
 import dataclasses
 import hashlib
 import math
+import os
 from typing import Dict, List, Optional, Sequence
 
 import torch
 
 ROW_ALIGN = 256          # pool rows reserved per sequence are a multiple of this
-_CHUNK_ROWS = 16384      # rows drawn per randn call (part of the recipe)
+_CHUNK_ROWS = 2048       # rows per generator chunk (part of the recipe)
 
 
 @dataclasses.dataclass(frozen=True)
@@ -120,11 +123,26 @@ def _round_up(x: int, a: int) -> int:
     return (x + a - 1) // a * a
 
 
-def _normal_rows(rows: int, cols: int, g: torch.Generator) -> torch.Tensor:
-    out = torch.empty(rows, cols, dtype=torch.float32)
-    for r0 in range(0, rows, _CHUNK_ROWS):
-        r1 = min(rows, r0 + _CHUNK_ROWS)
-        out[r0:r1] = torch.randn(r1 - r0, cols, generator=g, dtype=torch.float32)
+_DRAW_THREADS = 8        # chunks drawn concurrently (does not affect the values)
+
+
+def _draw_rows(r0: int, r1: int, cols: int, seed: int, tag: str) -> torch.Tensor:
+    """Rows [r0, r1) of a [*, cols] N(0,1) tensor whose chunk c (rows
+    c*_CHUNK_ROWS ...) comes from its own generator (seed, tag, c).  r0 must be
+    chunk-aligned.  Chunks are drawn on a few threads."""
+    out = torch.empty(r1 - r0, cols, dtype=torch.float32)
+    jobs = [(c0 // _CHUNK_ROWS, c0, min(r1, c0 + _CHUNK_ROWS)) for c0 in range(r0, r1, _CHUNK_ROWS)]
+
+    def job(j):
+        i, c0, c1 = j
+        torch.randn(c1 - c0, cols, generator=_gen(seed, f"{tag}/{i}"), dtype=torch.float32,
+                    out=out[c0 - r0:c1 - r0])
+
+    if len(jobs) == 1:
+        job(jobs[0])
+    else:
+        with concurrent.futures.ThreadPoolExecutor(min(_DRAW_THREADS, len(jobs))) as ex:
+            list(ex.map(job, jobs))
     return out
 
 
@@ -184,32 +202,27 @@ def generate(w: Workload) -> Inputs:
     td = w.torch_dtype
 
     valid = torch.zeros(pool, 1, dtype=torch.float32)
-    for s, n in zip(starts, lens):
-        valid[s:s + n] = 1.0
+    for s_, n_ in zip(starts, lens):
+        valid[s_:s_ + n_] = 1.0
 
-    def anchor(tag):
-        return _normal_rows(pool, D, _gen(w.seed, tag)) * valid
-
-    def retained(a32, tag):
-        if m == 0:
-            return torch.zeros(pool, 0, dtype=td)
+    def layer_pair(tag):
+        """Anchor rows A ~ N(0,1) and the target's retained prefix A @ M1 + 0.1 E1."""
+        a_out = torch.empty(pool, D, dtype=td)
+        r_out = torch.empty(pool, m, dtype=td)
         M1 = torch.randn(D, m, generator=_gen(w.seed, "M1_" + tag),
-                         dtype=torch.float32) / math.sqrt(D)
-        gE = _gen(w.seed, "E1_" + tag)
-        out = torch.empty(pool, m, dtype=td)
-        for r0 in range(0, pool, _CHUNK_ROWS):
-            r1 = min(pool, r0 + _CHUNK_ROWS)
-            e = torch.randn(r1 - r0, m, generator=gE, dtype=torch.float32)
-            out[r0:r1] = ((a32[r0:r1] @ M1 + 0.1 * e) * valid[r0:r1]).to(td)
-        return out
+                         dtype=torch.float32) / math.sqrt(D) if m else None
+        block = _CHUNK_ROWS * _DRAW_THREADS
+        for r0 in range(0, pool, block):
+            r1 = min(pool, r0 + block)
+            a = _draw_rows(r0, r1, D, w.seed, tag + "_a") * valid[r0:r1]
+            a_out[r0:r1] = a.to(td)
+            if m:
+                e = _draw_rows(r0, r1, m, w.seed, "E1_" + tag)
+                r_out[r0:r1] = ((a @ M1 + 0.1 * e) * valid[r0:r1]).to(td)
+        return a_out, r_out
 
-    a32 = anchor("K_a")
-    K_r = retained(a32, "K")
-    K_a = a32.to(td)
-    a32 = anchor("V_a")
-    V_r = retained(a32, "V")
-    V_a = a32.to(td)
-    del a32
+    K_a, K_r = layer_pair("K")
+    V_a, V_r = layer_pair("V")
 
     d_in, d_out = w.d_in, w.d_out
     def weight(tag):

@@ -1,0 +1,158 @@
+"""C-ABI checks that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2603_22910_amd import binding as ek
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x100000  # non-null stand-in for a device pointer; never dereferenced on these paths
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ek.LIB_PATH):
+        from paper_2603_22910_amd import build
+        build.build_library()
+    return ek.load()
+
+
+def test_exports_match_header(lib):
+    hdr = open(os.path.join(ROOT, "include", "echokv.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(echokv_[a-z_]+)\s*\(", hdr))
+    assert declared == set(ek.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings(lib):
+    seen = {ek.status_string(c) for c in range(8)}
+    assert len(seen) == 8 and ek.status_string(0) == "ok"
+    assert ek.status_string(99) == "unknown status"
+
+
+def caches(D=512, m=256, lens=(100,), caps=None, pool=None):
+    caps = caps or [256] * len(lens)
+    starts = np.cumsum([0] + list(caps[:-1]))
+    pool = pool or int(sum(caps))
+    a = ek.LayerCache(FAKE, FAKE, D, pool, starts, lens, caps)
+    t = ek.LayerCache(FAKE if m else None, FAKE if m else None, m, pool, starts, lens, caps)
+    return a, t
+
+
+def code(fn, *args, **kw):
+    try:
+        fn(*args, **kw)
+    except ek.EchoKVError as e:
+        return e.code
+    return ek.OK
+
+
+def test_shape_validation(lib):
+    a, t = caches()
+    ok = ek.make_shape(8, 8, 64, 256, "f32")
+    big = 1 << 30
+    args = (a, t, FAKE, FAKE, FAKE, FAKE, None, FAKE)
+    for bad, want in [
+        (ek.make_shape(8, 3, 64, 256, "f32"), ek.ERR_SHAPE),          # H_q % H_kv
+        (ek.make_shape(8, 8, 64, 576, "f32"), ek.ERR_SHAPE),          # m > D
+        (ek.make_shape(8, 8, 64, -64, "f32"), ek.ERR_SHAPE),
+        (ek.make_shape(8, 8, 64, 96, "f32"), ek.ERR_UNSUPPORTED),     # m % d
+        (ek.make_shape(8, 8, 48, 0, "f32"), ek.ERR_UNSUPPORTED),      # head_dim
+        (ek.make_shape(0, 8, 64, 256, "f32"), ek.ERR_SHAPE),
+    ]:
+        assert ek.workspace_bytes(bad, 1, 100, 1) == 0
+        assert code(ek.decode_attn, bad, *args[:-1], _Ws(big), stream=0) == want
+    bad_dtype = ek.make_shape(8, 8, 64, 256, "f32"); bad_dtype.dtype = 7
+    assert code(ek.decode_attn, bad_dtype, *args[:-1], _Ws(big), stream=0) == ek.ERR_DTYPE
+    assert ek.workspace_bytes(ok, 1, 100, 1) > 0
+    assert ek.workspace_bytes(ok, 0, 100, 1) == 0
+
+
+class _Ws:
+    """Workspace stand-in with a fake pointer and a claimed size."""
+    def __init__(self, nbytes, ptr=FAKE):
+        self._n, self._p = nbytes, ptr
+    def numel(self): return self._n
+    def element_size(self): return 1
+    def data_ptr(self): return self._p
+
+
+def test_decode_argument_errors(lib):
+    sh = ek.make_shape(8, 8, 64, 256, "f32")
+    a, t = caches()
+    big = _Ws(1 << 30)
+    assert code(ek.decode_attn, sh, a, t, None, FAKE, FAKE, FAKE, None, big, stream=0) == ek.ERR_NULL
+    assert code(ek.decode_attn, sh, a, t, FAKE, FAKE, None, FAKE, None, big, stream=0) == ek.ERR_NULL
+    assert code(ek.decode_attn, sh, a, t, FAKE, FAKE, FAKE, None, None, big, stream=0) == ek.ERR_NULL
+    assert code(ek.decode_attn, sh, a, t, FAKE, FAKE, FAKE, FAKE, None, None, stream=0) == ek.ERR_WORKSPACE
+    assert code(ek.decode_attn, sh, a, t, FAKE, FAKE, FAKE, FAKE, None, _Ws(16), stream=0) == ek.ERR_WORKSPACE
+    assert code(ek.decode_attn, sh, a, t, FAKE, FAKE, FAKE, FAKE, None, _Ws(1 << 30, FAKE + 8),
+                stream=0) == ek.ERR_WORKSPACE                       # misaligned
+    # anchor / target disagree
+    a2, t2 = caches(lens=(100,)); t2.seq_len[0] = 99
+    assert code(ek.decode_attn, sh, a2, t2, FAKE, FAKE, FAKE, FAKE, None, big, stream=0) == ek.ERR_SHAPE
+    a3, t3 = caches(m=128)                                          # target width != m
+    assert code(ek.decode_attn, sh, a3, t3, FAKE, FAKE, FAKE, FAKE, None, big, stream=0) == ek.ERR_SHAPE
+    a4, t4 = caches(lens=(0,))                                      # empty sequence
+    assert code(ek.decode_attn, sh, a4, t4, FAKE, FAKE, FAKE, FAKE, None, big, stream=0) == ek.ERR_SHAPE
+    a5, t5 = caches(lens=(300,), caps=[256])                        # len > cap
+    assert code(ek.decode_attn, sh, a5, t5, FAKE, FAKE, FAKE, FAKE, None, big, stream=0) == ek.ERR_SHAPE
+    a6, t6 = caches(lens=(10,), caps=[256], pool=128)               # cap past the pool
+    assert code(ek.decode_attn, sh, a6, t6, FAKE, FAKE, FAKE, FAKE, None, big, stream=0) == ek.ERR_SHAPE
+    a7, t7 = caches(); a7.k = None
+    assert code(ek.decode_attn, sh, a7, t7, FAKE, FAKE, FAKE, FAKE, None, big, stream=0) == ek.ERR_NULL
+
+
+def test_full_retention_needs_no_weights_but_others_do(lib):
+    sh_full = ek.make_shape(8, 8, 64, 512, "f32")
+    a, t = caches(m=512)
+    # passes validation (no weights needed) and only then fails on the missing device
+    rc = code(ek.decode_attn, sh_full, a, t, None, None, FAKE, FAKE, None, _Ws(1 << 30), stream=0)
+    assert rc in (ek.OK, ek.ERR_HIP)
+
+
+def test_append_errors_leave_lengths_untouched(lib):
+    sh = ek.make_shape(8, 8, 64, 256, "f32")
+    a, t = caches(lens=(250, 10), caps=[256, 256])
+    before = t.seq_len.copy()
+    assert code(ek.cache_append, sh, t, FAKE, FAKE, [7, 1], stream=0) == ek.ERR_CAPACITY
+    assert np.array_equal(t.seq_len, before)
+    assert code(ek.cache_append, sh, t, FAKE, FAKE, [-1, 1], stream=0) == ek.ERR_SHAPE
+    assert code(ek.cache_append, sh, t, None, FAKE, [1, 1], stream=0) == ek.ERR_NULL
+    assert np.array_equal(t.seq_len, before)
+    odd = ek.LayerCache(FAKE, FAKE, 128, 512, [0, 256], [1, 1], [256, 256])  # neither D nor m
+    assert code(ek.cache_append, sh, odd, FAKE, FAKE, [1, 1], stream=0) == ek.ERR_SHAPE
+    # zero new tokens: nothing to launch, succeeds without a device
+    assert code(ek.cache_append, sh, t, None, None, [0, 0], stream=0) == ek.OK
+    assert np.array_equal(t.seq_len, before)
+
+
+def test_reconstruct_and_prefill_argument_errors(lib):
+    sh = ek.make_shape(8, 8, 64, 256, "f32")
+    a, t = caches(lens=(100,))
+    assert code(ek.reconstruct, sh, a, t, FAKE, FAKE, 1, 0, 10, FAKE, FAKE, stream=0) == ek.ERR_SHAPE
+    assert code(ek.reconstruct, sh, a, t, FAKE, FAKE, 0, 5, 101, FAKE, FAKE, stream=0) == ek.ERR_SHAPE
+    assert code(ek.reconstruct, sh, a, t, FAKE, FAKE, 0, 7, 5, FAKE, FAKE, stream=0) == ek.ERR_SHAPE
+    assert code(ek.reconstruct, sh, a, t, FAKE, None, 0, 0, 10, FAKE, FAKE, stream=0) == ek.ERR_NULL
+    assert code(ek.reconstruct, sh, a, t, FAKE, FAKE, 0, 0, 10, None, FAKE, stream=0) == ek.ERR_NULL
+    assert code(ek.reconstruct, sh, a, t, FAKE, FAKE, 0, 10, 10, FAKE, FAKE, stream=0) == ek.OK
+    big = _Ws(1 << 30)
+    pf = lambda seq, T_q, q0, ws=big: code(ek.prefill_attn, sh, a, t, FAKE, FAKE, seq, FAKE, T_q, q0,
+                                           FAKE, None, ws, stream=0)
+    assert pf(0, 50, 60) == ek.ERR_SHAPE          # chunk not in the cache yet
+    assert pf(0, 0, 0) == ek.ERR_SHAPE
+    assert pf(2, 10, 0) == ek.ERR_SHAPE
+    assert pf(0, 10, 0, _Ws(8)) == ek.ERR_WORKSPACE
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(ek, "_LIB", None)
+    monkeypatch.setattr(ek, "LIB_PATH", str(tmp_path / "libechokv.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        ek.load()

@@ -321,6 +321,18 @@ def test_gqa_head_map():
     np.testing.assert_allclose(o, o_mha[0], rtol=1e-13, atol=1e-14)
 
 
+def test_single_head_form_equals_full_layer():
+    H_q, H_kv, d, m, L = 8, 4, 8, 16, 21
+    c, Q = make_case(H_q, H_kv, d, m, L, seed=67)
+    o, lse = orc.echokv_decode(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"],
+                               c["W_K"], c["W_V"], H_kv)
+    for h in range(H_q):
+        oh, lh = orc.echokv_decode_head(Q[0, h], c["K_a"], c["V_a"], c["K_r"], c["V_r"],
+                                        c["W_K"], c["W_V"], h // 2, d)
+        np.testing.assert_allclose(oh, o[h], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(lh, lse[h], rtol=1e-12)
+
+
 # ---- cache layout ----------------------------------------------------------------------
 def test_cache_append_keeps_prefix_only():
     D, m = 8, 3
