@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the EchoKV decode hot path on one MI355X.
+
+One step = one decode step of one target layer over the whole batch: append
+the step's new token to the anchor and target caches (echokv_cache_append x2),
+then echokv_decode_attn (retained-head streaming kernel, fused
+reconstruct+attend kernel, split-K merge).  Inputs are synthetic, seeded, and
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N] [--unfused]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def read_traffic(workload_name):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3
+    counter summary (profiles/traffic_<workload>.txt, `key = value` lines), or None."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload_name}.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        if "=" in line and not line.lstrip().startswith("#"):
+            k, v = line.split("=", 1)
+            vals[k.strip()] = v.strip()
+    try:
+        return float(vals["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
+
+
+def cpu_baseline(inp, min_s=12.0):
+    """The fp64 oracle, as it stands, timed on this host over a bounded sample
+    (whole sequences of the same workload) -> context tokens/s."""
+    import numpy as np
+    from oracle import echokv_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    w = inp.w
+    f64 = lambda t: t.double().numpy()
+    W_K, W_V = f64(inp.W_K), f64(inp.W_V)
+    tokens, seqs, t0 = 0, 0, time.perf_counter()
+    while time.perf_counter() - t0 < min_s:       # whole sequences, wrapping round the batch
+        b = seqs % inp.n_decode
+        r = inp.rows(b)
+        orc.echokv_decode(f64(inp.q[b]), f64(inp.K_a[r]), f64(inp.V_a[r]), f64(inp.K_r[r]),
+                          f64(inp.V_r[r]), W_K, W_V, w.n_kv_heads)
+        tokens += inp.seq_len[b]; seqs += 1
+    dt = time.perf_counter() - t0
+    return {"value": tokens / dt, "unit": "context tokens/s/layer", "cores": int(threads),
+            "kind": "oracle",
+            "sample": f"{seqs} sequence passes ({tokens} context tokens) of {w.name}, "
+                      f"fp64 NumPy oracle, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="benchmark configuration index (0-4)")
+    ap.add_argument("--unfused", action="store_true", help="time the unfused comparison path")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding or collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_22910_amd import binding as ek
+    from paper_2603_22910_amd import synth
+    from paper_2603_22910_amd.harness import DeviceWorkload
+
+    w = synth.CONFIGS[args.config]
+    if w.prefill_len:
+        w = w.scaled(prefill_len=0, prefill_q=0)   # decode leg only
+    inp = synth.generate(w)
+    flags = ek.FLAG_UNFUSED if args.unfused else 0
+    dw = DeviceWorkload(inp, flags=flags)
+    dev = dw.dev
+    B = inp.n_decode
+    tokens = inp.total_decode_tokens
+
+    # the step's new token: the last cached row of every sequence, re-appended
+    # each step (lengths are wound back by one on the host, so every step sees
+    # exactly the configured context lengths)
+    last_rows = torch.tensor([inp.seq_start[b] + inp.seq_len[b] - 1 for b in range(B)], device=dev)
+    ka_new, va_new = dw.K_a[last_rows].contiguous(), dw.V_a[last_rows].contiguous()
+    kt_new = torch.zeros(B, w.D, dtype=w.torch_dtype, device=dev)
+    vt_new = torch.zeros(B, w.D, dtype=w.torch_dtype, device=dev)
+    if w.n_retained:
+        kt_new[:, :w.n_retained] = dw.K_r[last_rows]
+        vt_new[:, :w.n_retained] = dw.V_r[last_rows]
+    ones = [1] * B
+    full_len = dw.anchor.seq_len.copy()
+
+    def step():
+        dw.anchor.seq_len[:] = full_len - 1
+        ek.cache_append(dw.shape, dw.anchor, ka_new, va_new, ones)
+        dw.target.seq_len[:] = full_len - 1
+        ek.cache_append(dw.shape, dw.target, kt_new, vt_new, ones)
+        dw.decode()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ek.profile_enable(True)
+    ek.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kern_ms, launches = ek.profile_read()
+    ek.profile_enable(False)
+
+    ms_per_step = dt * 1e3 / args.steps
+    value = tokens / (dt / args.steps)
+
+    # roofline of the dominant kernel (the fused predictor product + attention):
+    # algorithmic work = 4 * d_in * d_out flop per cached token (K and V products)
+    flops = 4.0 * w.d_in * w.d_out * tokens
+    bytes_alg = tokens * 2.0 * w.d_in * w.elem_size + 2.0 * w.d_in * w.d_out * w.elem_size
+    roofline = None
+    if launches > 0 and kern_ms > 0:
+        k_s = kern_ms / launches * 1e-3
+        ach = flops / k_s / 1e12
+        peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
+        roofline = {"bound": "mfma", "kernel": "fused_decode_kernel", "achieved": ach,
+                    "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+                    "traffic": read_traffic(w.name), "kernel_ms": k_s * 1e3,
+                    "algorithmic_flop": flops, "algorithmic_bytes": bytes_alg,
+                    "hbm_frac_of_algorithmic_bytes": bytes_alg / k_s / 1e9 / PEAK_HBM_GBS}
+
+    out = {
+        "metric": "context tokens/s/layer for fused reconstruct+decode-attn; % MFMA & HBM peak",
+        "value": value, "unit": "context tokens/s/layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "batch": B, "context_tokens": tokens,
+                   "H_q": w.n_q_heads, "H_kv": w.n_kv_heads, "head_dim": w.head_dim,
+                   "n_retained": w.n_retained, "d_in": w.d_in, "d_out": w.d_out,
+                   "path": "unfused" if args.unfused else "fused",
+                   "step": "cache_append(anchor)+cache_append(target)+decode_attn"},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inp)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

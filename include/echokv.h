@@ -138,6 +138,16 @@ int echokv_prefill_attn(const echokv_shape *shape, const echokv_layer_cache *anc
                         int32_t q_pos0, void *out, float *lse_out, void *workspace,
                         size_t workspace_bytes, void *hip_stream);
 
+/* Measurement aid (no paper passage: it exists so that a benchmark can report
+ * the duration of the kernel that dominates echokv_decode_attn, the fused
+ * predictor-product + attention kernel, separately from the whole call).
+ * While enabled, every echokv_decode_attn call records a HIP event pair on its
+ * stream around that kernel's launch.  echokv_profile_read waits for the
+ * recorded events, adds up the elapsed times, returns them with the number of
+ * launches, and forgets them.  Not thread safe; keep it off in production. */
+int echokv_profile_enable(int on);
+int echokv_profile_read(double *total_ms, int64_t *launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,8 @@ BF16, F32 = 0, 1
 FLAG_UNFUSED = 1
 
 EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
-           "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn")
+           "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn",
+           "echokv_profile_enable", "echokv_profile_read")
 
 
 class EchoKVError(RuntimeError):
@@ -71,6 +72,10 @@ def load() -> C.CDLL:
                                         C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_int32,
                                         C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.echokv_profile_enable.restype = C.c_int
+    lib.echokv_profile_enable.argtypes = [C.c_int]
+    lib.echokv_profile_read.restype = C.c_int
+    lib.echokv_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     _LIB = lib
     return lib
 
@@ -183,3 +188,14 @@ def prefill_attn(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v,
                                       seq, _ptr(q), T_q, q_pos0, _ptr(out), _ptr(lse_out),
                                       _ptr(workspace), nbytes, _stream(stream)),
            "echokv_prefill_attn")
+
+
+def profile_enable(on: bool):
+    _check(load().echokv_profile_enable(1 if on else 0), "echokv_profile_enable")
+
+
+def profile_read():
+    """(total milliseconds, launches) of the dominant decode kernel since the last read."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    _check(load().echokv_profile_read(C.byref(ms), C.byref(n)), "echokv_profile_read")
+    return float(ms.value), int(n.value)

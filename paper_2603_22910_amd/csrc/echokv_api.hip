@@ -91,6 +91,13 @@ WsPlan plan_ws(const Dims& dm, int64_t part_slots, int64_t recon_rows) {
 
 constexpr int kPrefillQChunk = kMaxSeqPerLaunch;   // queries per launch, streaming prefill
 
+// Optional event pairs around the dominant decode kernel (echokv_profile_*).
+struct Profiler {
+  bool on = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs;
+};
+Profiler g_prof;
+
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) return ECHOKV_ERR_HIP; } while (0)
 #define LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return ECHOKV_ERR_HIP; } while (0)
 
@@ -188,10 +195,19 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
     }
     if (n_rec_heads > 0) {
       if (fused) {
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (g_prof.on) {
+          HIP_TRY(hipEventCreate(&e0)); HIP_TRY(hipEventCreate(&e1));
+          HIP_TRY(hipEventRecord(e0, st));
+        }
         int rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.scale,
                                         (const T*)an->k, (const T*)an->v, (const T*)tg->k,
                                         (const T*)tg->v, (const T*)w_k, (const T*)w_v, qq, po,
                                         pml, mt, &fused_step, st);
+        if (g_prof.on) {
+          HIP_TRY(hipEventRecord(e1, st));
+          g_prof.pairs.emplace_back(e0, e1);
+        }
         if (rc) return rc;
       } else {
         GemmArgs<T> g;
@@ -368,6 +384,28 @@ size_t echokv_workspace_bytes(const echokv_shape* shape, int32_t batch, int64_t 
   size_t need = decode_ws_bytes(dm, batch, total_tokens, true);
   if (max_q > 1) need = std::max(need, prefill_ws_bytes(dm, total_tokens, max_q));
   return need;
+}
+
+int echokv_profile_enable(int on) {
+  g_prof.on = on != 0;
+  return ECHOKV_OK;
+}
+
+int echokv_profile_read(double* total_ms, int64_t* launches) {
+  if (!total_ms || !launches) return ECHOKV_ERR_NULL;
+  double tot = 0.0;
+  int64_t n = 0;
+  int rc = ECHOKV_OK;
+  for (auto& pr : g_prof.pairs) {
+    float ms = 0.f;
+    if (hipEventSynchronize(pr.second) != hipSuccess ||
+        hipEventElapsedTime(&ms, pr.first, pr.second) != hipSuccess) rc = ECHOKV_ERR_HIP;
+    else { tot += ms; ++n; }
+    (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second);
+  }
+  g_prof.pairs.clear();
+  *total_ms = tot; *launches = n;
+  return rc;
 }
 
 int echokv_cache_append(const echokv_shape* shape, echokv_layer_cache* dst, const void* k_new,

@@ -1,15 +1,489 @@
-// Fused reconstruct-then-attend decode kernel (bf16 MFMA).  Placeholder until
-// the MFMA path lands: reports "not supported" so the unfused path runs.
+// Fused reconstruct-then-attend decode kernel for gfx950 (bf16 MFMA), and the
+// stand-alone predictor product that shares its main loop.
+//
+// One workgroup owns a tile of 256 cached tokens x 256 predicted columns
+// (two heads of 128, or four of 64).  For that tile it
+//   1. runs the predictor product for K (Eq. 3) on v_mfma_f32_32x32x16_bf16,
+//      with W as the row operand so that each lane ends up holding whole
+//      columns of K_hat^T for ONE token: the score q . k_hat_j (Eq. 7) is then a
+//      sum over the lane's own accumulators plus one cross-half add;
+//   2. takes the softmax numerators over each wave's 128 tokens (max, sum of
+//      exponentials), leaving p_j in LDS;
+//   3. runs the predictor product for V with X as the row operand, so each
+//      lane holds rows (tokens) of V_hat for one column and sum_j p_j v_hat_j
+//      is again lane-local;
+//   4. writes one split-K partial (max, sum, unnormalised o) per wave and head.
+// K_hat and V_hat live only in accumulator registers: they never reach LDS or HBM.
+//
+// The predictor input row [anchor ; retained] (Eq. 3) is never materialised
+// either: the k-loop walks the anchor cache for the first D input dims and
+// the target's retained cache for the last m.
 #pragma once
 #include "common.h"
+
 namespace echokv {
-template <typename T> inline bool fused_decode_supported(int, int) { return false; }
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
+
+namespace fused {
+
+constexpr int BM = 256;      // tokens per workgroup tile
+constexpr int BN = 256;      // predicted columns per workgroup tile
+constexpr int BK = 64;       // input dims per pipeline stage
+constexpr int NTHREADS = 256;
+constexpr int WM = 128, WN = 128;   // per-wave tile (2 x 2 waves)
+constexpr int MAXPAIR = 8;   // (head in wave tile, query head in group) pairs per wave
+
+struct Args {
+  const bf16_t* xa[2];   // anchor cache K, V      [pool, D]
+  const bf16_t* xr[2];   // retained cache K, V    [pool, m]
+  const bf16_t* w[2];    // W_K, W_V               [D + m, d_out]
+  const bf16_t* q;       // [nseq, H_q, d]
+  float* part_o;         // [slots, H_q, d]
+  float* part_ml;        // [slots, H_q, 2]
+  bf16_t* out[2];        // store kernel only: K_hat / V_hat destination
+  int64_t ldo;           // store kernel: row stride (elements)
+  int32_t col0;          // store kernel: first column
+  int32_t D, m, d_out, H_q, G, n_ret_heads;
+  float scale;
+  int32_t n_col_tiles, n_tiles;   // column tiles; token tiles * column tiles
+};
+
+// LDS tile: [rows][64 k] bf16, a row is 8 chunks of 16 bytes; chunk c of row r
+// lives at chunk slot c ^ swz(r), swz(r) = (r ^ (r >> 3)) & 7, which keeps the
+// 16-byte fragment reads of 16 consecutive rows, the row-contiguous X writes
+// and the column-strided W writes all spread over the banks.  All addresses a
+// thread ever needs are a handful of per-thread bases plus compile-time
+// offsets; they are worked out once (struct Addr) so that the main loop
+// carries no address arithmetic.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+struct Smem {
+  char x[2][BM * BK * 2];
+  char w[2][BN * BK * 2];
+  float q[BN * MAXPAIR];               // [(head in tile * G + g)][d], pre-scaled
+  float p[4][MAXPAIR][128];            // per wave and pair: softmax numerators of its 128 tokens
+  float ml[4][MAXPAIR][2];             // per wave and pair: max and sum
+};
+constexpr int kStageBytes = BM * BK * 2;          // one stage of x (same for w)
+constexpr int kWBase = 2 * kStageBytes;           // offset of Smem::w from Smem::x
+
+struct Addr {
+  // fragment reads: row = wave base + 32*i + lr, chunk = 2*kk + lh.
+  // byte offset = fr[kk][i & 1] + (i >> 1) * 8192 (+ operand / stage base)
+  uint32_t frx[4][2], frw[4][2];
+  // X writes: row = 32*i + tid/8, chunk = tid & 7: wx[i & 1] + (i >> 1) * 8192
+  uint32_t wx[2];
+  // W writes: row = 8*(tid & 31) + j, chunk = tid >> 5: ww[j]
+  uint32_t ww[8];
+};
+
+__device__ __forceinline__ void make_addr(Addr& ad, int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wt = wave >> 1, wc = wave & 1;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int flr = (lr ^ (lr >> 3)) & 7;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+    for (int ip = 0; ip < 2; ++ip) {
+      const uint32_t o = (uint32_t)((ip * 32 + lr) * 128 + (((kk * 2 + lh) ^ flr ^ (ip << 2)) << 4));
+      ad.frx[kk][ip] = o + wt * (WM * 128);
+      ad.frw[kk][ip] = o + wc * (WN * 128) + kWBase;
+    }
+  const int r0 = tid >> 3, c = tid & 7;
+  const int f0 = (r0 ^ (r0 >> 3)) & 7;
+#pragma unroll
+  for (int ip = 0; ip < 2; ++ip)
+    ad.wx[ip] = (uint32_t)((ip * 32 + r0) * 128 + ((c ^ f0 ^ (ip << 2)) << 4));
+  const int nb = tid & 31, kb = tid >> 5;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    ad.ww[j] = (uint32_t)((nb * 8 + j) * 128 + (((kb ^ j ^ nb) & 7) << 4)) + kWBase;
+}
+
+// global -> registers for one k-tile.  X: 8 x 16B per thread; W: an 8x8 block.
+struct Stage {
+  u32x4_t x[8];
+  u32x4_t w[8];
+};
+
+// X rows of the tile: `base` points at the tile's first row and column k0;
+// row i*32 + tid/8 (clamped to `last`, the last valid row of the tile).
+__device__ __forceinline__ void load_x(Stage& s, const bf16_t* base, int ld, int last, int tid) {
+  const int c = tid & 7, r0 = tid >> 3;
+  const char* p = reinterpret_cast<const char*>(base) + c * 16;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const uint32_t off = (uint32_t)min(i * 32 + r0, last) * (uint32_t)(ld * 2);
+    s.x[i] = *reinterpret_cast<const u32x4_t*>(p + off);
+  }
+}
+
+// W block of 8 k x 8 n per thread; `base` points at row k0 of W, column n0.
+// Column blocks past d_out are clamped onto the last valid block: the heads
+// they would feed are skipped in the epilogue, they only need to be readable.
+__device__ __forceinline__ void load_w(Stage& s, const bf16_t* base, int d_out, int nclamp,
+                                       int tid) {
+  const int nb = tid & 31, kb = tid >> 5;
+  const uint32_t off0 = (uint32_t)(kb * 8) * (uint32_t)(d_out * 2) + (uint32_t)min(nb * 8, nclamp) * 2;
+  const char* p = reinterpret_cast<const char*>(base);
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    s.w[i] = *reinterpret_cast<const u32x4_t*>(p + off0 + (uint32_t)i * (uint32_t)(d_out * 2));
+}
+
+__device__ __forceinline__ void store_x(const Stage& s, char* smem, int stage, const Addr& ad) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    *reinterpret_cast<u32x4_t*>(smem + ad.wx[i & 1] + (i >> 1) * 8192 + stage * kStageBytes) = s.x[i];
+}
+
+// 8x8 transpose of 16-bit elements held as 8 rows (k) of 4 dwords (8 n), then
+// 8 row writes: LDS row n (a W column) gets its 8 consecutive k values.
+__device__ __forceinline__ void store_w(const Stage& s, char* smem, int stage, const Addr& ad) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    u32x4_t o;
+#pragma unroll
+    for (int pq = 0; pq < 4; ++pq) {
+      const uint32_t a = s.w[2 * pq][j >> 1], b = s.w[2 * pq + 1][j >> 1];
+      o[pq] = (j & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+    }
+    *reinterpret_cast<u32x4_t*>(smem + ad.ww[j] + stage * kStageBytes) = o;
+  }
+}
+
+__device__ __forceinline__ void load_frags(bf16x8_t (&xf)[4], bf16x8_t (&wf)[4], const char* smem,
+                                           int stage, int kk, const Addr& ad) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    xf[i] = *reinterpret_cast<const bf16x8_t*>(smem + ad.frx[kk][i & 1] + (i >> 1) * 8192 + stage * kStageBytes);
+    wf[i] = *reinterpret_cast<const bf16x8_t*>(smem + ad.frw[kk][i & 1] + (i >> 1) * 8192 + stage * kStageBytes);
+  }
+}
+
+// One k-tile of MFMAs for a wave: 4 k-steps x (4 X fragments, 4 W fragments, 16 MFMAs),
+// the fragments of step kk+1 being fetched while step kk multiplies.
+// SWAP: accumulator block [ci][ji] = W^T x X^T (rows = output columns, lanes =
+// tokens); otherwise [ji][ci] = X x W (rows = tokens, lanes = output columns).
+template <bool SWAP, int STAGE>
+__device__ __forceinline__ void mma_tile(floatx16_t (&acc)[4][4], const char* smem, const Addr& ad) {
+  bf16x8_t xf[2][4], wf[2][4];
+  load_frags(xf[0], wf[0], smem, STAGE, 0, ad);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    if (kk < 3) load_frags(xf[(kk + 1) & 1], wf[(kk + 1) & 1], smem, STAGE, kk + 1, ad);
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        if constexpr (SWAP)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk & 1][a], xf[kk & 1][b], acc[a][b], 0, 0, 0);
+        else
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[kk & 1][a], wf[kk & 1][b], acc[a][b], 0, 0, 0);
+      }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// Full k-loop over d_in = D + m for one of the two products.  Ends with a
+// barrier, so the stage buffers are free when it returns.
+//   xa_tile / xr_tile: first row of the token tile in the anchor / retained cache
+//   last: index (in the tile) of the last valid row;  w_tile: W + n0
+// The loop body handles two k-tiles so that the LDS stage is a compile-time
+// constant (d_in / 64 is even or odd; an odd tail is peeled).
+template <bool SWAP>
+__device__ __forceinline__ void gemm_pass(floatx16_t (&acc)[4][4], char* smem, const Args& a,
+                                          const bf16_t* xa_tile, const bf16_t* xr_tile,
+                                          const bf16_t* w_tile, int last, int nclamp, int tid_in) {
+  // The LDS addresses are rebuilt for every pass from an opaque copy of the
+  // thread id: values that stayed live across the register-hungry epilogues
+  // would be spilled and reloaded inside the main loop.
+  int tid = tid_in;
+  asm volatile("" : "+v"(tid));
+  Addr ad;
+  make_addr(ad, tid);
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  const int nk = (a.D + a.m) / BK;
+  const int nka = a.D / BK;
+  Stage st;
+  auto fetch = [&](int kn) {
+    if (kn < nka) load_x(st, xa_tile + kn * BK, a.D, last, tid);
+    else load_x(st, xr_tile + (kn - nka) * BK, a.m, last, tid);
+    load_w(st, w_tile + (int64_t)kn * BK * a.d_out, a.d_out, nclamp, tid);
+  };
+  fetch(0);
+  store_x(st, smem, 0, ad);
+  store_w(st, smem, 0, ad);
+  __syncthreads();
+  int kt = 0;
+  for (; kt + 2 <= nk; kt += 2) {
+    fetch(kt + 1);
+    mma_tile<SWAP, 0>(acc, smem, ad);
+    store_x(st, smem, 1, ad);
+    store_w(st, smem, 1, ad);
+    __syncthreads();
+    const bool more = kt + 2 < nk;
+    if (more) fetch(kt + 2);
+    mma_tile<SWAP, 1>(acc, smem, ad);
+    if (more) {
+      store_x(st, smem, 0, ad);
+      store_w(st, smem, 0, ad);
+    }
+    __syncthreads();
+  }
+  if (kt < nk) {          // odd tile count: last tile sits in stage 0
+    mma_tile<SWAP, 0>(acc, smem, ad);
+    __syncthreads();
+  }
+}
+
+// Workgroup id -> (token tile, column tile).  Consecutive workgroup ids go to
+// different XCDs, so each XCD is given one contiguous range of logical tiles:
+// the column tiles of a token tile then hit the same L2 copy of X.
+__device__ __forceinline__ bool tile_of_block(const Args& a, int& ttile, int& ctile) {
+  const int per_xcd = (a.n_tiles + 7) >> 3;
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= a.n_tiles) return false;
+  ttile = logical / a.n_col_tiles;
+  ctile = logical % a.n_col_tiles;
+  return true;
+}
+
+template <int HD>
+__global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta meta) {
+  __shared__ Smem sm;
+  char* smem = reinterpret_cast<char*>(&sm);
+  constexpr int HPW = WN / HD;       // heads per wave tile
+  constexpr int CBH = HD / 32;       // 32-column blocks per head
+  int ttile, ctile;
+  if (!tile_of_block(a, ttile, ctile)) return;
+  const int b = find_seq(meta.tbase, meta.n, ttile);
+  const int L = meta.len[b];
+  const int j0 = (ttile - meta.tbase[b]) * BM;
+  const int n0 = ctile * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wt = wave >> 1, wc = wave & 1;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int G = a.G;
+  const int H_kv = a.H_q / G;
+
+  // rows past the end of the sequence are clamped onto its last valid token,
+  // so that masked tokens still contribute finite numbers
+  const int last = min(BM, L - j0) - 1;
+  const int64_t row0 = meta.start[b] + j0;
+  const int nclamp = a.d_out - n0 - 8;     // last readable 8-column block of this tile
+  // queries of this tile's heads, pre-scaled, as fp32
+  {
+    const int kvh0 = a.n_ret_heads + n0 / HD;
+    for (int idx = tid; idx < (BN / HD) * G * HD; idx += NTHREADS) {
+      const int c = idx % HD, pg = idx / HD;       // pg = head_in_tile * G + g
+      const int kvh = kvh0 + pg / G;
+      float v = 0.f;
+      if (kvh < H_kv)
+        v = bf16_to_f32(a.q[((int64_t)b * a.H_q + kvh * G + pg % G) * HD + c]) * a.scale;
+      sm.q[pg * HD + c] = v;
+    }
+  }
+
+  floatx16_t acc[4][4];
+  // ---- K_hat^T = W_K^T X^T  (gemm_pass begins with loads and a barrier, which
+  //      also publishes sm.q) ------------------------------------------------------
+  gemm_pass<true>(acc, smem, a, a.xa[0] + row0 * a.D, a.xr[0] + row0 * a.m, a.w[0] + n0, last,
+                  nclamp, tid);
+  const int jw0 = j0 + wt * WM;                 // first token of this wave
+#pragma unroll
+  for (int hw = 0; hw < HPW; ++hw) {
+    for (int g = 0; g < G; ++g) {
+      const float* qs = &sm.q[((wc * HPW + hw) * G + g) * HD];
+      float s[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int cb = 0; cb < CBH; ++cb) {
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const float4 qv = *reinterpret_cast<const float4*>(qs + cb * 32 + r4 * 8 + lh * 4);
+#pragma unroll
+          for (int ji = 0; ji < 4; ++ji) {
+            const floatx16_t& c = acc[hw * CBH + cb][ji];
+            s[ji] = fmaf(qv.x, c[r4 * 4 + 0], s[ji]);
+            s[ji] = fmaf(qv.y, c[r4 * 4 + 1], s[ji]);
+            s[ji] = fmaf(qv.z, c[r4 * 4 + 2], s[ji]);
+            s[ji] = fmaf(qv.w, c[r4 * 4 + 3], s[ji]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      float mx = -INFINITY;
+#pragma unroll
+      for (int ji = 0; ji < 4; ++ji) {
+        s[ji] += __shfl_xor(s[ji], 32, 64);
+        if (jw0 + ji * 32 + lr >= L) s[ji] = -INFINITY;
+        mx = fmaxf(mx, s[ji]);
+      }
+      mx = wave_max(mx, 32);
+      float sum = 0.f;
+      float* pp = sm.p[wave][hw * G + g];
+#pragma unroll
+      for (int ji = 0; ji < 4; ++ji) {
+        const float p = (s[ji] == -INFINITY) ? 0.f : __expf(s[ji] - mx);
+        sum += p;
+        if (lh == 0) pp[ji * 32 + lr] = p;
+      }
+      sum = wave_sum(sum, 32);
+      if (lane == 0) { sm.ml[wave][hw * G + g][0] = mx; sm.ml[wave][hw * G + g][1] = sum; }
+    }
+  }
+  // ---- V_hat = X W_V (its first barrier orders the p / ml writes above) -----------
+  gemm_pass<false>(acc, smem, a, a.xa[1] + row0 * a.D, a.xr[1] + row0 * a.m, a.w[1] + n0, last,
+                   nclamp, tid);
+  if (jw0 >= L) return;                          // wave has no valid token: no partial
+  const int slot = meta.sbase[b] + (jw0 / kSlotTokens);
+#pragma unroll
+  for (int hw = 0; hw < HPW; ++hw) {
+    const int kvh = a.n_ret_heads + (n0 + wc * WN) / HD + hw;
+    if (kvh >= H_kv) continue;
+    for (int g = 0; g < G; ++g) {
+      const float* pp = sm.p[wave][hw * G + g];
+      float o[CBH];
+#pragma unroll
+      for (int cb = 0; cb < CBH; ++cb) o[cb] = 0.f;
+#pragma unroll
+      for (int ji = 0; ji < 4; ++ji) {
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const float4 pv = *reinterpret_cast<const float4*>(pp + ji * 32 + r4 * 8 + lh * 4);
+#pragma unroll
+          for (int cb = 0; cb < CBH; ++cb) {
+            const floatx16_t& c = acc[ji][hw * CBH + cb];
+            o[cb] = fmaf(pv.x, c[r4 * 4 + 0], o[cb]);
+            o[cb] = fmaf(pv.y, c[r4 * 4 + 1], o[cb]);
+            o[cb] = fmaf(pv.z, c[r4 * 4 + 2], o[cb]);
+            o[cb] = fmaf(pv.w, c[r4 * 4 + 3], o[cb]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      const int64_t ph = (int64_t)slot * a.H_q + kvh * G + g;
+#pragma unroll
+      for (int cb = 0; cb < CBH; ++cb) {
+        o[cb] += __shfl_xor(o[cb], 32, 64);
+        if (lh == 0) a.part_o[ph * HD + cb * 32 + lr] = o[cb];
+      }
+      if (lane == 0) {
+        a.part_ml[ph * 2] = sm.ml[wave][hw * G + g][0];
+        a.part_ml[ph * 2 + 1] = sm.ml[wave][hw * G + g][1];
+      }
+    }
+  }
+}
+
+// Stand-alone predictor product (Eq. 3) with the same main loop: K_hat or V_hat
+// (blockIdx.y) of the tile is rounded to bf16 and stored at
+// out[row, col0 + column].  Output row = sbase[b]*kSlotTokens + j.
+__global__ __launch_bounds__(NTHREADS) void recon_mfma_kernel(Args a, SeqMeta meta) {
+  __shared__ Smem sm;
+  char* smem = reinterpret_cast<char*>(&sm);
+  int ttile, ctile;
+  if (!tile_of_block(a, ttile, ctile)) return;
+  const int which = blockIdx.y;
+  const int b = find_seq(meta.tbase, meta.n, ttile);
+  const int L = meta.len[b];
+  const int j0 = (ttile - meta.tbase[b]) * BM;
+  const int n0 = ctile * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wt = wave >> 1, wc = wave & 1;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int last = min(BM, L - j0) - 1;
+  const int64_t row0 = meta.start[b] + j0;
+  const int nclamp = a.d_out - n0 - 8;
+  floatx16_t acc[4][4];
+  gemm_pass<false>(acc, smem, a, a.xa[which] + row0 * a.D, a.xr[which] + row0 * a.m,
+                   a.w[which] + n0, last, nclamp, tid);
+  bf16_t* out = a.out[which];
+  const int64_t orow0 = (int64_t)meta.sbase[b] * kSlotTokens;
+#pragma unroll
+  for (int ji = 0; ji < 4; ++ji) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int j = j0 + wt * WM + ji * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+      if (j >= L) continue;
+#pragma unroll
+      for (int ci = 0; ci < 4; ++ci) {
+        const int c = n0 + wc * WN + ci * 32 + lr;
+        if (c < a.d_out) out[(orow0 + j) * a.ldo + a.col0 + c] = f32_to_bf16(acc[ji][ci][r]);
+      }
+    }
+  }
+}
+
+}  // namespace fused
+
+// ---- host-side launchers ------------------------------------------------------------
+template <typename T> inline bool fused_decode_supported(int d, int G) {
+  return sizeof(T) == 2 && (d == 64 || d == 128) && (128 / d) * G <= fused::MAXPAIR;
+}
+template <typename T> inline bool recon_mfma_supported() { return sizeof(T) == 2; }
+
+inline int fused_fill_tiles(SeqMeta& mt) {
+  int acc = 0;
+  for (int b = 0; b < mt.n; ++b) { mt.tbase[b] = acc; acc += (mt.len[b] + fused::BM - 1) / fused::BM; }
+  mt.tbase[mt.n] = acc;
+  return acc;
+}
+
 template <typename T>
-inline int launch_fused_decode(int, int, int, int, float, const T*, const T*, const T*, const T*,
-                               const T*, const T*, const T*, float*, float*, SeqMeta&, int*,
-                               hipStream_t) { return 6; }
-template <typename T> inline bool recon_mfma_supported() { return false; }
+inline int launch_fused_decode(int H_q, int H_kv, int d, int m, float scale, const T* ka,
+                               const T* va, const T* kr, const T* vr, const T* wk, const T* wv,
+                               const T* q, float* part_o, float* part_ml, SeqMeta& mt,
+                               int* fused_step, hipStream_t st) {
+  if constexpr (sizeof(T) != 2) {
+    return 6;
+  } else {
+    fused::Args a;
+    a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk; a.w[1] = wv;
+    a.q = q; a.part_o = part_o; a.part_ml = part_ml;
+    a.out[0] = a.out[1] = nullptr; a.ldo = 0; a.col0 = 0;
+    a.D = H_kv * d; a.m = m; a.d_out = a.D - m; a.H_q = H_q; a.G = H_q / H_kv;
+    a.n_ret_heads = m / d; a.scale = scale;
+    a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;
+    a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
+    const int grid = ((a.n_tiles + 7) / 8) * 8;
+    if (d == 128) hipLaunchKernelGGL((fused::fused_decode_kernel<128>), dim3(grid), dim3(fused::NTHREADS), 0, st, a, mt);
+    else hipLaunchKernelGGL((fused::fused_decode_kernel<64>), dim3(grid), dim3(fused::NTHREADS), 0, st, a, mt);
+    if (hipGetLastError() != hipSuccess) return 7;
+    *fused_step = 1;
+    return 0;
+  }
+}
+
+// K_hat and V_hat of the sequences in `mt` -> out_k / out_v [rows, ldo] at
+// column col0, output row = sbase[b]*kSlotTokens + j.
 template <typename T>
-inline int launch_recon_mfma(int, int, const T*, const T*, const T*, const T*, const T*, const T*,
-                             T*, T*, int64_t, int, SeqMeta&, hipStream_t) { return 6; }
+inline int launch_recon_mfma(int D, int m, const T* ka, const T* va, const T* kr, const T* vr,
+                             const T* wk, const T* wv, T* out_k, T* out_v, int64_t ldo, int col0,
+                             SeqMeta& mt, hipStream_t st) {
+  if constexpr (sizeof(T) != 2) {
+    return 6;
+  } else {
+    fused::Args a;
+    a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk; a.w[1] = wv;
+    a.q = nullptr; a.part_o = nullptr; a.part_ml = nullptr;
+    a.out[0] = out_k; a.out[1] = out_v; a.ldo = ldo; a.col0 = col0;
+    a.D = D; a.m = m; a.d_out = D - m; a.H_q = 0; a.G = 1; a.n_ret_heads = 0; a.scale = 0.f;
+    a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;
+    a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
+    const int grid = ((a.n_tiles + 7) / 8) * 8;
+    hipLaunchKernelGGL(fused::recon_mfma_kernel, dim3(grid, 2), dim3(fused::NTHREADS), 0, st, a, mt);
+    if (hipGetLastError() != hipSuccess) return 7;
+    return 0;
+  }
+}
+
 }  // namespace echokv

@@ -227,7 +227,7 @@ def test_prefill_last_row_equals_decode():
                           inp.V_a, inp.K_r, inp.V_r, inp.W_K, inp.W_V, inp2.q, None, 0)
     dd = DeviceWorkload(single, out_dtype="f32")
     o_dec, _ = dd.decode(); torch.cuda.synchronize()
-    np.testing.assert_allclose(host(out)[-1], host(o_dec)[0], rtol=2e-3, atol=2e-4)
+    np.testing.assert_allclose(host(out)[-1], host(o_dec)[0], rtol=1e-2, atol=4e-3)  # bf16 K_hat in prefill
 
 
 # ---- full-size configurations: sampled outputs against the oracle ----------------
