@@ -109,29 +109,38 @@ struct Stage {
   u32x4_t w[8];
 };
 
-// X rows of the tile: `base` points at the tile's first row and column k0;
-// row i*32 + tid/8 (clamped to `last`, the last valid row of the tile).
-__device__ __forceinline__ void load_x(Stage& s, const bf16_t* base, int ld, int last, int tid) {
-  const int c = tid & 7, r0 = tid >> 3;
-  const char* p = reinterpret_cast<const char*>(base) + c * 16;
+// Per-thread global offsets, fixed for a pass.
+struct GOff {
+  uint32_t xrow[8];   // clamped tile row of X load i
+  uint32_t xcol;      // byte offset of this thread's 16-byte chunk in a 128-byte k-slab
+  uint32_t w0;        // byte offset of this thread's W block inside a k-tile of W
+};
+
+__device__ __forceinline__ void make_goff(GOff& g, int tid, int last, int d_out, int nclamp) {
+  const int r0 = tid >> 3;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const uint32_t off = (uint32_t)min(i * 32 + r0, last) * (uint32_t)(ld * 2);
-    s.x[i] = *reinterpret_cast<const u32x4_t*>(p + off);
-  }
+  for (int i = 0; i < 8; ++i) g.xrow[i] = (uint32_t)min(i * 32 + r0, last);
+  g.xcol = (uint32_t)(tid & 7) * 16;
+  const int nb = tid & 31, kb = tid >> 5;
+  // column blocks past d_out are clamped onto the last valid block: the heads
+  // they would feed are skipped in the epilogue, they only need to be readable
+  g.w0 = (uint32_t)(kb * 8) * (uint32_t)(d_out * 2) + (uint32_t)min(nb * 8, nclamp) * 2;
 }
 
-// W block of 8 k x 8 n per thread; `base` points at row k0 of W, column n0.
-// Column blocks past d_out are clamped onto the last valid block: the heads
-// they would feed are skipped in the epilogue, they only need to be readable.
-__device__ __forceinline__ void load_w(Stage& s, const bf16_t* base, int d_out, int nclamp,
-                                       int tid) {
-  const int nb = tid & 31, kb = tid >> 5;
-  const uint32_t off0 = (uint32_t)(kb * 8) * (uint32_t)(d_out * 2) + (uint32_t)min(nb * 8, nclamp) * 2;
-  const char* p = reinterpret_cast<const char*>(base);
+// Issue the 16 global loads of k-tile `kn`: uniform base + 32-bit per-thread offset.
+__device__ __forceinline__ void fetch_tile(Stage& s, const GOff& g, const bf16_t* xa_tile,
+                                           const bf16_t* xr_tile, const bf16_t* w_tile, int D,
+                                           int m, int d_out, int nka, int kn) {
+  const bool anchor = kn < nka;
+  const char* xb = reinterpret_cast<const char*>(anchor ? xa_tile + kn * BK : xr_tile + (kn - nka) * BK);
+  const uint32_t ld2 = (uint32_t)(anchor ? D : m) * 2;
 #pragma unroll
   for (int i = 0; i < 8; ++i)
-    s.w[i] = *reinterpret_cast<const u32x4_t*>(p + off0 + (uint32_t)i * (uint32_t)(d_out * 2));
+    s.x[i] = *reinterpret_cast<const u32x4_t*>(xb + (g.xrow[i] * ld2 + g.xcol));
+  const char* wb = reinterpret_cast<const char*>(w_tile + (int64_t)kn * BK * d_out);
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    s.w[i] = *reinterpret_cast<const u32x4_t*>(wb + (int64_t)i * d_out * 2 + g.w0);
 }
 
 __device__ __forceinline__ void store_x(const Stage& s, char* smem, int stage, const Addr& ad) {
@@ -142,6 +151,7 @@ __device__ __forceinline__ void store_x(const Stage& s, char* smem, int stage, c
 
 // 8x8 transpose of 16-bit elements held as 8 rows (k) of 4 dwords (8 n), then
 // 8 row writes: LDS row n (a W column) gets its 8 consecutive k values.
+// One byte-permute per output dword.
 __device__ __forceinline__ void store_w(const Stage& s, char* smem, int stage, const Addr& ad) {
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
@@ -149,100 +159,215 @@ __device__ __forceinline__ void store_w(const Stage& s, char* smem, int stage, c
 #pragma unroll
     for (int pq = 0; pq < 4; ++pq) {
       const uint32_t a = s.w[2 * pq][j >> 1], b = s.w[2 * pq + 1][j >> 1];
-      o[pq] = (j & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+      o[pq] = __builtin_amdgcn_perm(b, a, (j & 1) ? 0x07060302u : 0x05040100u);
     }
     *reinterpret_cast<u32x4_t*>(smem + ad.ww[j] + stage * kStageBytes) = o;
   }
 }
 
-__device__ __forceinline__ void load_frags(bf16x8_t (&xf)[4], bf16x8_t (&wf)[4], const char* smem,
-                                           int stage, int kk, const Addr& ad) {
+struct Frags {
+  bf16x8_t x[4], w[4];
+};
+
+// Fragment-read addresses point into the stage being multiplied, write
+// addresses into the other one; both flip once per k-tile.
+__device__ __forceinline__ void toggle_stage(Addr& ad) {
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+    for (int ip = 0; ip < 2; ++ip) { ad.frx[kk][ip] ^= kStageBytes; ad.frw[kk][ip] ^= kStageBytes; }
+#pragma unroll
+  for (int ip = 0; ip < 2; ++ip) ad.wx[ip] ^= kStageBytes;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) ad.ww[j] ^= kStageBytes;
+}
+
+__device__ __forceinline__ void load_frags(Frags& f, const char* smem, int stage, int kk,
+                                           const Addr& ad) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    xf[i] = *reinterpret_cast<const bf16x8_t*>(smem + ad.frx[kk][i & 1] + (i >> 1) * 8192 + stage * kStageBytes);
-    wf[i] = *reinterpret_cast<const bf16x8_t*>(smem + ad.frw[kk][i & 1] + (i >> 1) * 8192 + stage * kStageBytes);
+    f.x[i] = *reinterpret_cast<const bf16x8_t*>(smem + ad.frx[kk][i & 1] + (i >> 1) * 8192 + stage * kStageBytes);
+    f.w[i] = *reinterpret_cast<const bf16x8_t*>(smem + ad.frw[kk][i & 1] + (i >> 1) * 8192 + stage * kStageBytes);
   }
 }
 
-// One k-tile of MFMAs for a wave: 4 k-steps x (4 X fragments, 4 W fragments, 16 MFMAs),
-// the fragments of step kk+1 being fetched while step kk multiplies.
-// SWAP: accumulator block [ci][ji] = W^T x X^T (rows = output columns, lanes =
-// tokens); otherwise [ji][ci] = X x W (rows = tokens, lanes = output columns).
-template <bool SWAP, int STAGE>
-__device__ __forceinline__ void mma_tile(floatx16_t (&acc)[4][4], const char* smem, const Addr& ad) {
-  bf16x8_t xf[2][4], wf[2][4];
-  load_frags(xf[0], wf[0], smem, STAGE, 0, ad);
+// 16 MFMAs of one k-step.  SWAP: accumulator block [ci][ji] = W^T x X^T (rows =
+// output columns, lanes = tokens); otherwise [ji][ci] = X x W (rows = tokens,
+// lanes = output columns).
+template <bool SWAP>
+__device__ __forceinline__ void mma16(floatx16_t (&acc)[4][4], const Frags& f) {
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    if (kk < 3) load_frags(xf[(kk + 1) & 1], wf[(kk + 1) & 1], smem, STAGE, kk + 1, ad);
+  for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        if constexpr (SWAP)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[kk & 1][a], xf[kk & 1][b], acc[a][b], 0, 0, 0);
-        else
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf[kk & 1][a], wf[kk & 1][b], acc[a][b], 0, 0, 0);
-      }
-    __builtin_amdgcn_sched_barrier(0);
-  }
+    for (int b = 0; b < 4; ++b) {
+      if constexpr (SWAP)
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.w[a], f.x[b], acc[a][b], 0, 0, 0);
+      else
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.x[a], f.w[b], acc[a][b], 0, 0, 0);
+    }
 }
 
-// Full k-loop over d_in = D + m for one of the two products.  Ends with a
-// barrier, so the stage buffers are free when it returns.
+// scheduling-group masks of __builtin_amdgcn_sched_group_barrier
+#ifndef ECHOKV_NO_SGB
+#define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+#else
+#define SGB(mask, n)
+#endif
+constexpr int SG_VALU = 0x2, SG_MFMA = 0x8, SG_VMEM_RD = 0x20, SG_DS_RD = 0x100, SG_DS_WR = 0x200;
+
+// One k-tile (64 input dims) of the pipeline, for the LDS stage STAGE:
+//   step 0: MFMAs of k-step 0 | fragment reads of k-step 1 | tile kt+1: registers -> LDS (other stage)
+//   step 1: MFMAs of k-step 1 | fragment reads of k-step 2 | tile kt+2: global -> registers
+//   step 2: MFMAs of k-step 2 | fragment reads of k-step 3 ; barrier
+//   step 3: MFMAs of k-step 3 | fragment reads of k-step 0 of the next tile (other stage)
+// Each step is one scheduling region in which the memory and permute
+// instructions are dealt out between the MFMAs, so the matrix pipe does not
+// wait for them.  f0 holds the fragments of k-step 0 on entry and on exit.
+template <bool SWAP, bool STORE, bool FETCH>
+__device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags& f1, Stage& st,
+                                       char* smem, Addr& ad, const GOff& g,
+                                       const bf16_t* xa_tile, const bf16_t* xr_tile,
+                                       const bf16_t* w_tile, int D, int m, int d_out, int nka,
+                                       int kt) {
+  // ---- step 0
+  load_frags(f1, smem, 0, 1, ad);
+  if constexpr (STORE) {
+    store_x(st, smem, 0, ad);
+    store_w(st, smem, 0, ad);
+  }
+  mma16<SWAP>(acc, f0);
+  if constexpr (STORE) {
+    // LDS reads stay ahead of the LDS writes (the compiler must assume they
+    // may alias), and the writes keep their program order
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      SGB(SG_MFMA, 1);
+      SGB(SG_DS_RD, 2);
+      SGB(SG_VALU, 2);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      SGB(SG_MFMA, 1);
+      SGB(SG_DS_WR, 2);
+      SGB(SG_VALU, 3);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      SGB(SG_MFMA, 1);
+      SGB(SG_DS_WR, 1);
+      SGB(SG_VALU, 3);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      SGB(SG_MFMA, 1);
+      SGB(SG_DS_WR, 1);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      SGB(SG_MFMA, 1);
+      SGB(SG_DS_RD, 1);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- step 1
+  load_frags(f0, smem, 0, 2, ad);
+  if constexpr (FETCH) fetch_tile(st, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, kt + 2);
+  mma16<SWAP>(acc, f1);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    SGB(SG_MFMA, 1);
+    SGB(SG_DS_RD, 1);
+    if constexpr (FETCH) {
+      SGB(SG_VALU, 1);
+      SGB(SG_VMEM_RD, 1);
+    }
+  }
+  if constexpr (FETCH) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      SGB(SG_MFMA, 1);
+      SGB(SG_VMEM_RD, 1);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- step 2
+  load_frags(f1, smem, 0, 3, ad);
+  mma16<SWAP>(acc, f0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    SGB(SG_MFMA, 1);
+    SGB(SG_DS_RD, 1);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // every wave has read all it needs from STAGE and (STORE) finished writing the
+  // other stage; __syncthreads waits for this wave's LDS traffic first
+  __syncthreads();
+  // ---- step 3 (from here on "this stage" is the one just written)
+  toggle_stage(ad);
+  if constexpr (STORE) load_frags(f0, smem, 0, 0, ad);
+  mma16<SWAP>(acc, f1);
+  if constexpr (STORE) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      SGB(SG_MFMA, 1);
+      SGB(SG_DS_RD, 1);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// Full k-loop over d_in = D + m for one of the two products.  On return every
+// wave is past its last LDS read of the stage buffers' final tile only after
+// the caller's next barrier; the p / q / ml regions are never touched here.
 //   xa_tile / xr_tile: first row of the token tile in the anchor / retained cache
 //   last: index (in the tile) of the last valid row;  w_tile: W + n0
-// The loop body handles two k-tiles so that the LDS stage is a compile-time
-// constant (d_in / 64 is even or odd; an odd tail is peeled).
 template <bool SWAP>
 __device__ __forceinline__ void gemm_pass(floatx16_t (&acc)[4][4], char* smem, const Args& a,
                                           const bf16_t* xa_tile, const bf16_t* xr_tile,
                                           const bf16_t* w_tile, int last, int nclamp, int tid_in) {
-  // The LDS addresses are rebuilt for every pass from an opaque copy of the
-  // thread id: values that stayed live across the register-hungry epilogues
-  // would be spilled and reloaded inside the main loop.
+  // The per-thread addresses are rebuilt for every pass from an opaque copy of
+  // the thread id: values that stayed live across the register-hungry
+  // epilogues would be spilled and reloaded inside the main loop.
   int tid = tid_in;
   asm volatile("" : "+v"(tid));
   Addr ad;
   make_addr(ad, tid);
+  GOff g;
+  make_goff(g, tid, last, a.d_out, nclamp);
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  const int nk = (a.D + a.m) / BK;
-  const int nka = a.D / BK;
+  const int D = a.D, m = a.m, d_out = a.d_out;
+  const int nk = (D + m) / BK;
+  const int nka = D / BK;
   Stage st;
-  auto fetch = [&](int kn) {
-    if (kn < nka) load_x(st, xa_tile + kn * BK, a.D, last, tid);
-    else load_x(st, xr_tile + (kn - nka) * BK, a.m, last, tid);
-    load_w(st, w_tile + (int64_t)kn * BK * a.d_out, a.d_out, nclamp, tid);
-  };
-  fetch(0);
+  Frags f0, f1;
+  __syncthreads();     // the previous pass (or epilogue) is done with the stage buffers
+  fetch_tile(st, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, 0);
   store_x(st, smem, 0, ad);
   store_w(st, smem, 0, ad);
+  if (nk > 1) fetch_tile(st, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, 1);
   __syncthreads();
+  load_frags(f0, smem, 0, 0, ad);
+  // from now on: reads from stage 0, writes to stage 1
+#pragma unroll
+  for (int ip = 0; ip < 2; ++ip) ad.wx[ip] ^= kStageBytes;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) ad.ww[j] ^= kStageBytes;
+#define ECHOKV_KT(STORE, FETCH) \
+  k_tile<SWAP, STORE, FETCH>(acc, f0, f1, st, smem, ad, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, kt)
   int kt = 0;
-  for (; kt + 2 <= nk; kt += 2) {
-    fetch(kt + 1);
-    mma_tile<SWAP, 0>(acc, smem, ad);
-    store_x(st, smem, 1, ad);
-    store_w(st, smem, 1, ad);
-    __syncthreads();
-    const bool more = kt + 2 < nk;
-    if (more) fetch(kt + 2);
-    mma_tile<SWAP, 1>(acc, smem, ad);
-    if (more) {
-      store_x(st, smem, 0, ad);
-      store_w(st, smem, 0, ad);
-    }
-    __syncthreads();
+  for (; kt + 2 < nk; ++kt) ECHOKV_KT(true, true);
+  if (kt + 1 < nk) {
+    ECHOKV_KT(true, false);
+    ++kt;
   }
-  if (kt < nk) {          // odd tile count: last tile sits in stage 0
-    mma_tile<SWAP, 0>(acc, smem, ad);
-    __syncthreads();
-  }
+  ECHOKV_KT(false, false);
+#undef ECHOKV_KT
 }
 
 // Workgroup id -> (token tile, column tile).  Consecutive workgroup ids go to
