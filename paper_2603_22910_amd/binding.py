@@ -47,11 +47,12 @@ def load() -> C.CDLL:
     global _LIB
     if _LIB is not None:
         return _LIB
-    if not os.path.exists(LIB_PATH):
-        raise RuntimeError(f"{LIB_PATH} not found: build it with "
+    path = os.environ.get("ECHOKV_LIB", LIB_PATH)   # A/B builds of the same ABI
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} not found: build it with "
                            "`python -m paper_2603_22910_amd.build` (needs hipcc); "
                            "there is no CPU fallback")
-    lib = C.CDLL(LIB_PATH)
+    lib = C.CDLL(path)
     lib.echokv_status_string.restype = C.c_char_p
     lib.echokv_status_string.argtypes = [C.c_int]
     lib.echokv_workspace_bytes.restype = C.c_size_t

@@ -111,15 +111,15 @@ struct Stage {
 
 // Per-thread global offsets, fixed for a pass.
 struct GOff {
-  uint32_t xrow[8];   // clamped tile row of X load i
+  uint32_t r0;        // tile row of X load 0 (load i reads row min(r0 + 32 i, last))
+  uint32_t last;      // last valid row of the tile
   uint32_t xcol;      // byte offset of this thread's 16-byte chunk in a 128-byte k-slab
   uint32_t w0;        // byte offset of this thread's W block inside a k-tile of W
 };
 
 __device__ __forceinline__ void make_goff(GOff& g, int tid, int last, int d_out, int nclamp) {
-  const int r0 = tid >> 3;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) g.xrow[i] = (uint32_t)min(i * 32 + r0, last);
+  g.r0 = (uint32_t)(tid >> 3);
+  g.last = (uint32_t)last;
   g.xcol = (uint32_t)(tid & 7) * 16;
   const int nb = tid & 31, kb = tid >> 5;
   // column blocks past d_out are clamped onto the last valid block: the heads
@@ -127,20 +127,33 @@ __device__ __forceinline__ void make_goff(GOff& g, int tid, int last, int d_out,
   g.w0 = (uint32_t)(kb * 8) * (uint32_t)(d_out * 2) + (uint32_t)min(nb * 8, nclamp) * 2;
 }
 
-// Issue the 16 global loads of k-tile `kn`: uniform base + 32-bit per-thread offset.
-__device__ __forceinline__ void fetch_tile(Stage& s, const GOff& g, const bf16_t* xa_tile,
-                                           const bf16_t* xr_tile, const bf16_t* w_tile, int D,
-                                           int m, int d_out, int nka, int kn) {
+// Issue the global loads of k-tile `kn` (8 for X, 8 for W): uniform base +
+// 32-bit per-thread offset.
+__device__ __forceinline__ void fetch_x(Stage& s, const GOff& g, const bf16_t* xa_tile,
+                                        const bf16_t* xr_tile, int D, int m, int nka, int kn) {
+  // branch-free choice of the source (anchor dims first, then retained dims)
   const bool anchor = kn < nka;
-  const char* xb = reinterpret_cast<const char*>(anchor ? xa_tile + kn * BK : xr_tile + (kn - nka) * BK);
+  const uintptr_t pa = reinterpret_cast<uintptr_t>(xa_tile);
+  const uintptr_t pr = reinterpret_cast<uintptr_t>(xr_tile) - (uintptr_t)nka * (BK * 2);
+  typedef const __attribute__((address_space(1))) char* gptr_t;   // keep these global (not flat) loads
+  gptr_t xb = (gptr_t)((anchor ? pa : pr) + (uintptr_t)kn * (BK * 2));
   const uint32_t ld2 = (uint32_t)(anchor ? D : m) * 2;
 #pragma unroll
   for (int i = 0; i < 8; ++i)
-    s.x[i] = *reinterpret_cast<const u32x4_t*>(xb + (g.xrow[i] * ld2 + g.xcol));
+    s.x[i] = *(const __attribute__((address_space(1))) u32x4_t*)(xb + (min(g.r0 + 32u * i, g.last) * ld2 + g.xcol));
+}
+__device__ __forceinline__ void fetch_w(Stage& s, const GOff& g, const bf16_t* w_tile, int d_out,
+                                        int kn) {
   const char* wb = reinterpret_cast<const char*>(w_tile + (int64_t)kn * BK * d_out);
 #pragma unroll
   for (int i = 0; i < 8; ++i)
     s.w[i] = *reinterpret_cast<const u32x4_t*>(wb + (int64_t)i * d_out * 2 + g.w0);
+}
+__device__ __forceinline__ void fetch_tile(Stage& s, const GOff& g, const bf16_t* xa_tile,
+                                           const bf16_t* xr_tile, const bf16_t* w_tile, int D,
+                                           int m, int d_out, int nka, int kn) {
+  fetch_x(s, g, xa_tile, xr_tile, D, m, nka, kn);
+  fetch_w(s, g, w_tile, d_out, kn);
 }
 
 __device__ __forceinline__ void store_x(const Stage& s, char* smem, int stage, const Addr& ad) {
@@ -169,21 +182,11 @@ struct Frags {
   bf16x8_t x[4], w[4];
 };
 
-// Fragment-read addresses point into the stage being multiplied, write
-// addresses into the other one; both flip once per k-tile.
-__device__ __forceinline__ void toggle_stage(Addr& ad) {
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-    for (int ip = 0; ip < 2; ++ip) { ad.frx[kk][ip] ^= kStageBytes; ad.frw[kk][ip] ^= kStageBytes; }
-#pragma unroll
-  for (int ip = 0; ip < 2; ++ip) ad.wx[ip] ^= kStageBytes;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) ad.ww[j] ^= kStageBytes;
-}
-
 __device__ __forceinline__ void load_frags(Frags& f, const char* smem, int stage, int kk,
                                            const Addr& ad) {
+#if defined(ECHOKV_EXP_NOFRAG)
+  if (kk >= 0) return;
+#endif
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     f.x[i] = *reinterpret_cast<const bf16x8_t*>(smem + ad.frx[kk][i & 1] + (i >> 1) * 8192 + stage * kStageBytes);
@@ -196,6 +199,9 @@ __device__ __forceinline__ void load_frags(Frags& f, const char* smem, int stage
 // lanes = output columns).
 template <bool SWAP>
 __device__ __forceinline__ void mma16(floatx16_t (&acc)[4][4], const Frags& f) {
+#if defined(ECHOKV_EXP_NOMMA)
+  return;
+#endif
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -215,47 +221,55 @@ __device__ __forceinline__ void mma16(floatx16_t (&acc)[4][4], const Frags& f) {
 #endif
 constexpr int SG_VALU = 0x2, SG_MFMA = 0x8, SG_VMEM_RD = 0x20, SG_DS_RD = 0x100, SG_DS_WR = 0x200;
 
-// One k-tile (64 input dims) of the pipeline, for the LDS stage STAGE:
-//   step 0: MFMAs of k-step 0 | fragment reads of k-step 1 | tile kt+1: registers -> LDS (other stage)
-//   step 1: MFMAs of k-step 1 | fragment reads of k-step 2 | tile kt+2: global -> registers
-//   step 2: MFMAs of k-step 2 | fragment reads of k-step 3 ; barrier
-//   step 3: MFMAs of k-step 3 | fragment reads of k-step 0 of the next tile (other stage)
-// Each step is one scheduling region in which the memory and permute
-// instructions are dealt out between the MFMAs, so the matrix pipe does not
-// wait for them.  f0 holds the fragments of k-step 0 on entry and on exit.
-template <bool SWAP, bool STORE, bool FETCH>
+// One k-tile (64 input dims) of the pipeline, for the LDS stage STAGE.  Every
+// step issues 16 MFMAs, the 8 fragment reads of the next step and 8 memory
+// operations of the prefetch, dealt out between the MFMAs so that neither the
+// matrix pipe nor the memory queues see a burst:
+//   step 0: k-step 0 | X part of tile kt+1: registers -> LDS (other stage)
+//   step 1: k-step 1 | W part of tile kt+1: 8x8 transposes, registers -> LDS
+//   step 2: k-step 2 | X part of tile kt+3: global -> registers ; barrier
+//   step 3: k-step 3 | W part of tile kt+3: global -> registers ; first fragments of tile kt+1
+// f0 holds the fragments of k-step 0 on entry and on exit.
+template <bool SWAP, int STAGE, bool STORE, bool FETCH>
 __device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags& f1, Stage& st,
-                                       char* smem, Addr& ad, const GOff& g,
+                                       char* smem, const Addr& ad, const GOff& g,
                                        const bf16_t* xa_tile, const bf16_t* xr_tile,
                                        const bf16_t* w_tile, int D, int m, int d_out, int nka,
-                                       int kt) {
-  // ---- step 0
-  load_frags(f1, smem, 0, 1, ad);
-  if constexpr (STORE) {
-    store_x(st, smem, 0, ad);
-    store_w(st, smem, 0, ad);
-  }
+                                       int kfetch) {
+  // ---- step 0.  LDS reads stay ahead of the LDS writes (the compiler must
+  // assume they may alias), and the writes keep their program order.
+  load_frags(f1, smem, STAGE, 1, ad);
+  if constexpr (STORE) store_x(st, smem, STAGE ^ 1, ad);
   mma16<SWAP>(acc, f0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    SGB(SG_MFMA, 1);
+    SGB(SG_DS_RD, 1);
+  }
   if constexpr (STORE) {
-    // LDS reads stay ahead of the LDS writes (the compiler must assume they
-    // may alias), and the writes keep their program order
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      SGB(SG_MFMA, 1);
+      SGB(SG_DS_WR, 1);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // ---- step 1
+  load_frags(f0, smem, STAGE, 2, ad);
+  if constexpr (STORE) store_w(st, smem, STAGE ^ 1, ad);
+  mma16<SWAP>(acc, f1);
+  if constexpr (STORE) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       SGB(SG_MFMA, 1);
       SGB(SG_DS_RD, 2);
-      SGB(SG_VALU, 2);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      SGB(SG_MFMA, 1);
-      SGB(SG_DS_WR, 2);
-      SGB(SG_VALU, 3);
+      SGB(SG_VALU, 4);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       SGB(SG_MFMA, 1);
       SGB(SG_DS_WR, 1);
-      SGB(SG_VALU, 3);
+      SGB(SG_VALU, 4);
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -270,48 +284,37 @@ __device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags
     }
   }
   __builtin_amdgcn_sched_barrier(0);
-  // ---- step 1
-  load_frags(f0, smem, 0, 2, ad);
-  if constexpr (FETCH) fetch_tile(st, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, kt + 2);
+  // ---- step 2
+  load_frags(f1, smem, STAGE, 3, ad);
+  if constexpr (FETCH) fetch_x(st, g, xa_tile, xr_tile, D, m, nka, kfetch);
+  mma16<SWAP>(acc, f0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    SGB(SG_MFMA, 1);
+    SGB(SG_DS_RD, 1);
+    if constexpr (FETCH) {
+      SGB(SG_VALU, 3);
+      SGB(SG_MFMA, 1);
+      SGB(SG_VMEM_RD, 1);
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  // every wave has read all it needs from STAGE and (STORE) finished writing the
+  // other stage; __syncthreads waits for this wave's LDS traffic first
+#if !defined(ECHOKV_EXP_NOBARRIER)
+  __syncthreads();
+#endif
+  // ---- step 3
+  load_frags(f0, smem, STAGE ^ 1, 0, ad);
+  if constexpr (FETCH) fetch_w(st, g, w_tile, d_out, kfetch);
   mma16<SWAP>(acc, f1);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     SGB(SG_MFMA, 1);
     SGB(SG_DS_RD, 1);
     if constexpr (FETCH) {
-      SGB(SG_VALU, 1);
-      SGB(SG_VMEM_RD, 1);
-    }
-  }
-  if constexpr (FETCH) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
       SGB(SG_MFMA, 1);
       SGB(SG_VMEM_RD, 1);
-    }
-  }
-  __builtin_amdgcn_sched_barrier(0);
-  // ---- step 2
-  load_frags(f1, smem, 0, 3, ad);
-  mma16<SWAP>(acc, f0);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    SGB(SG_MFMA, 1);
-    SGB(SG_DS_RD, 1);
-  }
-  __builtin_amdgcn_sched_barrier(0);
-  // every wave has read all it needs from STAGE and (STORE) finished writing the
-  // other stage; __syncthreads waits for this wave's LDS traffic first
-  __syncthreads();
-  // ---- step 3 (from here on "this stage" is the one just written)
-  toggle_stage(ad);
-  if constexpr (STORE) load_frags(f0, smem, 0, 0, ad);
-  mma16<SWAP>(acc, f1);
-  if constexpr (STORE) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      SGB(SG_MFMA, 1);
-      SGB(SG_DS_RD, 1);
     }
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -325,7 +328,8 @@ __device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags
 template <bool SWAP>
 __device__ __forceinline__ void gemm_pass(floatx16_t (&acc)[4][4], char* smem, const Args& a,
                                           const bf16_t* xa_tile, const bf16_t* xr_tile,
-                                          const bf16_t* w_tile, int last, int nclamp, int tid_in) {
+                                          const bf16_t* w_tile, int last, int nclamp, int tid_in,
+                                          int rot) {
   // The per-thread addresses are rebuilt for every pass from an opaque copy of
   // the thread id: values that stayed live across the register-hungry
   // epilogues would be spilled and reloaded inside the main loop.
@@ -344,29 +348,43 @@ __device__ __forceinline__ void gemm_pass(floatx16_t (&acc)[4][4], char* smem, c
   const int D = a.D, m = a.m, d_out = a.d_out;
   const int nk = (D + m) / BK;
   const int nka = D / BK;
-  Stage st;
+  // Two register stages: k-tile t travels global -> sa (t even) / sb (t odd)
+  // -> LDS stage t & 1.  Tile t is fetched during tile t-3, written to LDS
+  // during tile t-1 and multiplied during tile t, so a global load has almost
+  // two tiles of MFMA time to land.  Fetch indices past the end are clamped
+  // (a redundant, harmless reload) so that every tile runs the same code.
+  Stage sa, sb;
   Frags f0, f1;
   __syncthreads();     // the previous pass (or epilogue) is done with the stage buffers
-  fetch_tile(st, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, 0);
-  store_x(st, smem, 0, ad);
-  store_w(st, smem, 0, ad);
-  if (nk > 1) fetch_tile(st, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, 1);
+  // k-tiles are visited in a rotated order (tile (i + rot) mod nk at step i):
+  // cache rows are a power of two bytes apart, so workgroups that walked the
+  // input dims in the same order would all pull from one memory channel at a time.
+  auto ktile = [&](int i) { const int t = min(i, nk - 1) + rot; return t >= nk ? t - nk : t; };
+  fetch_tile(sa, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(0));
+  store_x(sa, smem, 0, ad);
+  store_w(sa, smem, 0, ad);
+  fetch_tile(sb, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(1));
+  fetch_tile(sa, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(2));
   __syncthreads();
   load_frags(f0, smem, 0, 0, ad);
-  // from now on: reads from stage 0, writes to stage 1
-#pragma unroll
-  for (int ip = 0; ip < 2; ++ip) ad.wx[ip] ^= kStageBytes;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) ad.ww[j] ^= kStageBytes;
-#define ECHOKV_KT(STORE, FETCH) \
-  k_tile<SWAP, STORE, FETCH>(acc, f0, f1, st, smem, ad, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, kt)
+#if defined(ECHOKV_EXP_NOFETCH)
+#define ECHOKV_KT(STAGE, ST) \
+  k_tile<SWAP, STAGE, true, false>(acc, f0, f1, ST, smem, ad, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(kt + 3))
+#elif defined(ECHOKV_EXP_NOSTORE)
+#define ECHOKV_KT(STAGE, ST) \
+  k_tile<SWAP, STAGE, false, false>(acc, f0, f1, ST, smem, ad, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(kt + 3))
+#else
+#define ECHOKV_KT(STAGE, ST) \
+  k_tile<SWAP, STAGE, true, true>(acc, f0, f1, ST, smem, ad, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(kt + 3))
+#endif
   int kt = 0;
-  for (; kt + 2 < nk; ++kt) ECHOKV_KT(true, true);
-  if (kt + 1 < nk) {
-    ECHOKV_KT(true, false);
+  for (; kt + 1 < nk; kt += 2) {
+    ECHOKV_KT(0, sb);
     ++kt;
+    ECHOKV_KT(1, sa);
+    --kt;
   }
-  ECHOKV_KT(false, false);
+  if (kt < nk) ECHOKV_KT(0, sb);
 #undef ECHOKV_KT
 }
 
@@ -421,8 +439,14 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta 
   floatx16_t acc[4][4];
   // ---- K_hat^T = W_K^T X^T  (gemm_pass begins with loads and a barrier, which
   //      also publishes sm.q) ------------------------------------------------------
+  const int nk_all = (a.D + a.m) / BK;
+#if defined(ECHOKV_EXP_NOROT)
+  const int rot = 0;
+#else
+  const int rot = (ttile * 3) % nk_all;
+#endif
   gemm_pass<true>(acc, smem, a, a.xa[0] + row0 * a.D, a.xr[0] + row0 * a.m, a.w[0] + n0, last,
-                  nclamp, tid);
+                  nclamp, tid, rot);
   const int jw0 = j0 + wt * WM;                 // first token of this wave
 #pragma unroll
   for (int hw = 0; hw < HPW; ++hw) {
@@ -467,7 +491,7 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta 
   }
   // ---- V_hat = X W_V (its first barrier orders the p / ml writes above) -----------
   gemm_pass<false>(acc, smem, a, a.xa[1] + row0 * a.D, a.xr[1] + row0 * a.m, a.w[1] + n0, last,
-                   nclamp, tid);
+                   nclamp, tid, rot);
   if (jw0 >= L) return;                          // wave has no valid token: no partial
   const int slot = meta.sbase[b] + (jw0 / kSlotTokens);
 #pragma unroll
@@ -530,7 +554,7 @@ __global__ __launch_bounds__(NTHREADS) void recon_mfma_kernel(Args a, SeqMeta me
   const int nclamp = a.d_out - n0 - 8;
   floatx16_t acc[4][4];
   gemm_pass<false>(acc, smem, a, a.xa[which] + row0 * a.D, a.xr[which] + row0 * a.m,
-                   a.w[which] + n0, last, nclamp, tid);
+                   a.w[which] + n0, last, nclamp, tid, (ttile * 3) % ((a.D + a.m) / BK));
   bf16_t* out = a.out[which];
   const int64_t orow0 = (int64_t)meta.sbase[b] * kSlotTokens;
 #pragma unroll
