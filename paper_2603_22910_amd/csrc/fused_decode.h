@@ -127,33 +127,42 @@ __device__ __forceinline__ void make_goff(GOff& g, int tid, int last, int d_out,
   g.w0 = (uint32_t)(kb * 8) * (uint32_t)(d_out * 2) + (uint32_t)min(nb * 8, nclamp) * 2;
 }
 
-// Issue the global loads of k-tile `kn` (8 for X, 8 for W): uniform base +
-// 32-bit per-thread offset.
-__device__ __forceinline__ void fetch_x(Stage& s, const GOff& g, const bf16_t* xa_tile,
-                                        const bf16_t* xr_tile, int D, int m, int nka, int kn) {
-  // branch-free choice of the source (anchor dims first, then retained dims)
+// Global loads go through raw buffer instructions: a 128-bit resource
+// (uniform base) + a 32-bit per-thread byte offset + a uniform byte offset, so
+// no 64-bit address arithmetic is spent per load.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
+  // raw buffer, no stride, byte-granular range check far beyond any offset used here
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+}
+struct Src {
+  rsrc_t xa, xr, w;    // anchor tile rows, retained tile rows, W + n0
+};
+
+// Issue the global loads of k-tile `kn` (8 for X, 8 for W).
+__device__ __forceinline__ void fetch_x(Stage& s, const GOff& g, const Src& src, int D, int m,
+                                        int nka, int kn) {
+  // anchor dims first, then retained dims (Eq. 3); uniform selects, no branch
   const bool anchor = kn < nka;
-  const uintptr_t pa = reinterpret_cast<uintptr_t>(xa_tile);
-  const uintptr_t pr = reinterpret_cast<uintptr_t>(xr_tile) - (uintptr_t)nka * (BK * 2);
-  typedef const __attribute__((address_space(1))) char* gptr_t;   // keep these global (not flat) loads
-  gptr_t xb = (gptr_t)((anchor ? pa : pr) + (uintptr_t)kn * (BK * 2));
   const uint32_t ld2 = (uint32_t)(anchor ? D : m) * 2;
+  const int soff = (anchor ? kn : kn - nka) * (BK * 2);
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
-    s.x[i] = *(const __attribute__((address_space(1))) u32x4_t*)(xb + (min(g.r0 + 32u * i, g.last) * ld2 + g.xcol));
+  for (int i = 0; i < 8; ++i) {
+    const uint32_t voff = __umul24(min(g.r0 + 32u * i, g.last), ld2) + g.xcol;   // row < 256, ld2 < 2^24
+    s.x[i] = anchor ? __builtin_amdgcn_raw_buffer_load_b128(src.xa, voff, soff, 0)
+                    : __builtin_amdgcn_raw_buffer_load_b128(src.xr, voff, soff, 0);
+  }
 }
-__device__ __forceinline__ void fetch_w(Stage& s, const GOff& g, const bf16_t* w_tile, int d_out,
+__device__ __forceinline__ void fetch_w(Stage& s, const GOff& g, const Src& src, int d_out,
                                         int kn) {
-  const char* wb = reinterpret_cast<const char*>(w_tile + (int64_t)kn * BK * d_out);
 #pragma unroll
   for (int i = 0; i < 8; ++i)
-    s.w[i] = *reinterpret_cast<const u32x4_t*>(wb + (int64_t)i * d_out * 2 + g.w0);
+    s.w[i] = __builtin_amdgcn_raw_buffer_load_b128(src.w, g.w0, (kn * BK + i) * d_out * 2, 0);
 }
-__device__ __forceinline__ void fetch_tile(Stage& s, const GOff& g, const bf16_t* xa_tile,
-                                           const bf16_t* xr_tile, const bf16_t* w_tile, int D,
-                                           int m, int d_out, int nka, int kn) {
-  fetch_x(s, g, xa_tile, xr_tile, D, m, nka, kn);
-  fetch_w(s, g, w_tile, d_out, kn);
+__device__ __forceinline__ void fetch_tile(Stage& s, const GOff& g, const Src& src, int D, int m,
+                                           int d_out, int nka, int kn) {
+  fetch_x(s, g, src, D, m, nka, kn);
+  fetch_w(s, g, src, d_out, kn);
 }
 
 __device__ __forceinline__ void store_x(const Stage& s, char* smem, int stage, const Addr& ad) {
@@ -232,10 +241,8 @@ constexpr int SG_VALU = 0x2, SG_MFMA = 0x8, SG_VMEM_RD = 0x20, SG_DS_RD = 0x100,
 // f0 holds the fragments of k-step 0 on entry and on exit.
 template <bool SWAP, int STAGE, bool STORE, bool FETCH>
 __device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags& f1, Stage& st,
-                                       char* smem, const Addr& ad, const GOff& g,
-                                       const bf16_t* xa_tile, const bf16_t* xr_tile,
-                                       const bf16_t* w_tile, int D, int m, int d_out, int nka,
-                                       int kfetch) {
+                                       char* smem, const Addr& ad, const GOff& g, const Src& src,
+                                       int D, int m, int d_out, int nka, int kfetch) {
   // ---- step 0.  LDS reads stay ahead of the LDS writes (the compiler must
   // assume they may alias), and the writes keep their program order.
   load_frags(f1, smem, STAGE, 1, ad);
@@ -286,7 +293,7 @@ __device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags
   __builtin_amdgcn_sched_barrier(0);
   // ---- step 2
   load_frags(f1, smem, STAGE, 3, ad);
-  if constexpr (FETCH) fetch_x(st, g, xa_tile, xr_tile, D, m, nka, kfetch);
+  if constexpr (FETCH) fetch_x(st, g, src, D, m, nka, kfetch);
   mma16<SWAP>(acc, f0);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -306,7 +313,7 @@ __device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags
 #endif
   // ---- step 3
   load_frags(f0, smem, STAGE ^ 1, 0, ad);
-  if constexpr (FETCH) fetch_w(st, g, w_tile, d_out, kfetch);
+  if constexpr (FETCH) fetch_w(st, g, src, d_out, kfetch);
   mma16<SWAP>(acc, f1);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -360,22 +367,24 @@ __device__ __forceinline__ void gemm_pass(floatx16_t (&acc)[4][4], char* smem, c
   // cache rows are a power of two bytes apart, so workgroups that walked the
   // input dims in the same order would all pull from one memory channel at a time.
   auto ktile = [&](int i) { const int t = min(i, nk - 1) + rot; return t >= nk ? t - nk : t; };
-  fetch_tile(sa, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(0));
+  Src src;
+  src.xa = make_rsrc(xa_tile); src.xr = make_rsrc(xr_tile); src.w = make_rsrc(w_tile);
+  fetch_tile(sa, g, src, D, m, d_out, nka, ktile(0));
   store_x(sa, smem, 0, ad);
   store_w(sa, smem, 0, ad);
-  fetch_tile(sb, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(1));
-  fetch_tile(sa, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(2));
+  fetch_tile(sb, g, src, D, m, d_out, nka, ktile(1));
+  fetch_tile(sa, g, src, D, m, d_out, nka, ktile(2));
   __syncthreads();
   load_frags(f0, smem, 0, 0, ad);
 #if defined(ECHOKV_EXP_NOFETCH)
 #define ECHOKV_KT(STAGE, ST) \
-  k_tile<SWAP, STAGE, true, false>(acc, f0, f1, ST, smem, ad, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(kt + 3))
+  k_tile<SWAP, STAGE, true, false>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, ktile(kt + 3))
 #elif defined(ECHOKV_EXP_NOSTORE)
 #define ECHOKV_KT(STAGE, ST) \
-  k_tile<SWAP, STAGE, false, false>(acc, f0, f1, ST, smem, ad, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(kt + 3))
+  k_tile<SWAP, STAGE, false, false>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, ktile(kt + 3))
 #else
 #define ECHOKV_KT(STAGE, ST) \
-  k_tile<SWAP, STAGE, true, true>(acc, f0, f1, ST, smem, ad, g, xa_tile, xr_tile, w_tile, D, m, d_out, nka, ktile(kt + 3))
+  k_tile<SWAP, STAGE, true, true>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, ktile(kt + 3))
 #endif
   int kt = 0;
   for (; kt + 1 < nk; kt += 2) {
