@@ -272,6 +272,13 @@ int reconstruct_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_
   return ECHOKV_OK;
 }
 
+// bf16: the MFMA attention kernel keeps its softmax state in registers, so only
+// the materialised predicted dims live in the workspace; the fp32 streaming
+// path also needs split-K partials for one launch of query rows.
+int64_t prefill_part_slots(const Dims& dm, int64_t Ltot, int max_q) {
+  const bool mfma = dm.bf16 && prefill_mfma_supported<bf16_t>(dm.d);
+  return mfma ? 0 : (int64_t)std::min(max_q, kPrefillQChunk) * slots_for(Ltot);
+}
 // Prefill: predicted dims of the whole visible context are rebuilt once into
 // the workspace (every query tile reuses them), then causal attention runs
 // over retained heads (from the cache) and predicted heads (from the workspace).
@@ -282,9 +289,7 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
   const int n_ret_heads = dm.m / dm.d, n_rec_heads = dm.H_kv - n_ret_heads;
   const int Ltot = q_pos0 + T_q;
   const int64_t row0 = an->seq_start[seq];
-  const int qchunk = std::min(T_q, kPrefillQChunk);
-  const WsPlan wp = plan_ws(dm, (int64_t)qchunk * slots_for(Ltot),
-                            n_rec_heads ? (int64_t)slots_for(Ltot) * kSlotTokens : 0);
+  const WsPlan wp = plan_ws(dm, prefill_part_slots(dm, Ltot, T_q), (int64_t)slots_for(Ltot) * kSlotTokens);
   float* po = (float*)(ws + wp.off_po);
   float* pml = (float*)(ws + wp.off_pml);
   T* kh = (T*)(ws + wp.off_kh);
@@ -355,8 +360,7 @@ size_t decode_ws_bytes(const Dims& dm, int batch, int64_t total_tokens, bool unf
   return plan_ws(dm, slots, unfused ? slots * kSlotTokens : 0).total;
 }
 size_t prefill_ws_bytes(const Dims& dm, int64_t Ltot, int max_q) {
-  const int qchunk = std::min(max_q, kPrefillQChunk);
-  return plan_ws(dm, (int64_t)qchunk * slots_for(Ltot), (int64_t)slots_for(Ltot) * kSlotTokens).total;
+  return plan_ws(dm, prefill_part_slots(dm, Ltot, max_q), (int64_t)slots_for(Ltot) * kSlotTokens).total;
 }
 
 }  // namespace

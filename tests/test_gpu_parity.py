@@ -263,3 +263,28 @@ def test_decode_full_size_sampled(cfg):
     check(np.stack(gots), np.stack(refs), "bf16", f"{w.name} full-size sampled")
     # properties that hold at any size: finite lse, |out| bounded by max |V| scale
     assert np.isfinite(got_lse).all()
+
+
+@pytest.mark.parametrize("q_pos0", [0, 3000])
+def test_prefill_full_size_sampled(q_pos0):
+    """The benchmark's 8192-query causal chunk on the 7B-shaped layer (50% retention);
+    a sample of query rows is checked against the oracle, all heads."""
+    from oracle import echokv_oracle as orc
+    T_q = 8192
+    w = synth.CONFIGS[4].scaled(batch=0, seq_lens=(300,), prefill_len=q_pos0 + T_q, prefill_q=T_q)
+    inp = synth.generate(w)
+    dw = DeviceWorkload(inp)
+    out, lse = dw.prefill(); torch.cuda.synchronize()
+    got, got_lse = host(out), host(lse)
+    assert np.isfinite(got).all()
+    b = inp.n_decode
+    K_a, V_a, K_r, V_r = ref.seq_arrays(inp, b)
+    W_K, W_V = ref.weights(inp)
+    K_t = orc.reconstruct(K_a, K_r, W_K); V_t = orc.reconstruct(V_a, V_r, W_V)
+    rng = np.random.default_rng(5)
+    idx = sorted({0, 1, 63, 64, 127, 128, T_q - 1, *rng.integers(0, T_q, 40).tolist()})
+    Q = ref.f64(inp.q_prefill)[idx]
+    o_ref, l_ref, _ = orc.attention_rows(Q, K_t, V_t, w.n_kv_heads,
+                                         visible=[q_pos0 + i + 1 for i in idx])
+    check(got[idx], o_ref, "bf16", f"prefill full size q_pos0={q_pos0}")
+    assert np.abs(got_lse[idx] - l_ref).max() <= 2e-2
