@@ -71,11 +71,14 @@ def cpu_baseline(inp, min_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", type=int, default=1, help="benchmark configuration index (0-4)")
     ap.add_argument("--unfused", action="store_true", help="time the unfused comparison path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain 1 GiB device copies (known HBM traffic) so a counter "
+                         "run of this command can scale FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding or collectives); "
@@ -88,8 +91,6 @@ def main():
     from paper_2603_22910_amd.harness import DeviceWorkload
 
     w = synth.CONFIGS[args.config]
-    if w.prefill_len:
-        w = w.scaled(prefill_len=0, prefill_q=0)   # decode leg only
     inp = synth.generate(w)
     flags = ek.FLAG_UNFUSED if args.unfused else 0
     dw = DeviceWorkload(inp, flags=flags)
@@ -110,12 +111,21 @@ def main():
     ones = [1] * B
     full_len = dw.anchor.seq_len.copy()
 
-    def step():
+    has_prefill = inp.q_prefill is not None
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def step(timed=False):
         dw.anchor.seq_len[:] = full_len - 1
         ek.cache_append(dw.shape, dw.anchor, ka_new, va_new, ones)
         dw.target.seq_len[:] = full_len - 1
         ek.cache_append(dw.shape, dw.target, kt_new, vt_new, ones)
         dw.decode()
+        if has_prefill:            # the configuration's causal prefill chunk rides in the same step
+            if timed:
+                ev[0].record()
+            dw.prefill()
+            if timed:
+                ev[1].record()
 
     for _ in range(args.warmup):
         step()
@@ -123,20 +133,32 @@ def main():
     ek.profile_enable(True)
     ek.profile_read()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
+    for i in range(args.steps):
+        step(timed=(i == args.steps - 1))
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    prefill_ms = ev[0].elapsed_time(ev[1]) if has_prefill else None
+    if has_prefill:
+        tokens += inp.seq_len[inp.n_decode]      # the chunk's context counts as processed tokens
     kern_ms, launches = ek.profile_read()
     ek.profile_enable(False)
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=dev)     # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ms_per_step = dt * 1e3 / args.steps
     value = tokens / (dt / args.steps)
 
     # roofline of the dominant kernel (the fused predictor product + attention):
     # algorithmic work = 4 * d_in * d_out flop per cached token (K and V products)
-    flops = 4.0 * w.d_in * w.d_out * tokens
-    bytes_alg = tokens * 2.0 * w.d_in * w.elem_size + 2.0 * w.d_in * w.d_out * w.elem_size
+    dec_tokens = inp.total_decode_tokens
+    flops = 4.0 * w.d_in * w.d_out * dec_tokens
+    bytes_alg = dec_tokens * 2.0 * w.d_in * w.elem_size + 2.0 * w.d_in * w.d_out * w.elem_size
     roofline = None
     if launches > 0 and kern_ms > 0:
         k_s = kern_ms / launches * 1e-3
@@ -157,7 +179,9 @@ def main():
                    "H_q": w.n_q_heads, "H_kv": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_retained": w.n_retained, "d_in": w.d_in, "d_out": w.d_out,
                    "path": "unfused" if args.unfused else "fused",
-                   "step": "cache_append(anchor)+cache_append(target)+decode_attn"},
+                   "step": "cache_append(anchor)+cache_append(target)+decode_attn"
+                           + ("+prefill_attn" if has_prefill else ""),
+                   "prefill_ms_last_step": prefill_ms},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -57,7 +57,7 @@ typedef struct {
   int32_t n_q_heads;   /* H_q */
   int32_t n_kv_heads;  /* H_kv; H_q % H_kv == 0 */
   int32_t head_dim;    /* d; 64 or 128 */
-  int32_t n_retained;  /* m, flattened dims the target keeps; 0 < m <= D, m % d == 0 */
+  int32_t n_retained;  /* m, flattened dims the target keeps; 0 <= m <= D, m % d == 0 */
   int32_t dtype;       /* echokv_dtype of cache, weights and queries */
   int32_t out_dtype;   /* echokv_dtype of `out`; accumulation is always fp32 */
   float softmax_scale; /* <= 0 selects 1/sqrt(d) (Appendix "Analysis of QK-KL

@@ -210,17 +210,26 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
         }
         if (rc) return rc;
       } else {
-        GemmArgs<T> g;
-        g.xa[0] = (const T*)an->k; g.xa[1] = (const T*)an->v;
-        g.xr[0] = (const T*)tg->k; g.xr[1] = (const T*)tg->v;
-        g.w[0] = (const T*)w_k; g.w[1] = (const T*)w_v;
-        g.out[0] = (T*)(ws + wp.off_kh); g.out[1] = (T*)(ws + wp.off_vh);
-        g.D = dm.D; g.m = dm.m; g.d_out = dm.d_out; g.ldo = dm.d_out; g.col0 = 0;
-        g.rows_from_slots = 1;
-        int rc = launch_recon_fma<T>(dm, g, mt, st);
+        T* kh = (T*)(ws + wp.off_kh);
+        T* vh = (T*)(ws + wp.off_vh);
+        int rc;
+        if (recon_mfma_supported<T>()) {
+          rc = launch_recon_mfma<T>(dm.D, dm.m, (const T*)an->k, (const T*)an->v, (const T*)tg->k,
+                                    (const T*)tg->v, (const T*)w_k, (const T*)w_v, kh, vh,
+                                    dm.d_out, 0, mt, st);
+        } else {
+          GemmArgs<T> g;
+          g.xa[0] = (const T*)an->k; g.xa[1] = (const T*)an->v;
+          g.xr[0] = (const T*)tg->k; g.xr[1] = (const T*)tg->v;
+          g.w[0] = (const T*)w_k; g.w[1] = (const T*)w_v;
+          g.out[0] = kh; g.out[1] = vh;
+          g.D = dm.D; g.m = dm.m; g.d_out = dm.d_out; g.ldo = dm.d_out; g.col0 = 0;
+          g.rows_from_slots = 1;
+          rc = launch_recon_fma<T>(dm, g, mt, st);
+        }
         if (rc) return rc;
         AttnArgs<T> a;
-        a.k = g.out[0]; a.v = g.out[1]; a.ld = dm.d_out; a.col0 = 0; a.head0 = n_ret_heads;
+        a.k = kh; a.v = vh; a.ld = dm.d_out; a.col0 = 0; a.head0 = n_ret_heads;
         a.row_mode = 1; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
         a.split_tokens = pick_split_tokens(tokens, n_rec_heads);
         a.part_o = po; a.part_ml = pml;
