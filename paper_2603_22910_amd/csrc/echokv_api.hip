@@ -94,7 +94,12 @@ constexpr int kPrefillQChunk = kMaxSeqPerLaunch;   // queries per launch, stream
 // Optional event pairs around the dominant decode kernel (echokv_profile_*).
 struct Profiler {
   bool on = false;
-  std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs;   // recorded, not yet read
+  std::vector<hipEvent_t> pool;                           // created once, reused
+  bool get(hipEvent_t* e) {
+    if (!pool.empty()) { *e = pool.back(); pool.pop_back(); return true; }
+    return hipEventCreate(e) == hipSuccess;
+  }
 };
 Profiler g_prof;
 
@@ -197,7 +202,7 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
       if (fused) {
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (g_prof.on) {
-          HIP_TRY(hipEventCreate(&e0)); HIP_TRY(hipEventCreate(&e1));
+          if (!g_prof.get(&e0) || !g_prof.get(&e1)) return ECHOKV_ERR_HIP;
           HIP_TRY(hipEventRecord(e0, st));
         }
         int rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.scale,
@@ -414,7 +419,7 @@ int echokv_profile_read(double* total_ms, int64_t* launches) {
     if (hipEventSynchronize(pr.second) != hipSuccess ||
         hipEventElapsedTime(&ms, pr.first, pr.second) != hipSuccess) rc = ECHOKV_ERR_HIP;
     else { tot += ms; ++n; }
-    (void)hipEventDestroy(pr.first); (void)hipEventDestroy(pr.second);
+    g_prof.pool.push_back(pr.first); g_prof.pool.push_back(pr.second);
   }
   g_prof.pairs.clear();
   *total_ms = tot; *launches = n;

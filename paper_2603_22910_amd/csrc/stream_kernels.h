@@ -283,41 +283,66 @@ struct MergeArgs {
 template <typename TO>
 __global__ __launch_bounds__(256) void merge_kernel(MergeArgs<TO> a, SeqMeta meta) {
   const int h = blockIdx.x, b = blockIdx.y;
-  const int nslot = meta.sbase[b + 1] - meta.sbase[b];
   const int step = (h / a.G < a.n_stream_kv_heads) ? a.stream_step : a.fused_step;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int dpl = a.d >> 6;   // dims per lane: 1 (d=64) or 2 (d=128)
-  float M = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f;
-  for (int s = wave * step; s < nslot; s += 4 * step) {
-    const int64_t ph = (int64_t)(meta.sbase[b] + s) * a.H_q + h;
-    const float ms = a.part_ml[ph * 2], ls = a.part_ml[ph * 2 + 1];
-    const float x0 = a.part_o[ph * a.d + lane * dpl];
-    const float x1 = (dpl == 2) ? a.part_o[ph * a.d + lane * dpl + 1] : 0.f;
-    const float mn = fmaxf(M, ms);
-    const float c0 = (M == -INFINITY) ? 0.f : __expf(M - mn);
-    const float c1 = (ms == -INFINITY) ? 0.f : __expf(ms - mn);
-    l = l * c0 + ls * c1; o0 = o0 * c0 + x0 * c1; o1 = o1 * c0 + x1 * c1;
-    M = mn;
-  }
-  __shared__ float s_m[4], s_l[4], s_o[4][128];
-  if (lane == 0) { s_m[wave] = M; s_l[wave] = l; }
-  s_o[wave][lane * dpl] = o0;
-  if (dpl == 2) s_o[wave][lane * dpl + 1] = o1;
+  const int n = (meta.sbase[b + 1] - meta.sbase[b] + step - 1) / step;   // partials of this head
+  const int64_t slot0 = meta.sbase[b];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ float s_red[4];
+  __shared__ float s_w[256];
+  __shared__ float s_acc[8][128];
+  // 1. global max of the partial maxima (all partials' maxima are finite)
+  float M = -INFINITY;
+  for (int i = tid; i < n; i += 256)
+    M = fmaxf(M, a.part_ml[((slot0 + (int64_t)i * step) * a.H_q + h) * 2]);
+  M = wave_max(M, 64);
+  if (lane == 0) s_red[wave] = M;
   __syncthreads();
-  if (threadIdx.x < a.d) {
-    const int c = threadIdx.x;
-    const float MM = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
-    float ll = 0.f, acc = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float e = (s_m[w] == -INFINITY) ? 0.f : __expf(s_m[w] - MM);
-      ll += s_l[w] * e; acc += s_o[w][c] * e;
+  M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+  // 2. weighted sums, 256 partials at a time: weights exp(m_s - M) go to LDS, then
+  //    8 groups of 32 threads (4 head dims each) add up the weighted o rows with
+  //    independent, coalesced loads
+  const int grp = tid >> 5, q4 = (tid & 31) * 4;
+  const bool dim_ok = q4 < a.d;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float lsum = 0.f;
+  for (int c0 = 0; c0 < n; c0 += 256) {
+    const int i = c0 + tid;
+    float w = 0.f;
+    if (i < n) {
+      const int64_t ph = (slot0 + (int64_t)i * step) * a.H_q + h;
+      w = __expf(a.part_ml[ph * 2] - M);
+      lsum += w * a.part_ml[ph * 2 + 1];
     }
+    __syncthreads();            // previous chunk's weights are no longer read
+    s_w[tid] = w;
+    __syncthreads();
+    const int cn = min(256, n - c0);
+    if (dim_ok) {
+#pragma unroll 4
+      for (int j = grp; j < cn; j += 8) {
+        const int64_t ph = (slot0 + (int64_t)(c0 + j) * step) * a.H_q + h;
+        const float4 o = *reinterpret_cast<const float4*>(a.part_o + ph * a.d + q4);
+        const float wj = s_w[j];
+        acc.x = fmaf(wj, o.x, acc.x); acc.y = fmaf(wj, o.y, acc.y);
+        acc.z = fmaf(wj, o.z, acc.z); acc.w = fmaf(wj, o.w, acc.w);
+      }
+    }
+  }
+  lsum = wave_sum(lsum, 64);
+  __syncthreads();
+  if (lane == 0) s_red[wave] = lsum;
+  if (dim_ok) *reinterpret_cast<float4*>(&s_acc[grp][q4]) = acc;
+  __syncthreads();
+  if (tid < a.d) {
+    const float ll = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+    float r = 0.f;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) r += s_acc[g][tid];
+    r /= ll;
     const int64_t oh = (a.out_seq0 + b) * a.H_q + h;
-    const float r = acc / ll;
-    if constexpr (sizeof(TO) == 2) a.out[oh * a.d + c] = f32_to_bf16(r);
-    else a.out[oh * a.d + c] = r;
-    if (c == 0 && a.lse) a.lse[oh] = MM + __logf(ll);
+    if constexpr (sizeof(TO) == 2) a.out[oh * a.d + tid] = f32_to_bf16(r);
+    else a.out[oh * a.d + tid] = r;
+    if (tid == 0 && a.lse) a.lse[oh] = M + __logf(ll);
   }
 }
 
