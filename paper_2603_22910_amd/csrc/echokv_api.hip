@@ -12,6 +12,7 @@
 #include "common.h"
 #include "stream_kernels.h"
 #include "fused_decode.h"
+#include "fused_decode_f32.h"
 #include "prefill_kernels.h"
 
 using namespace echokv;
@@ -205,10 +206,17 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
           if (!g_prof.get(&e0) || !g_prof.get(&e1)) return ECHOKV_ERR_HIP;
           HIP_TRY(hipEventRecord(e0, st));
         }
-        int rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.scale,
-                                        (const T*)an->k, (const T*)an->v, (const T*)tg->k,
-                                        (const T*)tg->v, (const T*)w_k, (const T*)w_v, qq, po,
-                                        pml, mt, &fused_step, st);
+        int rc;
+        if constexpr (sizeof(T) == 4)
+          rc = launch_fused_decode_f32(dm.H_q, dm.H_kv, dm.d, dm.m, dm.scale, (const float*)an->k,
+                                       (const float*)an->v, (const float*)tg->k, (const float*)tg->v,
+                                       (const float*)w_k, (const float*)w_v, qq, po, pml, mt,
+                                       &fused_step, st);
+        else
+          rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.scale,
+                                      (const T*)an->k, (const T*)an->v, (const T*)tg->k,
+                                      (const T*)tg->v, (const T*)w_k, (const T*)w_v, qq, po,
+                                      pml, mt, &fused_step, st);
         if (g_prof.on) {
           HIP_TRY(hipEventRecord(e1, st));
           g_prof.pairs.emplace_back(e0, e1);

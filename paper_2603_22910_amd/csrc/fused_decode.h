@@ -59,12 +59,16 @@ struct Args {
 // carries no address arithmetic.
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-struct Smem {
-  char x[2][BM * BK * 2];
-  char w[2][BN * BK * 2];
+// LDS state of the attention epilogues (shared by the bf16 and fp32 kernels)
+struct EpiSmem {
   float q[BN * MAXPAIR];               // [(head in tile * G + g)][d], pre-scaled
   float p[4][MAXPAIR][128];            // per wave and pair: softmax numerators of its 128 tokens
   float ml[4][MAXPAIR][2];             // per wave and pair: max and sum
+};
+struct Smem {
+  char x[2][BM * BK * 2];
+  char w[2][BN * BK * 2];
+  EpiSmem e;
 };
 constexpr int kStageBytes = BM * BK * 2;          // one stage of x (same for w)
 constexpr int kWBase = 2 * kStageBytes;           // offset of Smem::w from Smem::x
@@ -409,58 +413,32 @@ __device__ __forceinline__ bool tile_of_block(const Args& a, int& ttile, int& ct
   return true;
 }
 
-template <int HD>
-__global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta meta) {
-  __shared__ Smem sm;
-  char* smem = reinterpret_cast<char*>(&sm);
-  constexpr int HPW = WN / HD;       // heads per wave tile
-  constexpr int CBH = HD / 32;       // 32-column blocks per head
-  int ttile, ctile;
-  if (!tile_of_block(a, ttile, ctile)) return;
-  const int b = find_seq(meta.tbase, meta.n, ttile);
-  const int L = meta.len[b];
-  const int j0 = (ttile - meta.tbase[b]) * BM;
-  const int n0 = ctile * BN;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wt = wave >> 1, wc = wave & 1;
-  const int lr = lane & 31, lh = lane >> 5;
-  const int G = a.G;
-  const int H_kv = a.H_q / G;
-
-  // rows past the end of the sequence are clamped onto its last valid token,
-  // so that masked tokens still contribute finite numbers
-  const int last = min(BM, L - j0) - 1;
-  const int64_t row0 = meta.start[b] + j0;
-  const int nclamp = a.d_out - n0 - 8;     // last readable 8-column block of this tile
-  // queries of this tile's heads, pre-scaled, as fp32
-  {
-    const int kvh0 = a.n_ret_heads + n0 / HD;
-    for (int idx = tid; idx < (BN / HD) * G * HD; idx += NTHREADS) {
-      const int c = idx % HD, pg = idx / HD;       // pg = head_in_tile * G + g
-      const int kvh = kvh0 + pg / G;
-      float v = 0.f;
-      if (kvh < H_kv)
-        v = bf16_to_f32(a.q[((int64_t)b * a.H_q + kvh * G + pg % G) * HD + c]) * a.scale;
-      sm.q[pg * HD + c] = v;
-    }
+// Queries of the tile's heads -> LDS as fp32, pre-scaled by the softmax scale.
+template <int HD, typename T>
+__device__ __forceinline__ void load_queries(EpiSmem& e, const T* q, int b, int H_q, int G,
+                                             int kvh0, float scale, int tid) {
+  const int H_kv = H_q / G;
+  for (int idx = tid; idx < (BN / HD) * G * HD; idx += NTHREADS) {
+    const int c = idx % HD, pg = idx / HD;       // pg = head_in_tile * G + g
+    const int kvh = kvh0 + pg / G;
+    float v = 0.f;
+    if (kvh < H_kv) v = Elem<T>::to_f32(q[((int64_t)b * H_q + kvh * G + pg % G) * HD + c]) * scale;
+    e.q[pg * HD + c] = v;
   }
+}
 
-  floatx16_t acc[4][4];
-  // ---- K_hat^T = W_K^T X^T  (gemm_pass begins with loads and a barrier, which
-  //      also publishes sm.q) ------------------------------------------------------
-  const int nk_all = (a.D + a.m) / BK;
-#if defined(ECHOKV_EXP_NOROT)
-  const int rot = 0;
-#else
-  const int rot = (ttile * 3) % nk_all;
-#endif
-  gemm_pass<true>(acc, smem, a, a.xa[0] + row0 * a.D, a.xr[0] + row0 * a.m, a.w[0] + n0, last,
-                  nclamp, tid, rot);
-  const int jw0 = j0 + wt * WM;                 // first token of this wave
+// After the K pass: acc[ci][ji] holds K_hat^T (rows = head dims of the wave's
+// 128 columns, lanes = tokens).  Scores (Eq. 7), masked beyond L, then the
+// wave's softmax numerators -> e.p, (max, sum) -> e.ml, per (head, query head).
+template <int HD>
+__device__ __forceinline__ void k_epilogue(const floatx16_t (&acc)[4][4], EpiSmem& e, int G,
+                                           int wave, int lane, int jw0, int L) {
+  constexpr int HPW = WN / HD, CBH = HD / 32;
+  const int wc = wave & 1, lr = lane & 31, lh = lane >> 5;
 #pragma unroll
   for (int hw = 0; hw < HPW; ++hw) {
     for (int g = 0; g < G; ++g) {
-      const float* qs = &sm.q[((wc * HPW + hw) * G + g) * HD];
+      const float* qs = &e.q[((wc * HPW + hw) * G + g) * HD];
       float s[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int cb = 0; cb < CBH; ++cb) {
@@ -487,7 +465,7 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta 
       }
       mx = wave_max(mx, 32);
       float sum = 0.f;
-      float* pp = sm.p[wave][hw * G + g];
+      float* pp = e.p[wave][hw * G + g];
 #pragma unroll
       for (int ji = 0; ji < 4; ++ji) {
         const float p = (s[ji] == -INFINITY) ? 0.f : __expf(s[ji] - mx);
@@ -495,20 +473,26 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta 
         if (lh == 0) pp[ji * 32 + lr] = p;
       }
       sum = wave_sum(sum, 32);
-      if (lane == 0) { sm.ml[wave][hw * G + g][0] = mx; sm.ml[wave][hw * G + g][1] = sum; }
+      if (lane == 0) { e.ml[wave][hw * G + g][0] = mx; e.ml[wave][hw * G + g][1] = sum; }
     }
   }
-  // ---- V_hat = X W_V (its first barrier orders the p / ml writes above) -----------
-  gemm_pass<false>(acc, smem, a, a.xa[1] + row0 * a.D, a.xr[1] + row0 * a.m, a.w[1] + n0, last,
-                   nclamp, tid, rot);
-  if (jw0 >= L) return;                          // wave has no valid token: no partial
-  const int slot = meta.sbase[b] + (jw0 / kSlotTokens);
+}
+
+// After the V pass: acc[ji][ci] holds V_hat (rows = tokens, lanes = head dims).
+// sum_j p_j v_hat_j per (head, query head) -> one split-K partial per wave.
+template <int HD>
+__device__ __forceinline__ void v_epilogue(const floatx16_t (&acc)[4][4], const EpiSmem& e, int G,
+                                           int wave, int lane, int slot, int H_q, int kvh_wave0,
+                                           float* part_o, float* part_ml) {
+  constexpr int HPW = WN / HD, CBH = HD / 32;
+  const int lr = lane & 31, lh = lane >> 5;
+  const int H_kv = H_q / G;
 #pragma unroll
   for (int hw = 0; hw < HPW; ++hw) {
-    const int kvh = a.n_ret_heads + (n0 + wc * WN) / HD + hw;
+    const int kvh = kvh_wave0 + hw;
     if (kvh >= H_kv) continue;
     for (int g = 0; g < G; ++g) {
-      const float* pp = sm.p[wave][hw * G + g];
+      const float* pp = e.p[wave][hw * G + g];
       float o[CBH];
 #pragma unroll
       for (int cb = 0; cb < CBH; ++cb) o[cb] = 0.f;
@@ -528,18 +512,53 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta 
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      const int64_t ph = (int64_t)slot * a.H_q + kvh * G + g;
+      const int64_t ph = (int64_t)slot * H_q + kvh * G + g;
 #pragma unroll
       for (int cb = 0; cb < CBH; ++cb) {
         o[cb] += __shfl_xor(o[cb], 32, 64);
-        if (lh == 0) a.part_o[ph * HD + cb * 32 + lr] = o[cb];
+        if (lh == 0) part_o[ph * HD + cb * 32 + lr] = o[cb];
       }
       if (lane == 0) {
-        a.part_ml[ph * 2] = sm.ml[wave][hw * G + g][0];
-        a.part_ml[ph * 2 + 1] = sm.ml[wave][hw * G + g][1];
+        part_ml[ph * 2] = e.ml[wave][hw * G + g][0];
+        part_ml[ph * 2 + 1] = e.ml[wave][hw * G + g][1];
       }
     }
   }
+}
+
+template <int HD>
+__global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta meta) {
+  __shared__ Smem sm;
+  char* smem = reinterpret_cast<char*>(&sm);
+  int ttile, ctile;
+  if (!tile_of_block(a, ttile, ctile)) return;
+  const int b = find_seq(meta.tbase, meta.n, ttile);
+  const int L = meta.len[b];
+  const int j0 = (ttile - meta.tbase[b]) * BM;
+  const int n0 = ctile * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wt = wave >> 1, wc = wave & 1;
+
+  // rows past the end of the sequence are clamped onto its last valid token,
+  // so that masked tokens still contribute finite numbers
+  const int last = min(BM, L - j0) - 1;
+  const int64_t row0 = meta.start[b] + j0;
+  const int nclamp = a.d_out - n0 - 8;     // last readable 8-column block of this tile
+  load_queries<HD>(sm.e, a.q, b, a.H_q, a.G, a.n_ret_heads + n0 / HD, a.scale, tid);
+
+  floatx16_t acc[4][4];
+  const int rot = (ttile * 3) % ((a.D + a.m) / BK);
+  // ---- K_hat^T = W_K^T X^T (gemm_pass begins with a barrier, which publishes e.q)
+  gemm_pass<true>(acc, smem, a, a.xa[0] + row0 * a.D, a.xr[0] + row0 * a.m, a.w[0] + n0, last,
+                  nclamp, tid, rot);
+  const int jw0 = j0 + wt * WM;                 // first token of this wave
+  k_epilogue<HD>(acc, sm.e, a.G, wave, lane, jw0, L);
+  // ---- V_hat = X W_V (e.p / e.ml are wave-private; the pass's barriers order them anyway)
+  gemm_pass<false>(acc, smem, a, a.xa[1] + row0 * a.D, a.xr[1] + row0 * a.m, a.w[1] + n0, last,
+                   nclamp, tid, rot);
+  if (jw0 >= L) return;                          // wave has no valid token: no partial
+  v_epilogue<HD>(acc, sm.e, a.G, wave, lane, meta.sbase[b] + jw0 / kSlotTokens, a.H_q,
+                 a.n_ret_heads + (n0 + wc * WN) / HD, a.part_o, a.part_ml);
 }
 
 // Stand-alone predictor product (Eq. 3) with the same main loop: K_hat or V_hat
@@ -585,7 +604,7 @@ __global__ __launch_bounds__(NTHREADS) void recon_mfma_kernel(Args a, SeqMeta me
 
 // ---- host-side launchers ------------------------------------------------------------
 template <typename T> inline bool fused_decode_supported(int d, int G) {
-  return sizeof(T) == 2 && (d == 64 || d == 128) && (128 / d) * G <= fused::MAXPAIR;
+  return (d == 64 || d == 128) && (128 / d) * G <= fused::MAXPAIR;
 }
 template <typename T> inline bool recon_mfma_supported() { return sizeof(T) == 2; }
 
