@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", type=int, default=1, help="benchmark configuration index (0-4)")
     ap.add_argument("--unfused", action="store_true", help="time the unfused comparison path")
+    ap.add_argument("--packed-weights", action="store_true",
+                    help="lay W_K/W_V out once with echokv_pack_weights before the timed region")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 1 GiB device copies (known HBM traffic) so a counter "
@@ -94,6 +96,8 @@ def main():
     inp = synth.generate(w)
     flags = ek.FLAG_UNFUSED if args.unfused else 0
     dw = DeviceWorkload(inp, flags=flags)
+    if args.packed_weights:
+        dw.pack_weights()
     dev = dw.dev
     B = inp.n_decode
     tokens = inp.total_decode_tokens
@@ -179,6 +183,7 @@ def main():
                    "H_q": w.n_q_heads, "H_kv": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_retained": w.n_retained, "d_in": w.d_in, "d_out": w.d_out,
                    "path": "unfused" if args.unfused else "fused",
+                   "weights": "packed [d_out,d_in]" if args.packed_weights else "row-major [d_in,d_out]",
                    "step": "cache_append(anchor)+cache_append(target)+decode_attn"
                            + ("+prefill_attn" if has_prefill else ""),
                    "prefill_ms_last_step": prefill_ms},

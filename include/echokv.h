@@ -51,6 +51,10 @@ typedef enum { ECHOKV_BF16 = 0, ECHOKV_F32 = 1 } echokv_dtype;
 /* flags for echokv_shape.flags */
 #define ECHOKV_FLAG_UNFUSED 1u /* decode: materialise the predicted dims in the
                                   workspace, then attend (comparison path) */
+#define ECHOKV_FLAG_W_PACKED 2u /* w_k / w_v point at weights laid out by
+                                  echokv_pack_weights ([D - m, D + m]); honoured by
+                                  echokv_decode_attn on the fused bf16 path, every
+                                  other use returns ECHOKV_ERR_UNSUPPORTED */
 
 /* One (anchor, target) layer pair. */
 typedef struct {
@@ -104,6 +108,16 @@ int echokv_reconstruct(const echokv_shape *shape, const echokv_layer_cache *anch
                        const echokv_layer_cache *target, const void *w_k,
                        const void *w_v, int32_t seq, int32_t tok_begin,
                        int32_t tok_end, void *k_out, void *v_out, void *hip_stream);
+
+/* One-time re-layout of a predictor weight matrix (Eq. 3) for the decode
+ * kernel: w_packed[c, k] = w[k, c], i.e. [D - m, D + m] row-major, each output
+ * column's input dims contiguous.  The weights of a layer are constant while
+ * serving, so a caller packs them once at load time and passes the packed
+ * pointers with ECHOKV_FLAG_W_PACKED set.
+ *   w        : device [D + m, D - m] row-major
+ *   w_packed : device [D - m, D + m], same dtype, must not overlap w */
+int echokv_pack_weights(const echokv_shape *shape, const void *w, void *w_packed,
+                        void *hip_stream);
 
 /* Bytes of workspace that echokv_decode_attn (batch sequences holding
  * total_tokens cached tokens in all) or echokv_prefill_attn (one sequence with

@@ -18,10 +18,11 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libechokv.s
 OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_CAPACITY, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = range(8)
 BF16, F32 = 0, 1
 FLAG_UNFUSED = 1
+FLAG_W_PACKED = 2
 
 EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn",
-           "echokv_profile_enable", "echokv_profile_read")
+           "echokv_profile_enable", "echokv_profile_read", "echokv_pack_weights")
 
 
 class EchoKVError(RuntimeError):
@@ -73,6 +74,8 @@ def load() -> C.CDLL:
                                         C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_int32,
                                         C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.echokv_pack_weights.restype = C.c_int
+    lib.echokv_pack_weights.argtypes = [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p]
     lib.echokv_profile_enable.restype = C.c_int
     lib.echokv_profile_enable.argtypes = [C.c_int]
     lib.echokv_profile_read.restype = C.c_int
@@ -189,6 +192,11 @@ def prefill_attn(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v,
                                       seq, _ptr(q), T_q, q_pos0, _ptr(out), _ptr(lse_out),
                                       _ptr(workspace), nbytes, _stream(stream)),
            "echokv_prefill_attn")
+
+
+def pack_weights(shape: Shape, w, w_packed, stream=None):
+    _check(load().echokv_pack_weights(C.byref(shape), _ptr(w), _ptr(w_packed), _stream(stream)),
+           "echokv_pack_weights")
 
 
 def profile_enable(on: bool):

@@ -216,7 +216,7 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
           rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.scale,
                                       (const T*)an->k, (const T*)an->v, (const T*)tg->k,
                                       (const T*)tg->v, (const T*)w_k, (const T*)w_v, qq, po,
-                                      pml, mt, &fused_step, st);
+                                      pml, mt, &fused_step, st, (flags & ECHOKV_FLAG_W_PACKED) != 0);
         if (g_prof.on) {
           HIP_TRY(hipEventRecord(e1, st));
           g_prof.pairs.emplace_back(e0, e1);
@@ -412,6 +412,22 @@ size_t echokv_workspace_bytes(const echokv_shape* shape, int32_t batch, int64_t 
   return need;
 }
 
+int echokv_pack_weights(const echokv_shape* shape, const void* w, void* w_packed,
+                        void* hip_stream) {
+  Dims dm;
+  int rc = check_shape(shape, &dm);
+  if (rc) return rc;
+  if (dm.d_out == 0) return ECHOKV_OK;
+  if (!w || !w_packed) return ECHOKV_ERR_NULL;
+  if (w == w_packed) return ECHOKV_ERR_SHAPE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  dim3 grid((dm.d_out + 63) / 64, (dm.d_in + 63) / 64);
+  if (dm.bf16) hipLaunchKernelGGL((transpose_kernel<bf16_t>), grid, dim3(256), 0, st, (const bf16_t*)w, (bf16_t*)w_packed, dm.d_in, dm.d_out);
+  else hipLaunchKernelGGL((transpose_kernel<float>), grid, dim3(256), 0, st, (const float*)w, (float*)w_packed, dm.d_in, dm.d_out);
+  LAUNCH_CHECK();
+  return ECHOKV_OK;
+}
+
 int echokv_profile_enable(int on) {
   g_prof.on = on != 0;
   return ECHOKV_OK;
@@ -490,6 +506,7 @@ int echokv_reconstruct(const echokv_shape* shape, const echokv_layer_cache* anch
   if (rc) return rc;
   rc = check_pair(dm, anchor, target);
   if (rc) return rc;
+  if (shape->flags & ECHOKV_FLAG_W_PACKED) return ECHOKV_ERR_UNSUPPORTED;
   if (seq < 0 || seq >= anchor->batch) return ECHOKV_ERR_SHAPE;
   if (tok_begin < 0 || tok_end < tok_begin || tok_end > anchor->seq_len[seq]) return ECHOKV_ERR_SHAPE;
   if (dm.d_out > 0 && (!w_k || !w_v)) return ECHOKV_ERR_NULL;
@@ -520,6 +537,9 @@ int echokv_decode_attn(const echokv_shape* shape, const echokv_layer_cache* anch
     }
     max_chunk_slots = std::max(max_chunk_slots, s);
   }
+  if ((shape->flags & ECHOKV_FLAG_W_PACKED) &&
+      ((shape->flags & ECHOKV_FLAG_UNFUSED) || !dm.bf16 || !fused_decode_supported<bf16_t>(dm.d, dm.G)))
+    return ECHOKV_ERR_UNSUPPORTED;
   const bool unfused = (shape->flags & ECHOKV_FLAG_UNFUSED) ||
                        !(dm.bf16 ? fused_decode_supported<bf16_t>(dm.d, dm.G)
                                  : fused_decode_supported<float>(dm.d, dm.G));
@@ -540,6 +560,7 @@ int echokv_prefill_attn(const echokv_shape* shape, const echokv_layer_cache* anc
   if (rc) return rc;
   rc = check_pair(dm, anchor, target);
   if (rc) return rc;
+  if (shape->flags & ECHOKV_FLAG_W_PACKED) return ECHOKV_ERR_UNSUPPORTED;
   if (seq < 0 || seq >= anchor->batch) return ECHOKV_ERR_SHAPE;
   if (T_q <= 0 || q_pos0 < 0) return ECHOKV_ERR_SHAPE;
   if ((int64_t)q_pos0 + T_q > anchor->seq_len[seq]) return ECHOKV_ERR_SHAPE;

@@ -119,6 +119,7 @@ struct GOff {
   uint32_t last;      // last valid row of the tile
   uint32_t xcol;      // byte offset of this thread's 16-byte chunk in a 128-byte k-slab
   uint32_t w0;        // byte offset of this thread's W block inside a k-tile of W
+  uint32_t wlast;     // packed weights: last valid row (output column) of the W^T tile
 };
 
 __device__ __forceinline__ void make_goff(GOff& g, int tid, int last, int d_out, int nclamp) {
@@ -129,6 +130,7 @@ __device__ __forceinline__ void make_goff(GOff& g, int tid, int last, int d_out,
   // column blocks past d_out are clamped onto the last valid block: the heads
   // they would feed are skipped in the epilogue, they only need to be readable
   g.w0 = (uint32_t)(kb * 8) * (uint32_t)(d_out * 2) + (uint32_t)min(nb * 8, nclamp) * 2;
+  g.wlast = (uint32_t)min(BN - 1, nclamp + 7);
 }
 
 // Global loads go through raw buffer instructions: a 128-bit resource
@@ -157,16 +159,31 @@ __device__ __forceinline__ void fetch_x(Stage& s, const GOff& g, const Src& src,
                     : __builtin_amdgcn_raw_buffer_load_b128(src.xr, voff, soff, 0);
   }
 }
-__device__ __forceinline__ void fetch_w(Stage& s, const GOff& g, const Src& src, int d_out,
-                                        int kn) {
+// PACKED: the weights were transposed once to [d_out, d_in] (echokv_pack_weights),
+// so a W^T tile is fetched exactly like an X tile: rows = output columns, 64
+// input dims contiguous.  Otherwise W is [d_in, d_out] and every thread
+// fetches an 8 (k) x 8 (n) block that store_w transposes on the way to LDS.
+template <bool PACKED>
+__device__ __forceinline__ void fetch_w(Stage& s, const GOff& g, const Src& src, int d_in,
+                                        int d_out, int kn) {
+  if constexpr (PACKED) {
+    const uint32_t ld2 = (uint32_t)d_in * 2;
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
-    s.w[i] = __builtin_amdgcn_raw_buffer_load_b128(src.w, g.w0, (kn * BK + i) * d_out * 2, 0);
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t voff = __umul24(min(g.r0 + 32u * i, g.wlast), ld2) + g.xcol;
+      s.w[i] = __builtin_amdgcn_raw_buffer_load_b128(src.w, voff, kn * (BK * 2), 0);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      s.w[i] = __builtin_amdgcn_raw_buffer_load_b128(src.w, g.w0, (kn * BK + i) * d_out * 2, 0);
+  }
 }
+template <bool PACKED>
 __device__ __forceinline__ void fetch_tile(Stage& s, const GOff& g, const Src& src, int D, int m,
                                            int d_out, int nka, int kn) {
   fetch_x(s, g, src, D, m, nka, kn);
-  fetch_w(s, g, src, d_out, kn);
+  fetch_w<PACKED>(s, g, src, D + m, d_out, kn);
 }
 
 __device__ __forceinline__ void store_x(const Stage& s, char* smem, int stage, const Addr& ad) {
@@ -178,7 +195,14 @@ __device__ __forceinline__ void store_x(const Stage& s, char* smem, int stage, c
 // 8x8 transpose of 16-bit elements held as 8 rows (k) of 4 dwords (8 n), then
 // 8 row writes: LDS row n (a W column) gets its 8 consecutive k values.
 // One byte-permute per output dword.
+template <bool PACKED>
 __device__ __forceinline__ void store_w(const Stage& s, char* smem, int stage, const Addr& ad) {
+  if constexpr (PACKED) {      // rows arrive k-contiguous: same placement as an X tile
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      *reinterpret_cast<u32x4_t*>(smem + ad.wx[i & 1] + (i >> 1) * 8192 + kWBase + stage * kStageBytes) = s.w[i];
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     u32x4_t o;
@@ -243,7 +267,7 @@ constexpr int SG_VALU = 0x2, SG_MFMA = 0x8, SG_VMEM_RD = 0x20, SG_DS_RD = 0x100,
 //   step 2: k-step 2 | X part of tile kt+3: global -> registers ; barrier
 //   step 3: k-step 3 | W part of tile kt+3: global -> registers ; first fragments of tile kt+1
 // f0 holds the fragments of k-step 0 on entry and on exit.
-template <bool SWAP, int STAGE, bool STORE, bool FETCH>
+template <bool SWAP, bool PACKED, int STAGE, bool STORE, bool FETCH>
 __device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags& f1, Stage& st,
                                        char* smem, const Addr& ad, const GOff& g, const Src& src,
                                        int D, int m, int d_out, int nka, int kfetch) {
@@ -267,9 +291,20 @@ __device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags
   __builtin_amdgcn_sched_barrier(0);
   // ---- step 1
   load_frags(f0, smem, STAGE, 2, ad);
-  if constexpr (STORE) store_w(st, smem, STAGE ^ 1, ad);
+  if constexpr (STORE) store_w<PACKED>(st, smem, STAGE ^ 1, ad);
   mma16<SWAP>(acc, f1);
-  if constexpr (STORE) {
+  if constexpr (STORE && PACKED) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      SGB(SG_MFMA, 1);
+      SGB(SG_DS_RD, 1);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      SGB(SG_MFMA, 1);
+      SGB(SG_DS_WR, 1);
+    }
+  } else if constexpr (STORE) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       SGB(SG_MFMA, 1);
@@ -317,13 +352,14 @@ __device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags
 #endif
   // ---- step 3
   load_frags(f0, smem, STAGE ^ 1, 0, ad);
-  if constexpr (FETCH) fetch_w(st, g, src, d_out, kfetch);
+  if constexpr (FETCH) fetch_w<PACKED>(st, g, src, D + m, d_out, kfetch);
   mma16<SWAP>(acc, f1);
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     SGB(SG_MFMA, 1);
     SGB(SG_DS_RD, 1);
     if constexpr (FETCH) {
+      if constexpr (PACKED) SGB(SG_VALU, 3);
       SGB(SG_MFMA, 1);
       SGB(SG_VMEM_RD, 1);
     }
@@ -336,20 +372,54 @@ __device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags
 // the caller's next barrier; the p / q / ml regions are never touched here.
 //   xa_tile / xr_tile: first row of the token tile in the anchor / retained cache
 //   last: index (in the tile) of the last valid row;  w_tile: W + n0
-template <bool SWAP>
+// What a pass needs to address its operands; rebuilt per pass (see gemm_pass).
+struct PassIo {
+  GOff g;
+  Src src;
+  int nk, nka, rot;
+  // k-tiles are visited in a rotated order (tile (i + rot) mod nk at step i):
+  // cache rows are a power of two bytes apart, so workgroups that walked the
+  // input dims in the same order would all pull from one memory channel at a
+  // time.  Indices past the end are clamped (a redundant, harmless reload) so
+  // that every tile runs the same code.
+  __device__ __forceinline__ int ktile(int i) const {
+    const int t = min(i, nk - 1) + rot;
+    return t >= nk ? t - nk : t;
+  }
+};
+
+__device__ __forceinline__ void make_io(PassIo& io, const Args& a, const bf16_t* xa_tile,
+                                        const bf16_t* xr_tile, const bf16_t* w_tile, int last,
+                                        int nclamp, int tid_in, int rot) {
+  // built from an opaque copy of the thread id: values that stayed live across
+  // the register-hungry epilogues would be spilled and reloaded inside the main loop
+  int tid = tid_in;
+  asm volatile("" : "+v"(tid));
+  make_goff(io.g, tid, last, a.d_out, nclamp);
+  io.src.xa = make_rsrc(xa_tile); io.src.xr = make_rsrc(xr_tile); io.src.w = make_rsrc(w_tile);
+  io.nk = (a.D + a.m) / BK; io.nka = a.D / BK; io.rot = rot;
+}
+
+// Issue the global loads of a pass's first k-tile.  Called before the
+// previous pass's epilogue so that their latency hides behind it.
+template <bool PACKED>
+__device__ __forceinline__ void pass_prefetch(Stage& sa, const PassIo& io, const Args& a) {
+  fetch_tile<PACKED>(sa, io.g, io.src, a.D, a.m, a.d_out, io.nka, io.ktile(0));
+}
+
+// Full k-loop over d_in = D + m for one of the two products; sa holds (or is
+// about to receive) k-tile 0.
+// Two register stages: k-tile t travels global -> sa (t even) / sb (t odd)
+// -> LDS stage t & 1.  Tile t is fetched during tile t-3, written to LDS
+// during tile t-1 and multiplied during tile t, so a global load has almost
+// two tiles of MFMA time to land.
+template <bool SWAP, bool PACKED>
 __device__ __forceinline__ void gemm_pass(floatx16_t (&acc)[4][4], char* smem, const Args& a,
-                                          const bf16_t* xa_tile, const bf16_t* xr_tile,
-                                          const bf16_t* w_tile, int last, int nclamp, int tid_in,
-                                          int rot) {
-  // The per-thread addresses are rebuilt for every pass from an opaque copy of
-  // the thread id: values that stayed live across the register-hungry
-  // epilogues would be spilled and reloaded inside the main loop.
+                                          const PassIo& io, Stage& sa, Stage& sb, int tid_in) {
   int tid = tid_in;
   asm volatile("" : "+v"(tid));
   Addr ad;
   make_addr(ad, tid);
-  GOff g;
-  make_goff(g, tid, last, a.d_out, nclamp);
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -357,38 +427,26 @@ __device__ __forceinline__ void gemm_pass(floatx16_t (&acc)[4][4], char* smem, c
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   const int D = a.D, m = a.m, d_out = a.d_out;
-  const int nk = (D + m) / BK;
-  const int nka = D / BK;
-  // Two register stages: k-tile t travels global -> sa (t even) / sb (t odd)
-  // -> LDS stage t & 1.  Tile t is fetched during tile t-3, written to LDS
-  // during tile t-1 and multiplied during tile t, so a global load has almost
-  // two tiles of MFMA time to land.  Fetch indices past the end are clamped
-  // (a redundant, harmless reload) so that every tile runs the same code.
-  Stage sa, sb;
+  const int nk = io.nk, nka = io.nka;
+  const GOff& g = io.g;
+  const Src& src = io.src;
   Frags f0, f1;
-  __syncthreads();     // the previous pass (or epilogue) is done with the stage buffers
-  // k-tiles are visited in a rotated order (tile (i + rot) mod nk at step i):
-  // cache rows are a power of two bytes apart, so workgroups that walked the
-  // input dims in the same order would all pull from one memory channel at a time.
-  auto ktile = [&](int i) { const int t = min(i, nk - 1) + rot; return t >= nk ? t - nk : t; };
-  Src src;
-  src.xa = make_rsrc(xa_tile); src.xr = make_rsrc(xr_tile); src.w = make_rsrc(w_tile);
-  fetch_tile(sa, g, src, D, m, d_out, nka, ktile(0));
+  __syncthreads();     // the previous pass is done with the stage buffers
+  fetch_tile<PACKED>(sb, g, src, D, m, d_out, nka, io.ktile(1));
   store_x(sa, smem, 0, ad);
-  store_w(sa, smem, 0, ad);
-  fetch_tile(sb, g, src, D, m, d_out, nka, ktile(1));
-  fetch_tile(sa, g, src, D, m, d_out, nka, ktile(2));
+  store_w<PACKED>(sa, smem, 0, ad);
+  fetch_tile<PACKED>(sa, g, src, D, m, d_out, nka, io.ktile(2));
   __syncthreads();
   load_frags(f0, smem, 0, 0, ad);
 #if defined(ECHOKV_EXP_NOFETCH)
 #define ECHOKV_KT(STAGE, ST) \
-  k_tile<SWAP, STAGE, true, false>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, ktile(kt + 3))
+  k_tile<SWAP, PACKED, STAGE, true, false>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, io.ktile(kt + 3))
 #elif defined(ECHOKV_EXP_NOSTORE)
 #define ECHOKV_KT(STAGE, ST) \
-  k_tile<SWAP, STAGE, false, false>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, ktile(kt + 3))
+  k_tile<SWAP, PACKED, STAGE, false, false>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, io.ktile(kt + 3))
 #else
 #define ECHOKV_KT(STAGE, ST) \
-  k_tile<SWAP, STAGE, true, true>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, ktile(kt + 3))
+  k_tile<SWAP, PACKED, STAGE, true, true>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, io.ktile(kt + 3))
 #endif
   int kt = 0;
   for (; kt + 1 < nk; kt += 2) {
@@ -430,14 +488,26 @@ __device__ __forceinline__ void load_queries(EpiSmem& e, const T* q, int b, int 
 // After the K pass: acc[ci][ji] holds K_hat^T (rows = head dims of the wave's
 // 128 columns, lanes = tokens).  Scores (Eq. 7), masked beyond L, then the
 // wave's softmax numerators -> e.p, (max, sum) -> e.ml, per (head, query head).
+// Keeps the accumulators in the accumulation registers for the duration of an
+// epilogue loop body: without it the compiler copies all 256 of them to
+// ordinary registers ahead of the loop over query heads and spills whatever
+// else is live (e.g. a prefetched k-tile).
+__device__ __forceinline__ void pin_acc(floatx16_t (&acc)[4][4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) asm volatile("" : "+a"(acc[i][j]));
+}
+
 template <int HD>
-__device__ __forceinline__ void k_epilogue(const floatx16_t (&acc)[4][4], EpiSmem& e, int G,
+__device__ __forceinline__ void k_epilogue(floatx16_t (&acc)[4][4], EpiSmem& e, int G,
                                            int wave, int lane, int jw0, int L) {
   constexpr int HPW = WN / HD, CBH = HD / 32;
   const int wc = wave & 1, lr = lane & 31, lh = lane >> 5;
 #pragma unroll
   for (int hw = 0; hw < HPW; ++hw) {
     for (int g = 0; g < G; ++g) {
+      pin_acc(acc);
       const float* qs = &e.q[((wc * HPW + hw) * G + g) * HD];
       float s[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -481,7 +551,7 @@ __device__ __forceinline__ void k_epilogue(const floatx16_t (&acc)[4][4], EpiSme
 // After the V pass: acc[ji][ci] holds V_hat (rows = tokens, lanes = head dims).
 // sum_j p_j v_hat_j per (head, query head) -> one split-K partial per wave.
 template <int HD>
-__device__ __forceinline__ void v_epilogue(const floatx16_t (&acc)[4][4], const EpiSmem& e, int G,
+__device__ __forceinline__ void v_epilogue(floatx16_t (&acc)[4][4], const EpiSmem& e, int G,
                                            int wave, int lane, int slot, int H_q, int kvh_wave0,
                                            float* part_o, float* part_ml) {
   constexpr int HPW = WN / HD, CBH = HD / 32;
@@ -492,6 +562,7 @@ __device__ __forceinline__ void v_epilogue(const floatx16_t (&acc)[4][4], const 
     const int kvh = kvh_wave0 + hw;
     if (kvh >= H_kv) continue;
     for (int g = 0; g < G; ++g) {
+      pin_acc(acc);
       const float* pp = e.p[wave][hw * G + g];
       float o[CBH];
 #pragma unroll
@@ -526,7 +597,7 @@ __device__ __forceinline__ void v_epilogue(const floatx16_t (&acc)[4][4], const 
   }
 }
 
-template <int HD>
+template <int HD, bool PACKED>
 __global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta meta) {
   __shared__ Smem sm;
   char* smem = reinterpret_cast<char*>(&sm);
@@ -548,14 +619,21 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta 
 
   floatx16_t acc[4][4];
   const int rot = (ttile * 3) % ((a.D + a.m) / BK);
+  // W tile base: column n0 of row-major W, or row n0 of the packed transpose
+  const int64_t woff = PACKED ? (int64_t)n0 * (a.D + a.m) : n0;
+  Stage sa, sb;
+  PassIo io;
   // ---- K_hat^T = W_K^T X^T (gemm_pass begins with a barrier, which publishes e.q)
-  gemm_pass<true>(acc, smem, a, a.xa[0] + row0 * a.D, a.xr[0] + row0 * a.m, a.w[0] + n0, last,
-                  nclamp, tid, rot);
+  make_io(io, a, a.xa[0] + row0 * a.D, a.xr[0] + row0 * a.m, a.w[0] + woff, last, nclamp, tid, rot);
+  pass_prefetch<PACKED>(sa, io, a);
+  gemm_pass<true, PACKED>(acc, smem, a, io, sa, sb, tid);
+  // the V pass's first tiles are requested now and land while the scores are worked out
+  make_io(io, a, a.xa[1] + row0 * a.D, a.xr[1] + row0 * a.m, a.w[1] + woff, last, nclamp, tid, rot);
+  pass_prefetch<PACKED>(sa, io, a);
   const int jw0 = j0 + wt * WM;                 // first token of this wave
   k_epilogue<HD>(acc, sm.e, a.G, wave, lane, jw0, L);
   // ---- V_hat = X W_V (e.p / e.ml are wave-private; the pass's barriers order them anyway)
-  gemm_pass<false>(acc, smem, a, a.xa[1] + row0 * a.D, a.xr[1] + row0 * a.m, a.w[1] + n0, last,
-                   nclamp, tid, rot);
+  gemm_pass<false, PACKED>(acc, smem, a, io, sa, sb, tid);
   if (jw0 >= L) return;                          // wave has no valid token: no partial
   v_epilogue<HD>(acc, sm.e, a.G, wave, lane, meta.sbase[b] + jw0 / kSlotTokens, a.H_q,
                  a.n_ret_heads + (n0 + wc * WN) / HD, a.part_o, a.part_ml);
@@ -581,8 +659,12 @@ __global__ __launch_bounds__(NTHREADS) void recon_mfma_kernel(Args a, SeqMeta me
   const int64_t row0 = meta.start[b] + j0;
   const int nclamp = a.d_out - n0 - 8;
   floatx16_t acc[4][4];
-  gemm_pass<false>(acc, smem, a, a.xa[which] + row0 * a.D, a.xr[which] + row0 * a.m,
-                   a.w[which] + n0, last, nclamp, tid, (ttile * 3) % ((a.D + a.m) / BK));
+  Stage sa, sb;
+  PassIo io;
+  make_io(io, a, a.xa[which] + row0 * a.D, a.xr[which] + row0 * a.m, a.w[which] + n0, last, nclamp,
+          tid, (ttile * 3) % ((a.D + a.m) / BK));
+  pass_prefetch<false>(sa, io, a);
+  gemm_pass<false, false>(acc, smem, a, io, sa, sb, tid);
   bf16_t* out = a.out[which];
   const int64_t orow0 = (int64_t)meta.sbase[b] * kSlotTokens;
 #pragma unroll
@@ -619,7 +701,7 @@ template <typename T>
 inline int launch_fused_decode(int H_q, int H_kv, int d, int m, float scale, const T* ka,
                                const T* va, const T* kr, const T* vr, const T* wk, const T* wv,
                                const T* q, float* part_o, float* part_ml, SeqMeta& mt,
-                               int* fused_step, hipStream_t st) {
+                               int* fused_step, hipStream_t st, bool packed = false) {
   if constexpr (sizeof(T) != 2) {
     return 6;
   } else {
@@ -632,8 +714,11 @@ inline int launch_fused_decode(int H_q, int H_kv, int d, int m, float scale, con
     a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;
     a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
     const int grid = ((a.n_tiles + 7) / 8) * 8;
-    if (d == 128) hipLaunchKernelGGL((fused::fused_decode_kernel<128>), dim3(grid), dim3(fused::NTHREADS), 0, st, a, mt);
-    else hipLaunchKernelGGL((fused::fused_decode_kernel<64>), dim3(grid), dim3(fused::NTHREADS), 0, st, a, mt);
+    const dim3 g(grid), blk(fused::NTHREADS);
+    if (d == 128 && packed) hipLaunchKernelGGL((fused::fused_decode_kernel<128, true>), g, blk, 0, st, a, mt);
+    else if (d == 128) hipLaunchKernelGGL((fused::fused_decode_kernel<128, false>), g, blk, 0, st, a, mt);
+    else if (packed) hipLaunchKernelGGL((fused::fused_decode_kernel<64, true>), g, blk, 0, st, a, mt);
+    else hipLaunchKernelGGL((fused::fused_decode_kernel<64, false>), g, blk, 0, st, a, mt);
     if (hipGetLastError() != hipSuccess) return 7;
     *fused_step = 1;
     return 0;

@@ -55,12 +55,32 @@ class DeviceWorkload:
     def set_flags(self, flags: int):
         self.shape.flags = flags
 
+    def pack_weights(self):
+        """Lay W_K / W_V out once as [d_out, d_in] and make decode() use them."""
+        if self.W_K is None:
+            return
+        self.W_K_packed = torch.empty(self.w.d_out, self.w.d_in, dtype=self.W_K.dtype, device=self.dev)
+        self.W_V_packed = torch.empty_like(self.W_K_packed)
+        ek.pack_weights(self.shape, self.W_K, self.W_K_packed)
+        ek.pack_weights(self.shape, self.W_V, self.W_V_packed)
+        self.shape.flags |= ek.FLAG_W_PACKED
+
     def decode(self, stream=None):
-        ek.decode_attn(self.shape, self.anchor, self.target, self.W_K, self.W_V, self.q, self.out,
+        packed = bool(self.shape.flags & ek.FLAG_W_PACKED)
+        wk, wv = (self.W_K_packed, self.W_V_packed) if packed else (self.W_K, self.W_V)
+        ek.decode_attn(self.shape, self.anchor, self.target, wk, wv, self.q, self.out,
                        self.lse, self.workspace, stream)
         return self.out, self.lse
 
     def prefill(self, stream=None):
+        saved = self.shape.flags
+        self.shape.flags = saved & ~ek.FLAG_W_PACKED      # prefill takes row-major weights
+        try:
+            return self._prefill(stream)
+        finally:
+            self.shape.flags = saved
+
+    def _prefill(self, stream=None):
         seq = self.inp.n_decode
         T_q = int(self.q_prefill.shape[0])
         ek.prefill_attn(self.shape, self.anchor_all, self.target_all, self.W_K, self.W_V, seq,

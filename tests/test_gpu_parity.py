@@ -16,7 +16,9 @@ import oracle_ref as ref
 pytestmark = pytest.mark.gpu
 
 TOL = {"bf16": (2e-2, 5e-3), "f32": (1e-5, 1e-5)}
-MODES = [pytest.param(0, id="fused"), pytest.param(ek.FLAG_UNFUSED, id="unfused")]
+PACKED = "packed"      # fused path with weights re-laid out once by echokv_pack_weights
+MODES = [pytest.param(0, id="fused"), pytest.param(ek.FLAG_UNFUSED, id="unfused"),
+         pytest.param(PACKED, id="packed")]
 
 
 def check(got, want, dtype, what=""):
@@ -31,9 +33,20 @@ def host(t):
     return t.float().cpu().double().numpy()
 
 
+def make_dw(inp, flags, **kw):
+    if flags == PACKED:
+        w = inp.w
+        if w.dtype != "bf16" or w.d_out == 0:
+            pytest.skip("packed weights: bf16 fused path with something to predict only")
+        dw = DeviceWorkload(inp, flags=0, **kw)
+        dw.pack_weights()
+        return dw
+    return DeviceWorkload(inp, flags=flags, **kw)
+
+
 def run_decode_case(w, flags, out_dtype=None, lse_tol=None):
     inp = synth.generate(w)
-    dw = DeviceWorkload(inp, out_dtype=out_dtype, flags=flags)
+    dw = make_dw(inp, flags, out_dtype=out_dtype)
     out, lse = dw.decode()
     torch.cuda.synchronize()
     o_ref, l_ref = ref.decode_ref(inp)
@@ -90,6 +103,23 @@ def test_decode_shapes(H_q, H_kv, d, m, dtype, flags):
     run_decode_case(w, flags)
 
 
+def test_pack_weights_is_a_transpose_and_flag_is_checked():
+    w = SMALL[1].scaled(seq_lens=(100,))
+    inp = synth.generate(w)
+    dw = DeviceWorkload(inp)
+    dw.pack_weights(); torch.cuda.synchronize()
+    assert torch.equal(dw.W_K_packed.cpu(), inp.W_K.t().contiguous())
+    assert torch.equal(dw.W_V_packed.cpu(), inp.W_V.t().contiguous())
+    with pytest.raises(ek.EchoKVError) as e:          # packed layout only feeds the fused decode
+        ek.reconstruct(dw.shape, dw.anchor_all, dw.target_all, dw.W_K_packed, dw.W_V_packed, 0, 0, 10,
+                       dw.out, dw.out)
+    assert e.value.code == ek.ERR_UNSUPPORTED
+    dw.shape.flags |= ek.FLAG_UNFUSED
+    with pytest.raises(ek.EchoKVError) as e:
+        dw.decode()
+    assert e.value.code == ek.ERR_UNSUPPORTED
+
+
 def test_decode_custom_scale():
     w = SMALL[1].scaled(seq_lens=(300,))
     inp = synth.generate(w)
@@ -102,7 +132,7 @@ def test_decode_custom_scale():
 @pytest.mark.parametrize("flags", MODES)
 def test_decode_is_deterministic(flags):
     inp = synth.generate(SMALL[4])
-    dw = DeviceWorkload(inp, flags=flags)
+    dw = make_dw(inp, flags)
     a = dw.decode()[0].clone(); b = dw.decode()[0].clone()
     torch.cuda.synchronize()
     assert torch.equal(a, b)
@@ -116,8 +146,10 @@ def test_selector_weights_copy_heads_exactly(flags):
     inp = synth.generate(w)
     src = list(range(128, 256)) + [w.D + i for i in range(128)]     # anchor head 1, retained head 0
     inp.W_K = synth.selector_weights(w, src); inp.W_V = synth.selector_weights(w, src)
-    dw = DeviceWorkload(inp, flags=flags)
+    dw = DeviceWorkload(inp, flags=0 if flags == PACKED else flags)
     k_out, v_out = dw.reconstruct(0, 0, 300); torch.cuda.synchronize()
+    if flags == PACKED:
+        dw.pack_weights()
     X = torch.cat([inp.K_a[:300], inp.K_r[:300]], dim=1)
     assert torch.equal(k_out.cpu()[:, :256], inp.K_r[:300])
     assert torch.equal(k_out.cpu()[:, 256:], X[:, src])
@@ -126,7 +158,7 @@ def test_selector_weights_copy_heads_exactly(flags):
     check(host(out), o_ref, "bf16", "selector decode")
     # heads 2 and 3 see copies of anchor head 1 / retained head 0: head 3 == head 0 given equal q
     inp.q[0, 3] = inp.q[0, 0]
-    dw2 = DeviceWorkload(inp, flags=flags, out_dtype="f32")
+    dw2 = make_dw(inp, flags, out_dtype="f32")
     o2 = host(dw2.decode()[0]); torch.cuda.synchronize()
     o2 = host(dw2.out)
     np.testing.assert_allclose(o2[0, 3], o2[0, 0], rtol=2e-5, atol=2e-6)
