@@ -99,6 +99,17 @@ int echokv_cache_append(const echokv_shape *shape, echokv_layer_cache *dst,
                         const void *k_new, const void *v_new,
                         const int32_t *n_new, void *hip_stream);
 
+/* Switch a target layer from full caching to compressed caching (the on-demand
+ * transition of Sec. "Overview of EchoKV": when memory runs short, the dims
+ * [m, D) of the layer are evicted and from then on predicted; Eq. 2 says what
+ * stays).  Copies the first m dims of every valid row of `full` (width D) into
+ * `dst` (width m) and sets dst->seq_len[b] = full->seq_len[b].  The two caches
+ * describe the same sequences but may place them differently (seq_start,
+ * seq_cap); dst must not overlap full.  The caller frees the full cache once
+ * the stream has passed this call.  ERR_CAPACITY if a sequence does not fit. */
+int echokv_cache_compress(const echokv_shape *shape, const echokv_layer_cache *full,
+                          echokv_layer_cache *dst, void *hip_stream);
+
 /* Rebuild the full-width K and V rows of tokens [tok_begin, tok_end) of
  * sequence `seq` (Eq. 3 then Eq. 6): out row = [retained m dims ; [anchor row ;
  * retained row] W].

@@ -80,6 +80,12 @@ def cache_append(cache: np.ndarray, seq_start: int, seq_len: int,
     return seq_len + n
 
 
+def cache_compress(full_cache: np.ndarray, m: int) -> np.ndarray:
+    """Full -> compressed switch of a target layer (Sec. "Overview of EchoKV"):
+    the dims [m, D) are evicted, the first m flattened dims stay (Eq. 2)."""
+    return np.array(full_cache[:, :m], copy=True)
+
+
 # --------------------------------------------------------------------------
 # reconstruction (Eq. 3, Eq. 6)
 # --------------------------------------------------------------------------

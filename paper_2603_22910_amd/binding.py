@@ -22,7 +22,8 @@ FLAG_W_PACKED = 2
 
 EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn",
-           "echokv_profile_enable", "echokv_profile_read", "echokv_pack_weights")
+           "echokv_profile_enable", "echokv_profile_read", "echokv_pack_weights",
+           "echokv_cache_compress")
 
 
 class EchoKVError(RuntimeError):
@@ -74,6 +75,9 @@ def load() -> C.CDLL:
                                         C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_int32,
                                         C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.echokv_cache_compress.restype = C.c_int
+    lib.echokv_cache_compress.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
+                                          C.POINTER(LayerCacheC), C.c_void_p]
     lib.echokv_pack_weights.restype = C.c_int
     lib.echokv_pack_weights.argtypes = [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p]
     lib.echokv_profile_enable.restype = C.c_int
@@ -165,6 +169,12 @@ def cache_append(shape: Shape, dst: LayerCache, k_new, v_new, n_new: Sequence[in
     _check(load().echokv_cache_append(C.byref(shape), C.byref(c), _ptr(k_new), _ptr(v_new),
                                       n.ctypes.data_as(C.POINTER(C.c_int32)), _stream(stream)),
            "echokv_cache_append")
+
+
+def cache_compress(shape: Shape, full: LayerCache, dst: LayerCache, stream=None):
+    f, d = full.as_c(), dst.as_c()
+    _check(load().echokv_cache_compress(C.byref(shape), C.byref(f), C.byref(d), _stream(stream)),
+           "echokv_cache_compress")
 
 
 def reconstruct(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, seq: int,

@@ -497,6 +497,38 @@ int echokv_cache_append(const echokv_shape* shape, echokv_layer_cache* dst, cons
   return ECHOKV_OK;
 }
 
+int echokv_cache_compress(const echokv_shape* shape, const echokv_layer_cache* full,
+                          echokv_layer_cache* dst, void* hip_stream) {
+  Dims dm;
+  int rc = check_shape(shape, &dm);
+  if (rc) return rc;
+  rc = check_cache(full, dm.D);
+  if (rc) return rc;
+  rc = check_cache(dst, dm.m);
+  if (rc) return rc;
+  if (full->batch != dst->batch) return ECHOKV_ERR_SHAPE;
+  for (int b = 0; b < full->batch; ++b)
+    if (full->seq_len[b] > dst->seq_cap[b]) return ECHOKV_ERR_CAPACITY;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (dm.m > 0) {
+    for (int b = 0; b < full->batch; ++b) {
+      const int64_t rows = full->seq_len[b];
+      if (rows == 0) continue;
+      Copy2dArgs c;
+      c.src[0] = (const char*)full->k + full->seq_start[b] * dm.D * dm.es;
+      c.src[1] = (const char*)full->v + full->seq_start[b] * dm.D * dm.es;
+      c.dst[0] = (char*)dst->k + dst->seq_start[b] * dm.m * dm.es;
+      c.dst[1] = (char*)dst->v + dst->seq_start[b] * dm.m * dm.es;
+      c.src_row_bytes = (int64_t)dm.D * dm.es; c.dst_row_bytes = (int64_t)dm.m * dm.es;
+      c.copy_bytes = (int64_t)dm.m * dm.es; c.rows = rows;
+      hipLaunchKernelGGL(copy2d_kernel, dim3((unsigned)std::min<int64_t>(rows, 16384), 2), dim3(256), 0, st, c);
+      LAUNCH_CHECK();
+    }
+  }
+  for (int b = 0; b < full->batch; ++b) dst->seq_len[b] = full->seq_len[b];
+  return ECHOKV_OK;
+}
+
 int echokv_reconstruct(const echokv_shape* shape, const echokv_layer_cache* anchor,
                        const echokv_layer_cache* target, const void* w_k, const void* w_v,
                        int32_t seq, int32_t tok_begin, int32_t tok_end, void* k_out, void* v_out,

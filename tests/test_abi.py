@@ -151,6 +151,22 @@ def test_reconstruct_and_prefill_argument_errors(lib):
     assert pf(0, 10, 0, _Ws(8)) == ek.ERR_WORKSPACE
 
 
+def test_compress_and_pack_argument_errors(lib):
+    sh = ek.make_shape(8, 8, 64, 256, "f32")
+    full = ek.LayerCache(FAKE, FAKE, 512, 512, [0, 256], [100, 10], [256, 256])
+    dst = ek.LayerCache(FAKE, FAKE, 256, 512, [0, 256], [0, 0], [64, 256])
+    assert code(ek.cache_compress, sh, full, dst, stream=0) == ek.ERR_CAPACITY
+    assert list(dst.seq_len) == [0, 0]
+    wrong = ek.LayerCache(FAKE, FAKE, 128, 512, [0, 256], [0, 0], [256, 256])
+    assert code(ek.cache_compress, sh, full, wrong, stream=0) == ek.ERR_SHAPE
+    one = ek.LayerCache(FAKE, FAKE, 256, 512, [0], [0], [256])
+    assert code(ek.cache_compress, sh, full, one, stream=0) == ek.ERR_SHAPE
+    assert code(ek.pack_weights, sh, None, FAKE, stream=0) == ek.ERR_NULL
+    assert code(ek.pack_weights, sh, FAKE, FAKE, stream=0) == ek.ERR_SHAPE      # in place
+    full_ret = ek.make_shape(8, 8, 64, 512, "f32")
+    assert code(ek.pack_weights, full_ret, None, None, stream=0) == ek.OK      # nothing to pack
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(ek, "_LIB", None)
     monkeypatch.setattr(ek, "LIB_PATH", str(tmp_path / "libechokv.so"))

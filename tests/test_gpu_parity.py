@@ -320,3 +320,58 @@ def test_prefill_full_size_sampled(q_pos0):
                                          visible=[q_pos0 + i + 1 for i in idx])
     check(got[idx], o_ref, "bf16", f"prefill full size q_pos0={q_pos0}")
     assert np.abs(got_lse[idx] - l_ref).max() <= 2e-2
+
+
+@pytest.mark.parametrize("flags", MODES)
+def test_decode_more_sequences_than_one_launch_describes(flags):
+    """The kernels describe at most 128 sequences per launch; larger batches
+    are processed in groups."""
+    lens = tuple(1 + (37 * i) % 300 for i in range(150))
+    w = synth.Workload("b150", "bf16", 4, 2, 128, 128, seed=77, seq_lens=lens)
+    run_decode_case(w, flags)
+
+
+def test_workspace_exactly_as_reported_is_enough_and_less_is_rejected():
+    w = SMALL[1]
+    inp = synth.generate(w)
+    dw = DeviceWorkload(inp)
+    need = ek.workspace_bytes(dw.shape, inp.n_decode, inp.total_decode_tokens, 1)
+    assert dw.workspace.numel() == need
+    out, _ = dw.decode(); torch.cuda.synchronize()
+    o_ref, _ = ref.decode_ref(inp)
+    check(host(out), o_ref, "bf16", "exact workspace")
+    dw.workspace = dw.workspace[:4096]
+    with pytest.raises(ek.EchoKVError) as e:
+        dw.decode()
+    assert e.value.code == ek.ERR_WORKSPACE
+
+
+def test_switch_from_full_cache_to_compressed_cache():
+    """On-demand transition: a target layer first served from its full cache
+    (m = D, ordinary attention), then compressed in place of a rebuild."""
+    from oracle import echokv_oracle as orc
+    w = synth.Workload("switch", "bf16", 8, 8, 128, 512, seed=41, seq_lens=(333, 70))
+    inp = synth.generate(w)
+    dev = torch.device("cuda:0")
+    # the target layer's full K/V: retained prefix as generated + arbitrary other dims
+    g = torch.Generator().manual_seed(1)
+    full_k = torch.randn(inp.pool_tokens, w.D, generator=g).to(torch.bfloat16)
+    full_v = torch.randn(inp.pool_tokens, w.D, generator=g).to(torch.bfloat16)
+    full_k[:, :w.n_retained] = inp.K_r; full_v[:, :w.n_retained] = inp.V_r
+    shape = ek.make_shape(w.n_q_heads, w.n_kv_heads, w.head_dim, w.n_retained, "bf16")
+    fk, fv = full_k.to(dev), full_v.to(dev)
+    full = ek.LayerCache(fk, fv, w.D, inp.pool_tokens, inp.seq_start, inp.seq_len, inp.seq_cap)
+    # compressed cache laid out differently (tight capacities) on purpose
+    caps = [384, 128]; starts = [128, 0]
+    ck = torch.zeros(512, w.n_retained, dtype=torch.bfloat16, device=dev); cv = torch.zeros_like(ck)
+    dst = ek.LayerCache(ck, cv, w.n_retained, 512, starts, [0, 0], caps)
+    ek.cache_compress(shape, full, dst); torch.cuda.synchronize()
+    assert list(dst.seq_len) == inp.seq_len
+    for b in range(2):
+        want = orc.cache_compress(ref.f64(full_k[inp.rows(b)]), w.n_retained)
+        got = ck[starts[b]:starts[b] + inp.seq_len[b]].float().cpu().double().numpy()
+        assert np.array_equal(got, want)
+    small = ek.LayerCache(ck, cv, w.n_retained, 512, starts, [0, 0], [384, 64])
+    with pytest.raises(ek.EchoKVError) as e:
+        ek.cache_compress(shape, full, small)
+    assert e.value.code == ek.ERR_CAPACITY

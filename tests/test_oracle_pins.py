@@ -345,6 +345,16 @@ def test_cache_append_keeps_prefix_only():
     assert not anchor[:5].any() and not anchor[7:].any() and not target[7:].any()
 
 
+def test_cache_compress_equals_dropping_at_append_time():
+    # switching a full cache to compressed gives what appending with dropping would have
+    D, m, n = 12, 5, 9
+    full = rnd((n, D), 3)
+    target = np.zeros((n, m))
+    orc.cache_append(target, 0, 0, full)
+    assert np.array_equal(orc.cache_compress(full, m), target)
+    assert orc.cache_compress(full, D).shape == (n, D) and orc.cache_compress(full, 0).shape == (n, 0)
+
+
 # ---- P12 + generator wiring ------------------------------------------------------------
 def test_synthetic_retained_prefix_is_predictable_from_anchor():
     from paper_2603_22910_amd import synth
