@@ -45,7 +45,7 @@ template <int HD> struct Cfg {
 __device__ __forceinline__ int vswz(int r) { return (r ^ (r >> 3)) & 7; }
 
 template <int HD>
-__global__ __launch_bounds__(NTHREADS) void prefill_attn_kernel(Args a) {
+__global__ __launch_bounds__(NTHREADS, 2) void prefill_attn_kernel(Args a) {
   using C = Cfg<HD>;
   __shared__ __attribute__((aligned(16))) char sk[2][C::KTILE_BYTES];
   __shared__ __attribute__((aligned(16))) char sv[2][C::VTILE_BYTES];
@@ -77,6 +77,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_kernel(Args a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
+  const float scale2 = a.scale * 1.44269504088896340736f;    // softmax in base 2: exp(x) = 2^(x log2 e)
 
   const int kv_end = min(Ltot, a.q_pos0 + min(i0 + BQ, a.T_q));   // keys any query of the block sees
   const int ntiles = (kv_end + BKV - 1) / BKV;
@@ -152,29 +153,31 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_kernel(Args a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int key = kv0 + mb * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-        const float s = (key <= qpos) ? sacc[mb][r] * a.scale : -INFINITY;
+        const float s = (key <= qpos) ? sacc[mb][r] * scale2 : -INFINITY;   // base-2 logits
         sacc[mb][r] = s;
         mx = fmaxf(mx, s);
       }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);          // finite from the first tile on (key 0 is visible)
-    const float corr = __expf(m_run - m_new);
+    const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
     float lsum = 0.f;
     bf16x8_t pf[4];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = __expf(sacc[mb][r] - m_new);
+        const float p = __builtin_amdgcn_exp2f(sacc[mb][r] - m_new);
         lsum += p;
         pf[mb * 2 + (r >> 3)][r & 7] = (__bf16)p;
       }
     l_run = l_run * corr + lsum;
     m_run = m_new;
+    if (__any(corr != 1.0f)) {            // the running maxima settle quickly: usually nothing to rescale
 #pragma unroll
-    for (int cb = 0; cb < C::CB; ++cb)
+      for (int cb = 0; cb < C::CB; ++cb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[cb][r] *= corr;
+        for (int r = 0; r < 16; ++r) oacc[cb][r] *= corr;
+    }
     // ---- O^T += V^T P^T : k-step ts covers keys 16 ts .. 16 ts + 15 in slot order
     //      (lane half lh, element e) <-> key 16 ts + 4 lh + (e < 4 ? e : e + 4)
 #pragma unroll
@@ -214,7 +217,8 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_kernel(Args a) {
           *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + ob + c) = make_float4(x0, x1, x2, x3);
         }
       }
-    if (a.lse && lh == 0) a.lse[(int64_t)qi * a.H_q + h] = m_run + __logf(l_tot);
+    if (a.lse && lh == 0)
+      a.lse[(int64_t)qi * a.H_q + h] = (m_run + __log2f(l_tot)) * 0.69314718055994530942f;
   }
 }
 
