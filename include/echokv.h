@@ -42,7 +42,7 @@ typedef enum {
   ECHOKV_ERR_DTYPE = 3,       /* unknown dtype code */
   ECHOKV_ERR_CAPACITY = 4,    /* append past a sequence's reserved rows */
   ECHOKV_ERR_WORKSPACE = 5,   /* workspace missing or too small */
-  ECHOKV_ERR_UNSUPPORTED = 6, /* legal in the method, not built (e.g. m % d != 0) */
+  ECHOKV_ERR_UNSUPPORTED = 6, /* legal in the method, not built (e.g. m % 64 != 0) */
   ECHOKV_ERR_HIP = 7          /* a HIP runtime call or launch failed */
 } echokv_status;
 
@@ -61,7 +61,8 @@ typedef struct {
   int32_t n_q_heads;   /* H_q */
   int32_t n_kv_heads;  /* H_kv; H_q % H_kv == 0 */
   int32_t head_dim;    /* d; 64 or 128 */
-  int32_t n_retained;  /* m, flattened dims the target keeps; 0 <= m <= D, m % d == 0 */
+  int32_t n_retained;  /* m, flattened dims the target keeps; 0 <= m <= D, m % 64 == 0
+                          (the prefix may end inside a head, as in the paper's m = 64 preset) */
   int32_t dtype;       /* echokv_dtype of cache, weights and queries */
   int32_t out_dtype;   /* echokv_dtype of `out`; accumulation is always fp32 */
   float softmax_scale; /* <= 0 selects 1/sqrt(d) (Appendix "Analysis of QK-KL

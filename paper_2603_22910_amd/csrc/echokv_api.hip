@@ -21,6 +21,10 @@ namespace {
 
 struct Dims {
   int H_q, H_kv, d, D, m, d_in, d_out, G, es, oes;
+  // m = g0*d + r: g0 whole heads are retained; if r > 0 the next head is split.  The kernels then
+  // work on d_out_v = d_out + r "virtual" output columns: the weights are extended by r selector
+  // columns that copy the split head's retained dims, so that head looks fully predicted to them.
+  int g0, r, d_out_v;
   bool bf16, out_bf16;
   float scale;
 };
@@ -37,11 +41,12 @@ int check_shape(const echokv_shape* s, Dims* o) {
   const int64_t D = (int64_t)s->n_kv_heads * s->head_dim;
   if (s->n_retained < 0 || s->n_retained > D) return ECHOKV_ERR_SHAPE;
   if (s->head_dim != 64 && s->head_dim != 128) return ECHOKV_ERR_UNSUPPORTED;
-  if (s->n_retained % s->head_dim) return ECHOKV_ERR_UNSUPPORTED;
+  if (s->n_retained % 64) return ECHOKV_ERR_UNSUPPORTED;   // k-tiles of 64 input dims
   if (!std::isfinite(s->softmax_scale)) return ECHOKV_ERR_SHAPE;
   o->H_q = s->n_q_heads; o->H_kv = s->n_kv_heads; o->d = s->head_dim;
   o->D = (int)D; o->m = s->n_retained; o->d_in = o->D + o->m; o->d_out = o->D - o->m;
   o->G = o->H_q / o->H_kv;
+  o->g0 = o->m / o->d; o->r = o->m % o->d; o->d_out_v = o->d_out + o->r;
   o->bf16 = s->dtype == ECHOKV_BF16; o->out_bf16 = s->out_dtype == ECHOKV_BF16;
   o->es = o->bf16 ? 2 : 4; o->oes = o->out_bf16 ? 2 : 4;
   o->scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / std::sqrt((float)o->d);
@@ -75,17 +80,21 @@ int check_pair(const Dims& dm, const echokv_layer_cache* a, const echokv_layer_c
 
 inline int slots_for(int64_t tokens) { return (int)((tokens + kSlotTokens - 1) / kSlotTokens); }
 
-// Workspace plan: [partial o][partial (max,sum)][K_hat][V_hat]
+// Workspace plan: [extended W_K][extended W_V][partial o][partial (max,sum)][K_hat][V_hat]
 struct WsPlan {
-  size_t off_po, off_pml, off_kh, off_vh, total;
+  size_t off_po, off_pml, off_kh, off_vh, off_wk, off_wv, total;
 };
 WsPlan plan_ws(const Dims& dm, int64_t part_slots, int64_t recon_rows) {
   WsPlan p;
   size_t o = 0;
+  // extended weights first: their place must not depend on the slot counts of a launch group
+  const size_t aug = dm.r ? (size_t)dm.d_in * dm.d_out_v * dm.es : 0;
+  p.off_wk = o;  o += align_up(aug);
+  p.off_wv = o;  o += align_up(aug);
   p.off_po = o;  o += align_up((size_t)part_slots * dm.H_q * dm.d * 4);
   p.off_pml = o; o += align_up((size_t)part_slots * dm.H_q * 2 * 4);
-  p.off_kh = o;  o += align_up((size_t)recon_rows * dm.d_out * dm.es);
-  p.off_vh = o;  o += align_up((size_t)recon_rows * dm.d_out * dm.es);
+  p.off_kh = o;  o += align_up((size_t)recon_rows * dm.d_out_v * dm.es);
+  p.off_vh = o;  o += align_up((size_t)recon_rows * dm.d_out_v * dm.es);
   p.total = o;
   return p;
 }
@@ -121,6 +130,25 @@ int fill_slots(SeqMeta& mt) {
   return acc;
 }
 
+// Weights as the kernels see them: W itself, or (split head, r > 0) W with r selector columns in
+// front, built in the workspace.  Column v < r of the extension copies predictor input
+// D + g0*d + v, i.e. retained dim g0*d + v of the target layer, exactly (1 * x in fp32).
+template <typename T>
+int effective_weights(const Dims& dm, const void* w_k, const void* w_v, char* ws, const WsPlan& wp,
+                      const T** wk, const T** wv, hipStream_t st) {
+  *wk = (const T*)w_k; *wv = (const T*)w_v;
+  if (dm.r == 0 || dm.d_out == 0) return ECHOKV_OK;
+  T* ak = (T*)(ws + wp.off_wk);
+  T* av = (T*)(ws + wp.off_wv);
+  AugArgs<T> a;
+  a.w[0] = (const T*)w_k; a.w[1] = (const T*)w_v; a.out[0] = ak; a.out[1] = av;
+  a.d_in = dm.d_in; a.d_out = dm.d_out; a.r = dm.r; a.sel0 = dm.D + dm.g0 * dm.d;
+  hipLaunchKernelGGL((augment_weights_kernel<T>), dim3(dm.d_in, 2), dim3(256), 0, st, a);
+  LAUNCH_CHECK();
+  *wk = ak; *wv = av;
+  return ECHOKV_OK;
+}
+
 template <typename T>
 int launch_attn_split(const Dims& dm, AttnArgs<T> a, SeqMeta& mt, int n_kv_heads, hipStream_t st) {
   const int tiles = fill_tiles(mt, a.split_tokens);
@@ -142,7 +170,7 @@ int launch_attn_split(const Dims& dm, AttnArgs<T> a, SeqMeta& mt, int n_kv_heads
 template <typename T>
 int launch_recon_fma(const Dims& dm, GemmArgs<T> g, SeqMeta& mt, hipStream_t st) {
   const int tiles = fill_tiles(mt, 64);
-  dim3 grid(tiles, (dm.d_out + 63) / 64, 2);
+  dim3 grid(tiles, (g.d_out + 63) / 64, 2);
   hipLaunchKernelGGL((recon_fma_kernel<T>), grid, dim3(256), 0, st, g, mt);
   LAUNCH_CHECK();
   return ECHOKV_OK;
@@ -173,8 +201,10 @@ template <typename T>
 int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
                 const echokv_layer_cache* tg, const void* w_k, const void* w_v, const void* q,
                 void* out, float* lse, char* ws, hipStream_t st) {
-  const int n_ret_heads = dm.m / dm.d, n_rec_heads = dm.H_kv - n_ret_heads;
+  const int n_ret_heads = dm.g0, n_rec_heads = dm.H_kv - n_ret_heads;
   const bool fused = !(flags & ECHOKV_FLAG_UNFUSED) && fused_decode_supported<T>(dm.d, dm.G);
+  const T* wk = nullptr; const T* wv = nullptr;
+  bool have_w = false;
   for (int b0 = 0; b0 < an->batch; b0 += kMaxSeqPerLaunch) {
     SeqMeta mt;
     mt.n = std::min(kMaxSeqPerLaunch, an->batch - b0);
@@ -184,6 +214,11 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
     }
     const int slots = fill_slots(mt);
     const WsPlan wp = plan_ws(dm, slots, fused ? 0 : (int64_t)slots * kSlotTokens);
+    if (!have_w) {      // the plan of the first (largest-index-independent) group places the extended weights
+      int rcw = effective_weights<T>(dm, w_k, w_v, ws, wp, &wk, &wv, st);
+      if (rcw) return rcw;
+      have_w = true;
+    }
     float* po = (float*)(ws + wp.off_po);
     float* pml = (float*)(ws + wp.off_pml);
     const T* qq = (const T*)q + (int64_t)b0 * dm.H_q * dm.d;
@@ -208,14 +243,14 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
         }
         int rc;
         if constexpr (sizeof(T) == 4)
-          rc = launch_fused_decode_f32(dm.H_q, dm.H_kv, dm.d, dm.m, dm.scale, (const float*)an->k,
-                                       (const float*)an->v, (const float*)tg->k, (const float*)tg->v,
-                                       (const float*)w_k, (const float*)w_v, qq, po, pml, mt,
-                                       &fused_step, st);
+          rc = launch_fused_decode_f32(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale,
+                                       (const float*)an->k, (const float*)an->v, (const float*)tg->k,
+                                       (const float*)tg->v, (const float*)wk, (const float*)wv, qq,
+                                       po, pml, mt, &fused_step, st);
         else
-          rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.scale,
+          rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale,
                                       (const T*)an->k, (const T*)an->v, (const T*)tg->k,
-                                      (const T*)tg->v, (const T*)w_k, (const T*)w_v, qq, po,
+                                      (const T*)tg->v, wk, wv, qq, po,
                                       pml, mt, &fused_step, st, (flags & ECHOKV_FLAG_W_PACKED) != 0);
         if (g_prof.on) {
           HIP_TRY(hipEventRecord(e1, st));
@@ -227,22 +262,22 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
         T* vh = (T*)(ws + wp.off_vh);
         int rc;
         if (recon_mfma_supported<T>()) {
-          rc = launch_recon_mfma<T>(dm.D, dm.m, (const T*)an->k, (const T*)an->v, (const T*)tg->k,
-                                    (const T*)tg->v, (const T*)w_k, (const T*)w_v, kh, vh,
-                                    dm.d_out, 0, mt, st);
+          rc = launch_recon_mfma<T>(dm.D, dm.m, dm.d_out_v, (const T*)an->k, (const T*)an->v,
+                                    (const T*)tg->k, (const T*)tg->v, wk, wv, kh, vh,
+                                    dm.d_out_v, 0, mt, st);
         } else {
           GemmArgs<T> g;
           g.xa[0] = (const T*)an->k; g.xa[1] = (const T*)an->v;
           g.xr[0] = (const T*)tg->k; g.xr[1] = (const T*)tg->v;
-          g.w[0] = (const T*)w_k; g.w[1] = (const T*)w_v;
+          g.w[0] = wk; g.w[1] = wv;
           g.out[0] = kh; g.out[1] = vh;
-          g.D = dm.D; g.m = dm.m; g.d_out = dm.d_out; g.ldo = dm.d_out; g.col0 = 0;
+          g.D = dm.D; g.m = dm.m; g.d_out = dm.d_out_v; g.ldo = dm.d_out_v; g.col0 = 0;
           g.rows_from_slots = 1;
           rc = launch_recon_fma<T>(dm, g, mt, st);
         }
         if (rc) return rc;
         AttnArgs<T> a;
-        a.k = kh; a.v = vh; a.ld = dm.d_out; a.col0 = 0; a.head0 = n_ret_heads;
+        a.k = kh; a.v = vh; a.ld = dm.d_out_v; a.col0 = 0; a.head0 = n_ret_heads;
         a.row_mode = 1; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
         a.split_tokens = pick_split_tokens(tokens, n_rec_heads);
         a.part_o = po; a.part_ml = pml;
@@ -279,9 +314,10 @@ int reconstruct_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_
     SeqMeta mt;
     mt.n = 1; mt.start[0] = row0; mt.len[0] = (int)rows; mt.sbase[0] = 0; mt.sbase[1] = slots_for(rows);
     if (recon_mfma_supported<T>()) {
-      return launch_recon_mfma<T>(dm.D, dm.m, (const T*)an->k, (const T*)an->v, (const T*)tg->k,
-                                  (const T*)tg->v, (const T*)w_k, (const T*)w_v, (T*)k_out,
-                                  (T*)v_out, dm.D, dm.m, mt, st);
+      // flattened output [retained m ; predicted d_out]: no head alignment involved, plain W
+      return launch_recon_mfma<T>(dm.D, dm.m, dm.d_out, (const T*)an->k, (const T*)an->v,
+                                  (const T*)tg->k, (const T*)tg->v, (const T*)w_k, (const T*)w_v,
+                                  (T*)k_out, (T*)v_out, dm.D, dm.m, mt, st);
     }
     GemmArgs<T> g;
     g.xa[0] = (const T*)an->k; g.xa[1] = (const T*)an->v;
@@ -308,7 +344,7 @@ template <typename T>
 int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_layer_cache* tg,
                  const void* w_k, const void* w_v, int seq, const void* q, int T_q, int q_pos0,
                  void* out, float* lse, char* ws, hipStream_t st) {
-  const int n_ret_heads = dm.m / dm.d, n_rec_heads = dm.H_kv - n_ret_heads;
+  const int n_ret_heads = dm.g0, n_rec_heads = dm.H_kv - n_ret_heads;
   const int Ltot = q_pos0 + T_q;
   const int64_t row0 = an->seq_start[seq];
   const WsPlan wp = plan_ws(dm, prefill_part_slots(dm, Ltot, T_q), (int64_t)slots_for(Ltot) * kSlotTokens);
@@ -317,26 +353,28 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
   T* kh = (T*)(ws + wp.off_kh);
   T* vh = (T*)(ws + wp.off_vh);
   if (n_rec_heads > 0) {
+    const T* wk; const T* wv;
+    int rc = effective_weights<T>(dm, w_k, w_v, ws, wp, &wk, &wv, st);
+    if (rc) return rc;
     SeqMeta mt;
     mt.n = 1; mt.start[0] = row0; mt.len[0] = Ltot; mt.sbase[0] = 0; mt.sbase[1] = slots_for(Ltot);
     if (recon_mfma_supported<T>()) {
-      int rc = launch_recon_mfma<T>(dm.D, dm.m, (const T*)an->k, (const T*)an->v, (const T*)tg->k,
-                                    (const T*)tg->v, (const T*)w_k, (const T*)w_v, kh, vh,
-                                    dm.d_out, 0, mt, st);
+      rc = launch_recon_mfma<T>(dm.D, dm.m, dm.d_out_v, (const T*)an->k, (const T*)an->v,
+                                (const T*)tg->k, (const T*)tg->v, wk, wv, kh, vh, dm.d_out_v, 0, mt, st);
       if (rc) return rc;
     } else {
       GemmArgs<T> g;
       g.xa[0] = (const T*)an->k; g.xa[1] = (const T*)an->v;
       g.xr[0] = (const T*)tg->k; g.xr[1] = (const T*)tg->v;
-      g.w[0] = (const T*)w_k; g.w[1] = (const T*)w_v;
+      g.w[0] = wk; g.w[1] = wv;
       g.out[0] = kh; g.out[1] = vh;
-      g.D = dm.D; g.m = dm.m; g.d_out = dm.d_out; g.ldo = dm.d_out; g.col0 = 0; g.rows_from_slots = 0;
-      int rc = launch_recon_fma<T>(dm, g, mt, st);
+      g.D = dm.D; g.m = dm.m; g.d_out = dm.d_out_v; g.ldo = dm.d_out_v; g.col0 = 0; g.rows_from_slots = 0;
+      rc = launch_recon_fma<T>(dm, g, mt, st);
       if (rc) return rc;
     }
   }
   if (prefill_mfma_supported<T>(dm.d)) {
-    return launch_prefill_mfma<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.scale, dm.out_bf16,
+    return launch_prefill_mfma<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale, dm.out_bf16,
                                   (const T*)tg->k + row0 * dm.m, (const T*)tg->v + row0 * dm.m,
                                   kh, vh, (const T*)q, T_q, q_pos0, out, lse, st);
   }
@@ -361,7 +399,7 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
     }
     if (n_rec_heads > 0) {
       AttnArgs<T> a;
-      a.k = kh; a.v = vh; a.ld = dm.d_out; a.col0 = 0; a.head0 = n_ret_heads;
+      a.k = kh; a.v = vh; a.ld = dm.d_out_v; a.col0 = 0; a.head0 = n_ret_heads;
       a.row_mode = 2; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
       a.split_tokens = pick_split_tokens(tokens, n_rec_heads);
       a.part_o = po; a.part_ml = pml;
@@ -570,7 +608,7 @@ int echokv_decode_attn(const echokv_shape* shape, const echokv_layer_cache* anch
     max_chunk_slots = std::max(max_chunk_slots, s);
   }
   if ((shape->flags & ECHOKV_FLAG_W_PACKED) &&
-      ((shape->flags & ECHOKV_FLAG_UNFUSED) || !dm.bf16 || !fused_decode_supported<bf16_t>(dm.d, dm.G)))
+      (dm.r != 0 || (shape->flags & ECHOKV_FLAG_UNFUSED) || !dm.bf16 || !fused_decode_supported<bf16_t>(dm.d, dm.G)))
     return ECHOKV_ERR_UNSUPPORTED;
   const bool unfused = (shape->flags & ECHOKV_FLAG_UNFUSED) ||
                        !(dm.bf16 ? fused_decode_supported<bf16_t>(dm.d, dm.G)

@@ -698,7 +698,8 @@ inline int fused_fill_tiles(SeqMeta& mt) {
 }
 
 template <typename T>
-inline int launch_fused_decode(int H_q, int H_kv, int d, int m, float scale, const T* ka,
+inline int launch_fused_decode(int H_q, int H_kv, int d, int m, int d_out, int n_ret_heads,
+                               float scale, const T* ka,
                                const T* va, const T* kr, const T* vr, const T* wk, const T* wv,
                                const T* q, float* part_o, float* part_ml, SeqMeta& mt,
                                int* fused_step, hipStream_t st, bool packed = false) {
@@ -709,8 +710,8 @@ inline int launch_fused_decode(int H_q, int H_kv, int d, int m, float scale, con
     a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk; a.w[1] = wv;
     a.q = q; a.part_o = part_o; a.part_ml = part_ml;
     a.out[0] = a.out[1] = nullptr; a.ldo = 0; a.col0 = 0;
-    a.D = H_kv * d; a.m = m; a.d_out = a.D - m; a.H_q = H_q; a.G = H_q / H_kv;
-    a.n_ret_heads = m / d; a.scale = scale;
+    a.D = H_kv * d; a.m = m; a.d_out = d_out; a.H_q = H_q; a.G = H_q / H_kv;
+    a.n_ret_heads = n_ret_heads; a.scale = scale;
     a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;
     a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
     const int grid = ((a.n_tiles + 7) / 8) * 8;
@@ -726,9 +727,9 @@ inline int launch_fused_decode(int H_q, int H_kv, int d, int m, float scale, con
 }
 
 // K_hat and V_hat of the sequences in `mt` -> out_k / out_v [rows, ldo] at
-// column col0, output row = sbase[b]*kSlotTokens + j.
+// column col0, output row = sbase[b]*kSlotTokens + j.  d_out = width of W.
 template <typename T>
-inline int launch_recon_mfma(int D, int m, const T* ka, const T* va, const T* kr, const T* vr,
+inline int launch_recon_mfma(int D, int m, int d_out, const T* ka, const T* va, const T* kr, const T* vr,
                              const T* wk, const T* wv, T* out_k, T* out_v, int64_t ldo, int col0,
                              SeqMeta& mt, hipStream_t st) {
   if constexpr (sizeof(T) != 2) {
@@ -738,7 +739,7 @@ inline int launch_recon_mfma(int D, int m, const T* ka, const T* va, const T* kr
     a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk; a.w[1] = wv;
     a.q = nullptr; a.part_o = nullptr; a.part_ml = nullptr;
     a.out[0] = out_k; a.out[1] = out_v; a.ldo = ldo; a.col0 = col0;
-    a.D = D; a.m = m; a.d_out = D - m; a.H_q = 0; a.G = 1; a.n_ret_heads = 0; a.scale = 0.f;
+    a.D = D; a.m = m; a.d_out = d_out; a.H_q = 0; a.G = 1; a.n_ret_heads = 0; a.scale = 0.f;
     a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;
     a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
     const int grid = ((a.n_tiles + 7) / 8) * 8;

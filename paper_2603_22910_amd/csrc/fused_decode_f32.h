@@ -118,7 +118,8 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_f32_kernel(Args a, SeqM
 
 }  // namespace fused32
 
-inline int launch_fused_decode_f32(int H_q, int H_kv, int d, int m, float scale, const float* ka,
+inline int launch_fused_decode_f32(int H_q, int H_kv, int d, int m, int d_out, int n_ret_heads,
+                                   float scale, const float* ka,
                                    const float* va, const float* kr, const float* vr,
                                    const float* wk, const float* wv, const float* q,
                                    float* part_o, float* part_ml, SeqMeta& mt, int* fused_step,
@@ -126,8 +127,8 @@ inline int launch_fused_decode_f32(int H_q, int H_kv, int d, int m, float scale,
   fused32::Args a;
   a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk; a.w[1] = wv;
   a.q = q; a.part_o = part_o; a.part_ml = part_ml;
-  a.D = H_kv * d; a.m = m; a.d_out = a.D - m; a.H_q = H_q; a.G = H_q / H_kv;
-  a.n_ret_heads = m / d; a.scale = scale;
+  a.D = H_kv * d; a.m = m; a.d_out = d_out; a.H_q = H_q; a.G = H_q / H_kv;
+  a.n_ret_heads = n_ret_heads; a.scale = scale;
   a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;
   a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
   if (d == 128) hipLaunchKernelGGL((fused32::fused_decode_f32_kernel<128>), dim3(a.n_tiles), dim3(fused::NTHREADS), 0, st, a, mt);

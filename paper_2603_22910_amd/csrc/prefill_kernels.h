@@ -231,7 +231,8 @@ template <typename T> inline bool prefill_mfma_supported(int d) {
 // k_ret / v_ret: retained cache at the sequence's first row (stride m);
 // k_hat / v_hat: predicted dims of tokens 0 .. q_pos0+T_q-1 (stride d_out).
 template <typename T>
-inline int launch_prefill_mfma(int H_q, int H_kv, int d, int m, float scale, bool out_bf16,
+inline int launch_prefill_mfma(int H_q, int H_kv, int d, int m, int d_out, int n_ret_heads,
+                               float scale, bool out_bf16,
                                const T* k_ret, const T* v_ret, const T* k_hat, const T* v_hat,
                                const T* q, int T_q, int q_pos0, void* out, float* lse,
                                hipStream_t st) {
@@ -241,7 +242,7 @@ inline int launch_prefill_mfma(int H_q, int H_kv, int d, int m, float scale, boo
     prefill::Args a;
     a.k_ret = k_ret; a.v_ret = v_ret; a.k_hat = k_hat; a.v_hat = v_hat; a.q = q;
     a.out = out; a.lse = lse;
-    a.H_q = H_q; a.G = H_q / H_kv; a.m = m; a.d_out = H_kv * d - m; a.n_ret_heads = m / d;
+    a.H_q = H_q; a.G = H_q / H_kv; a.m = m; a.d_out = d_out; a.n_ret_heads = n_ret_heads;
     a.T_q = T_q; a.q_pos0 = q_pos0; a.out_bf16 = out_bf16 ? 1 : 0; a.scale = scale;
     dim3 grid((T_q + prefill::BQ - 1) / prefill::BQ, H_q);
     if (d == 128) hipLaunchKernelGGL((prefill::prefill_attn_kernel<128>), grid, dim3(prefill::NTHREADS), 0, st, a);

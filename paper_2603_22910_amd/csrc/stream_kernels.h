@@ -71,6 +71,29 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* src, T* dst, in
 }
 
 // ---------------------------------------------------------------------------
+// Extended weights for a target layer whose retained prefix ends inside a head
+// (m = g0*d + r, r > 0): out[k, v] = (k == sel0 + v) for v < r, W[k, v - r] else,
+// out being [d_in, d_out + r] row-major.  The r selector columns make the
+// predictor product reproduce the split head's retained dims bit for bit, so
+// the attention kernels can treat that head as fully predicted (Eq. 6 concat).
+// grid = (d_in, 2): one block per input row, blockIdx.y = K or V.
+// ---------------------------------------------------------------------------
+template <typename T>
+struct AugArgs {
+  const T* w[2];
+  T* out[2];
+  int32_t d_in, d_out, r, sel0;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void augment_weights_kernel(AugArgs<T> a) {
+  const int k = blockIdx.x, which = blockIdx.y;
+  const T* src = a.w[which] + (int64_t)k * a.d_out;
+  T* dst = a.out[which] + (int64_t)k * (a.d_out + a.r);
+  for (int v = threadIdx.x; v < a.d_out + a.r; v += blockDim.x)
+    dst[v] = (v < a.r) ? Elem<T>::from_f32(k == a.sel0 + v ? 1.0f : 0.0f) : src[v - a.r];
+}
+
+// ---------------------------------------------------------------------------
 // Predictor product with ordinary FMAs (Eq. 3): for the tokens of each
 // sequence, out[row, col0 + c] = sum_k X[j,k] W[k,c], X = [anchor row ; retained row].
 // 64x64 output tile, 256 threads, 4x4 outputs each, fp32 accumulation.

@@ -93,6 +93,10 @@ def test_decode_tile_boundaries(L, flags):
     (3, 3, 128, 128, "bf16"),      # d_out = 256 not filling a 256-wide tile evenly with 3 heads
     (6, 3, 128, 128, "bf16"),
     (5, 5, 128, 128, "bf16"),      # 4 predicted heads + odd retained count
+    (1, 1, 64, 0, "bf16"),         # one k-tile only (d_in = 64), one predicted head
+    (2, 2, 64, 64, "bf16"),        # three k-tiles (odd tail)
+    (2, 1, 128, 0, "bf16"),        # two k-tiles, G = 2
+    (1, 1, 64, 0, "f32"),
     (4, 2, 128, 128, "f32"),
     (8, 8, 64, 0, "f32"),
     (8, 4, 64, 256, "f32"),        # full retention fp32
@@ -375,3 +379,29 @@ def test_switch_from_full_cache_to_compressed_cache():
     with pytest.raises(ek.EchoKVError) as e:
         ek.cache_compress(shape, full, small)
     assert e.value.code == ek.ERR_CAPACITY
+
+
+# ---- the paper's own (S, m) presets on its models' KV layout (8 KV heads x 128) ----------
+# Appendix "Compression-Ratio Configurations": m = 384 (ratio 0.7), m = 0 (0.5), m = 64 (0.3;
+# the retained prefix ends in the middle of head 0).  S only says how many target layers
+# share an anchor; each (anchor, target) pair is one call.
+@pytest.mark.parametrize("flags", MODES)
+@pytest.mark.parametrize("m", [384, 0, 64, 192, 960])
+def test_decode_paper_presets(m, flags):
+    if flags == PACKED and m % 128:
+        pytest.skip("packed weights are not offered when a head is split")
+    w = synth.Workload(f"preset_m{m}", "bf16", 32, 8, 128, m, seed=50 + m, seq_lens=(700, 129))
+    run_decode_case(w, flags)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_split_head_prefill_and_reconstruct(dtype):
+    w = synth.Workload("preset_m64_pf", dtype, 8, 4, 128, 64, seed=61, seq_lens=(300,),
+                       prefill_len=260, prefill_q=200)
+    inp, dw = run_prefill_case(w)
+    k_out, v_out = dw.reconstruct(0, 5, 290); torch.cuda.synchronize()
+    k_ref, v_ref = ref.reconstruct_ref(inp, 0, 5, 290)
+    assert np.array_equal(host(k_out)[:, :64], k_ref[:, :64])
+    tol = 1e-5 if dtype == "f32" else 5e-3
+    assert error_metrics(host(k_out), k_ref)[1] <= tol and error_metrics(host(v_out), v_ref)[1] <= tol
+    run_decode_case(w.scaled(prefill_len=0, prefill_q=0), 0)
