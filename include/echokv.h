@@ -55,6 +55,8 @@ typedef enum { ECHOKV_BF16 = 0, ECHOKV_F32 = 1 } echokv_dtype;
                                   echokv_pack_weights ([D - m, D + m]); honoured by
                                   echokv_decode_attn on the fused bf16 path, every
                                   other use returns ECHOKV_ERR_UNSUPPORTED */
+#define ECHOKV_FLAG_STAGED 4u  /* with W_PACKED: use the register-staged main loop
+                                  instead of the direct-to-LDS one (comparison) */
 
 /* One (anchor, target) layer pair. */
 typedef struct {

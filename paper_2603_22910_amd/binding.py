@@ -19,6 +19,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_CAPACITY, ERR_WORKSPACE, ERR_UNSUPPORTED
 BF16, F32 = 0, 1
 FLAG_UNFUSED = 1
 FLAG_W_PACKED = 2
+FLAG_STAGED = 4
 
 EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn",

@@ -13,6 +13,7 @@
 #include "stream_kernels.h"
 #include "fused_decode.h"
 #include "fused_decode_f32.h"
+#include "fused_decode_dma.h"
 #include "prefill_kernels.h"
 
 using namespace echokv;
@@ -247,6 +248,12 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
                                        (const float*)an->k, (const float*)an->v, (const float*)tg->k,
                                        (const float*)tg->v, (const float*)wk, (const float*)wv, qq,
                                        po, pml, mt, &fused_step, st);
+        else if ((flags & ECHOKV_FLAG_W_PACKED) && !(flags & ECHOKV_FLAG_STAGED))
+          rc = launch_fused_decode_dma(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale,
+                                       (const bf16_t*)an->k, (const bf16_t*)an->v,
+                                       (const bf16_t*)tg->k, (const bf16_t*)tg->v,
+                                       (const bf16_t*)wk, (const bf16_t*)wv, (const bf16_t*)qq, po,
+                                       pml, mt, &fused_step, st);
         else
           rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale,
                                       (const T*)an->k, (const T*)an->v, (const T*)tg->k,

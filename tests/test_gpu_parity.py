@@ -16,9 +16,10 @@ import oracle_ref as ref
 pytestmark = pytest.mark.gpu
 
 TOL = {"bf16": (2e-2, 5e-3), "f32": (1e-5, 1e-5)}
-PACKED = "packed"      # fused path with weights re-laid out once by echokv_pack_weights
+PACKED = 1 << 20       # test-only marker: weights re-laid out once by echokv_pack_weights (direct-to-LDS kernel)
 MODES = [pytest.param(0, id="fused"), pytest.param(ek.FLAG_UNFUSED, id="unfused"),
-         pytest.param(PACKED, id="packed")]
+         pytest.param(PACKED, id="packed"),
+         pytest.param(PACKED | ek.FLAG_STAGED, id="packed_staged")]
 
 
 def check(got, want, dtype, what=""):
@@ -34,12 +35,13 @@ def host(t):
 
 
 def make_dw(inp, flags, **kw):
-    if flags == PACKED:
+    if flags & PACKED:
         w = inp.w
         if w.dtype != "bf16" or w.d_out == 0:
             pytest.skip("packed weights: bf16 fused path with something to predict only")
         dw = DeviceWorkload(inp, flags=0, **kw)
         dw.pack_weights()
+        dw.shape.flags |= flags & ek.FLAG_STAGED
         return dw
     return DeviceWorkload(inp, flags=flags, **kw)
 
@@ -150,10 +152,11 @@ def test_selector_weights_copy_heads_exactly(flags):
     inp = synth.generate(w)
     src = list(range(128, 256)) + [w.D + i for i in range(128)]     # anchor head 1, retained head 0
     inp.W_K = synth.selector_weights(w, src); inp.W_V = synth.selector_weights(w, src)
-    dw = DeviceWorkload(inp, flags=0 if flags == PACKED else flags)
+    dw = DeviceWorkload(inp, flags=0 if flags & PACKED else flags)
     k_out, v_out = dw.reconstruct(0, 0, 300); torch.cuda.synchronize()
-    if flags == PACKED:
+    if flags & PACKED:
         dw.pack_weights()
+        dw.shape.flags |= flags & ek.FLAG_STAGED
     X = torch.cat([inp.K_a[:300], inp.K_r[:300]], dim=1)
     assert torch.equal(k_out.cpu()[:, :256], inp.K_r[:300])
     assert torch.equal(k_out.cpu()[:, 256:], X[:, src])
@@ -388,7 +391,7 @@ def test_switch_from_full_cache_to_compressed_cache():
 @pytest.mark.parametrize("flags", MODES)
 @pytest.mark.parametrize("m", [384, 0, 64, 192, 960])
 def test_decode_paper_presets(m, flags):
-    if flags == PACKED and m % 128:
+    if flags & PACKED and m % 128:
         pytest.skip("packed weights are not offered when a head is split")
     w = synth.Workload(f"preset_m{m}", "bf16", 32, 8, 128, m, seed=50 + m, seq_lens=(700, 129))
     run_decode_case(w, flags)
