@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--unfused", action="store_true", help="time the unfused comparison path")
     ap.add_argument("--packed-weights", action="store_true",
                     help="lay W_K/W_V out once with echokv_pack_weights before the timed region")
+    ap.add_argument("--absorbed", action="store_true",
+                    help="time the weight-absorbed decode (same output, other association "
+                         "order, HBM-bound) instead of the fused reconstruct-then-attend kernel")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 1 GiB device copies (known HBM traffic) so a counter "
@@ -94,7 +97,7 @@ def main():
 
     w = synth.CONFIGS[args.config]
     inp = synth.generate(w)
-    flags = ek.FLAG_UNFUSED if args.unfused else 0
+    flags = ek.FLAG_UNFUSED if args.unfused else ek.FLAG_ABSORBED if args.absorbed else 0
     dw = DeviceWorkload(inp, flags=flags)
     if args.packed_weights:
         dw.pack_weights()
@@ -164,7 +167,15 @@ def main():
     flops = 4.0 * w.d_in * w.d_out * dec_tokens
     bytes_alg = dec_tokens * 2.0 * w.d_in * w.elem_size + 2.0 * w.d_in * w.d_out * w.elem_size
     roofline = None
-    if launches > 0 and kern_ms > 0:
+    if args.absorbed and launches > 0 and kern_ms > 0:
+        # the absorbed path's kernels together read every cache row and both weight matrices once
+        k_s = kern_ms / launches * 1e-3
+        ach = bytes_alg / k_s / 1e9
+        roofline = {"bound": "hbm", "kernel": "absorbed decode (scores_kernel + pv_kernel and 5 small ones)",
+                    "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
+                    "traffic": read_traffic(w.name + "_absorbed"), "kernel_ms": k_s * 1e3,
+                    "algorithmic_bytes": bytes_alg}
+    elif launches > 0 and kern_ms > 0:
         k_s = kern_ms / launches * 1e-3
         ach = flops / k_s / 1e12
         peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
@@ -182,7 +193,7 @@ def main():
         "config": {"workload": w.name, "batch": B, "context_tokens": tokens,
                    "H_q": w.n_q_heads, "H_kv": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_retained": w.n_retained, "d_in": w.d_in, "d_out": w.d_out,
-                   "path": "unfused" if args.unfused else "fused",
+                   "path": "unfused" if args.unfused else "absorbed" if args.absorbed else "fused",
                    "weights": "packed [d_out,d_in]" if args.packed_weights else "row-major [d_in,d_out]",
                    "step": "cache_append(anchor)+cache_append(target)+decode_attn"
                            + ("+prefill_attn" if has_prefill else ""),

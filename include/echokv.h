@@ -57,6 +57,13 @@ typedef enum { ECHOKV_BF16 = 0, ECHOKV_F32 = 1 } echokv_dtype;
                                   other use returns ECHOKV_ERR_UNSUPPORTED */
 #define ECHOKV_FLAG_STAGED 4u  /* with W_PACKED: use the register-staged main loop
                                   instead of the direct-to-LDS one (comparison) */
+#define ECHOKV_FLAG_ABSORBED 8u /* decode: same output in the other association order
+                                  (Eq. 3 is linear): queries are folded into W_K and
+                                  the probability-weighted sum of predictor inputs is
+                                  multiplied by W_V afterwards, so K-hat / V-hat are
+                                  never formed and every cache row is read once.
+                                  bf16 caches, row-major weights only; include the
+                                  flag in the shape passed to echokv_workspace_bytes */
 
 /* One (anchor, target) layer pair. */
 typedef struct {

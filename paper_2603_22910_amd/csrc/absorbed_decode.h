@@ -1,0 +1,630 @@
+// Weight-absorbed decode (gfx950, bf16 caches): the same attention output as
+// reconstruct-then-attend, evaluated in the other association order.
+//
+// The predictor is linear (Eq. 3) and, in this library's cache model, nothing
+// sits between reconstruction and the dot products of Eq. 7.  So with
+// x_j = [anchor_j ; retained_j] (length d_in) and, per query head h of KV head g,
+//     u_h[k] = sum_i Wt_K[k, g*d + i] q_h[i]        (Wt = W with the retained dims'
+//                                                    selector columns put back, Eq. 6)
+// the score is  s_j = x^K_j . u_h,  and the output is
+//     o_h[i] = sum_k ( sum_j p_j x^V_j[k] ) Wt_V[k, g*d + i].
+// Both token-sized products are skinny GEMMs (N = number of query heads) that
+// read every cache row exactly once: the path is HBM-bound, not MFMA-bound.
+//
+// Kernels (all launched back to back on the caller's stream):
+//   absorb_q      u = Wt_K q                       reads W_K once
+//   scores        S^T[h, j] = u_h . x^K_j          streams the K caches, MFMA
+//   softmax_stats per token split: M = max_j S, l = sum_j 2^(S - M)
+//   pv            Y_part[h, k] = sum_j 2^(S - M) x^V_j[k]   streams the V caches, MFMA
+//   y_sum         Y = merge of the splits' Y_part, normalised
+//   out_partial   O_part = Y Wt_V over a slice of k     reads W_V once
+//   out_final     out = sum of the slices
+// Both streaming loops move whole row segments (512 contiguous bytes per row):
+// the score pass through LDS, because its MFMA operand wants one token row per
+// lane; the value pass straight into registers, where 8 x 8 blocks are
+// transposed with byte permutes (the MFMA k-slot order is free as long as both
+// operands agree).
+#pragma once
+#include "common.h"
+#include "fused_decode.h"
+
+namespace echokv {
+namespace absorbed {
+
+using fused::rsrc_t; using fused::make_rsrc; using fused::u32x4_t;
+
+constexpr int kHB = 32;           // query heads per MFMA block
+constexpr int kTokTile = kSlotTokens;   // tokens per workgroup of the score pass
+constexpr int kScoreWaves = 8;
+constexpr int kColTile = 256;     // predictor-input columns per workgroup of the value pass
+constexpr int kPvWaves = 4;
+
+struct Args {
+  const bf16_t* xa[2];   // anchor cache K, V      [pool, D]
+  const bf16_t* xr[2];   // retained cache K, V    [pool, m]
+  const bf16_t* w[2];    // W_K, W_V               [D + m, d_out] row-major
+  const bf16_t* q;       // [nseq, H_q, d]
+  bf16_t* u;             // [nseq, H_pad, d_in]    absorbed queries, log2 units
+  float* s;              // [H_pad, s_ld]          scores, log2 units; column = slot * 128 + token
+  float* ml;             // [splits, H_pad, 2]     (max, sum) of each token split
+  float* ypart;          // [splits, H_pad, d_in]
+  float* y;              // [nseq, H_q, d_in]      normalised
+  float* opart;          // [k_slices, nseq, H_q, d]
+  void* out; float* lse;
+  int64_t out_seq0;
+  int32_t D, m, d_in, d_out, H_q, H_pad, G, d;
+  int32_t s_ld, split_tokens, n_col_a, n_col_tiles, k_slices, k_slice;
+  float qscale;          // softmax scale * log2(e)
+};
+
+// Element (k, f) of Wt: W[k, f - m] for a predicted dim f >= m, else the selector of
+// retained dim f (input row D + f).
+__device__ __forceinline__ void wt_row8(const bf16_t* w, int k, int f0, int m, int D, int d_out,
+                                        float (&o)[8]) {
+  if (f0 >= m) {
+    load16<bf16_t>(w + (int64_t)k * d_out + (f0 - m), o);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (k == D + f0 + i) ? 1.f : 0.f;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// u[b, h, k] = qscale * sum_i Wt_K[k, g*d + i] q[b, h, i]   (bf16), on MFMA:
+// C[pair, k] += Q[pair, i] Wt[k, i] with 32 (sequence, head-of-group) pairs as rows.
+// grid = (ceil(d_in / 128), H_kv), 4 waves of 32 input rows each; a wave keeps
+// its d / 16 Wt fragments in registers and walks over the pairs.
+// ---------------------------------------------------------------------------
+template <int HD>
+__global__ __launch_bounds__(256) void absorb_q_kernel(Args a, int nseq) {
+  constexpr int NS = HD / 16;
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lh = lane >> 5, wave = tid >> 6;
+  const int g = blockIdx.y;
+  const int k = blockIdx.x * 128 + wave * 32 + lr;
+  const int kc = min(k, a.d_in - 1);
+  u32x4_t wf[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) {
+    const int f0 = g * HD + 16 * s + 8 * lh;
+    if (f0 >= a.m) {
+      wf[s] = *reinterpret_cast<const u32x4_t*>(a.w[0] + (int64_t)kc * a.d_out + (f0 - a.m));
+    } else {               // selector columns of the retained dims (Eq. 6): bf16 ones at k == D + f
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        wf[s][p] = (kc == a.D + f0 + 2 * p ? 0x3F80u : 0u) | (kc == a.D + f0 + 2 * p + 1 ? 0x3F800000u : 0u);
+    }
+  }
+  const int npairs = nseq * a.G;
+  for (int p0 = 0; p0 < npairs; p0 += 32) {
+    const int pair = p0 + lr;
+    const bool ok = pair < npairs;
+    const int pc = ok ? pair : 0;
+    const bf16_t* qp = a.q + ((int64_t)(pc / a.G) * a.H_q + g * a.G + pc % a.G) * HD + 8 * lh;
+    floatx16_t acc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    u32x4_t qf[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) qf[s] = *reinterpret_cast<const u32x4_t*>(qp + 16 * s);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      u32x4_t qq = qf[s];
+      if (!ok) qq = u32x4_t{0u, 0u, 0u, 0u};
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, qq),
+                                                    __builtin_bit_cast(bf16x8_t, wf[s]), acc, 0, 0, 0);
+    }
+    if (k < a.d_in) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int pr = p0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+        if (pr < npairs)
+          a.u[((int64_t)(pr / a.G) * a.H_pad + g * a.G + pr % a.G) * a.d_in + k] = f32_to_bf16(acc[r] * a.qscale);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Score pass.  One workgroup (8 waves) = one 128-token slot of one sequence x
+// one block of 32 query heads.  MFMA form: C[head, token] += U[head, k] X[token, k],
+// so a lane owns a token column and the stores to S^T are 128-byte rows.
+//
+// The MFMA operand layout wants, per lane, 16 bytes of a different token row:
+// loaded straight from global memory that is 32 rows x 32 bytes per
+// instruction, a pattern that reaches about half of the streaming bandwidth.
+// So the X tile goes HBM -> LDS in stages of 256 input dims with
+// `buffer_load ... lds`, one instruction moving 2 rows x 512 contiguous bytes,
+// and the fragments are read back from LDS (chunk c of row r sits at slot
+// c ^ (r % 32): conflict-free 16-byte reads down a column).  Two stages of
+// 64 KB; inside a stage wave w multiplies input dims [32 w, 32 w + 32) for all
+// 128 tokens, with its U fragments loaded from global memory (L2-resident).
+// The waves' partial sums meet once in LDS at the end.
+// ---------------------------------------------------------------------------
+#ifndef ECHOKV_LDS
+#define ECHOKV_LDS __attribute__((address_space(3)))
+#endif
+constexpr int kStageK = 256;                              // input dims per LDS stage
+constexpr int kStageBytes = kTokTile * kStageK * 2;       // 64 KB
+
+struct ScoreIo {
+  const bf16_t* pa; const bf16_t* pr;
+  rsrc_t ru;
+  uint32_t D2, m2, uoff;
+  int D, m, nsa, ns, last;
+};
+
+struct StageDesc { bool anchor; int k0, kw, kg0; };
+__device__ __forceinline__ StageDesc stage_desc(const ScoreIo& io, int t) {
+  t = min(t, io.ns - 1);
+  StageDesc d;
+  d.anchor = t < io.nsa;
+  d.k0 = (d.anchor ? t : t - io.nsa) * kStageK;
+  d.kw = min(kStageK, (d.anchor ? io.D : io.m) - d.k0);
+  d.kg0 = d.anchor ? d.k0 : io.D + d.k0;
+  return d;
+}
+
+// this wave's 8 direct-to-LDS loads of stage t (rows 16 w .. 16 w + 15) and its 2 U fragments
+__device__ __forceinline__ void score_issue(char* buf, u32x4_t (&u)[2], const ScoreIo& io, int t,
+                                            int wave, int lane) {
+  const StageDesc d = stage_desc(io, t);
+  const rsrc_t rx = make_rsrc(d.anchor ? io.pa : io.pr);
+  const uint32_t ld2 = d.anchor ? io.D2 : io.m2;
+  const int nchunk = d.kw / 8;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int row = wave * 16 + 2 * i + (lane >> 5);
+    const int chunk = min((lane & 31) ^ (row & 31), nchunk - 1);     // a partial stage repeats its last chunk
+    const uint32_t voff = __umul24((uint32_t)min(row, io.last), ld2) + (uint32_t)chunk * 16;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (ECHOKV_LDS void*)(buf + (wave * 16 + 2 * i) * (kStageK * 2)),
+                                             16, voff, d.k0 * 2, 0, 0);
+  }
+  const int kw0 = 32 * wave < d.kw ? 32 * wave : 0;
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
+    u[s] = __builtin_amdgcn_raw_buffer_load_b128(io.ru, io.uoff, (d.kg0 + kw0 + 16 * s) * 2, 0);
+}
+
+__device__ __forceinline__ void score_wait_landed() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | 10);     // vmcnt(10): only the younger stage (8 + 2 loads) may be in flight
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+__device__ __forceinline__ void score_wait_read() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0): own fragment reads returned
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+__device__ __forceinline__ void score_stage(floatx16_t (&acc)[4], char* buf, u32x4_t (&u)[2],
+                                            const ScoreIo& io, int t, int wave, int lane, bool head_ok) {
+  const int lr = lane & 31, lh = lane >> 5;
+  const StageDesc d = stage_desc(io, t);
+  const bool active = head_ok && t < io.ns && 32 * wave < d.kw;
+  score_wait_landed();                          // stage t is in LDS for every wave
+  u32x4_t xf[4][2];
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+      xf[tb][s] = *reinterpret_cast<const u32x4_t*>(buf + (tb * 32 + lr) * (kStageK * 2) +
+                                                    (((4 * wave + 2 * s + lh) ^ lr) << 4));
+  score_wait_read();                            // every wave holds its fragments: the buffer is free
+  u32x4_t uc[2] = {u[0], u[1]};
+  score_issue(buf, u, io, t + 2, wave, lane);
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    u32x4_t uu = uc[s];
+    if (!active) uu = u32x4_t{0u, 0u, 0u, 0u};
+    const bf16x8_t ua = __builtin_bit_cast(bf16x8_t, uu);
+#pragma unroll
+    for (int tb = 0; tb < 4; ++tb)
+      acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua, __builtin_bit_cast(bf16x8_t, xf[tb][s]),
+                                                        acc[tb], 0, 0, 0);
+  }
+}
+
+__global__ __launch_bounds__(kScoreWaves * 64) void scores_kernel(Args a, SeqMeta meta) {
+  __shared__ __attribute__((aligned(1024))) char lds[2 * kStageBytes];     // 128 KB
+  const int slot = blockIdx.x, hb = blockIdx.y;
+  const int b = find_seq(meta.sbase, meta.n, slot);
+  const int L = meta.len[b];
+  const int j0 = (slot - meta.sbase[b]) * kTokTile;
+  const int64_t row0 = meta.start[b] + j0;
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  ScoreIo io;
+  io.pa = a.xa[0] + row0 * a.D; io.pr = a.xr[0] + row0 * a.m;
+  io.ru = make_rsrc(a.u + ((int64_t)b * a.H_pad + hb * kHB) * a.d_in);
+  io.D2 = (uint32_t)a.D * 2; io.m2 = (uint32_t)a.m * 2;
+  io.uoff = (uint32_t)lr * (uint32_t)a.d_in * 2 + (uint32_t)lh * 16;
+  io.D = a.D; io.m = a.m;
+  io.nsa = (a.D + kStageK - 1) / kStageK; io.ns = io.nsa + (a.m + kStageK - 1) / kStageK;
+  io.last = min(kTokTile, L - j0) - 1;
+  const bool head_ok = hb * kHB + lr < a.H_q;
+
+  floatx16_t acc[4];
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;
+
+  // stage t lives in buffer t % 2; stages past the last one repeat it with a zeroed U
+  // fragment, so every wave runs the same barriers
+  u32x4_t u0[2], u1[2];
+  score_issue(lds, u0, io, 0, wave, lane);
+  score_issue(lds + kStageBytes, u1, io, 1, wave, lane);
+  for (int t = 0; t < io.ns; t += 2) {
+    score_stage(acc, lds, u0, io, t, wave, lane, head_ok);
+    score_stage(acc, lds + kStageBytes, u1, io, t + 1, wave, lane, head_ok);
+  }
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): the look-ahead loads have landed
+  __syncthreads();
+
+  float* red = reinterpret_cast<float*>(lds);    // [wave][token block][acc row][lane]
+#pragma unroll
+  for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) red[((wave * 4 + tb) * 16 + r) * 64 + lane] = acc[tb][r];
+  __syncthreads();
+  // wave w adds up token block w / 2, accumulator rows 8 (w % 2) .. + 8
+  const int tb = wave >> 1, r0 = (wave & 1) * 8;
+  float* srow = a.s + (int64_t)slot * kTokTile + tb * 32 + lr;
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < kScoreWaves; ++w) v += red[((w * 4 + tb) * 16 + r0 + r) * 64 + lane];
+    const int head = 8 * ((r0 + r) >> 2) + 4 * lh + (r & 3);      // accumulator row -> head
+    srow[(int64_t)(hb * kHB + head) * a.s_ld] = v;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// (max, sum of 2^(S - max)) of one (token split, head) piece of a row of S^T.
+// grid = (H_q, splits), 256 threads.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void softmax_stats_kernel(Args a, SeqMeta meta) {
+  const int h = blockIdx.x, sp = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int b = find_seq(meta.tbase, meta.n, sp);
+  const int t_begin = (sp - meta.tbase[b]) * a.split_tokens;
+  const int n = min(meta.len[b] - t_begin, a.split_tokens);
+  const float* row = a.s + (int64_t)h * a.s_ld + (int64_t)meta.sbase[b] * kSlotTokens + t_begin;
+  __shared__ float s_red[4];
+  float M = -INFINITY;
+  for (int j = tid; j < n; j += 256) M = fmaxf(M, row[j]);
+  M = wave_max(M, 64);
+  if (lane == 0) s_red[wave] = M;
+  __syncthreads();
+  M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+  float l = 0.f;
+  for (int j = tid; j < n; j += 256) l += exp2f(row[j] - M);
+  l = wave_sum(l, 64);
+  __syncthreads();
+  if (lane == 0) s_red[wave] = l;
+  __syncthreads();
+  if (tid == 0) {
+    float* ml = a.ml + ((int64_t)sp * a.H_pad + h) * 2;
+    ml[0] = M; ml[1] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Value pass.  One workgroup = one token split of one sequence x 256 input
+// columns (anchor columns or retained columns, never both) x 32 query heads;
+// its 4 waves take every 4th step of 16 tokens.
+// MFMA form: C[head, col] += P^T[head, token] X[token, col].  A lane loads, for
+// 8 consecutive columns, the 8 token rows of its half (512-byte row segments
+// across the wave), transposes the 8 x 8 block in registers and so owns
+// column 8 * (lane % 32) + i of MFMA i.
+// ---------------------------------------------------------------------------
+struct PvStage {
+  u32x4_t x[8];      // token lh * 8 + e, 8 columns
+  u32x4_t s[2];      // 8 scores of head lane % 32
+};
+
+struct PvIo {
+  rsrc_t rx, rs;
+  uint32_t pitch2, colb, soff0;
+  int nrows, nsteps;
+  int lh8;
+};
+
+__device__ __forceinline__ void pv_fetch(PvStage& st, const PvIo& io, int step) {
+  step = min(step, io.nsteps - 1);
+  const int t0 = step * 16 + io.lh8;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t row = (uint32_t)min(t0 + e, io.nrows - 1);
+    st.x[e] = __builtin_amdgcn_raw_buffer_load_b128(io.rx, __umul24(row, io.pitch2) + io.colb, 0, 0);
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+    st.s[i] = __builtin_amdgcn_raw_buffer_load_b128(io.rs, io.soff0 + i * 16, step * 64, 0);
+}
+
+__device__ __forceinline__ void pv_mma(floatx16_t (&acc)[8], const PvStage& st, const PvIo& io,
+                                       int step, float M) {
+  // probabilities of this lane's head for its 8 tokens (0 beyond the split's end)
+  const int t0 = step * 16 + io.lh8;
+  u32x4_t pw;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float s0 = __uint_as_float(st.s[i >> 1][(2 * i) & 3]);
+    const float s1 = __uint_as_float(st.s[i >> 1][(2 * i + 1) & 3]);
+    const float p0 = (t0 + 2 * i < io.nrows) ? exp2f(s0 - M) : 0.f;
+    const float p1 = (t0 + 2 * i + 1 < io.nrows) ? exp2f(s1 - M) : 0.f;
+    pw[i] = (uint32_t)f32_to_bf16(p0) | ((uint32_t)f32_to_bf16(p1) << 16);
+  }
+  const bf16x8_t pa = __builtin_bit_cast(bf16x8_t, pw);
+  // 8 x 8 transpose: word p of output i holds tokens 2p, 2p + 1 of column i
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    u32x4_t xt;
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+      xt[p] = __builtin_amdgcn_perm(st.x[2 * p + 1][i >> 1], st.x[2 * p][i >> 1],
+                                    (i & 1) ? 0x07060302u : 0x05040100u);
+    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, __builtin_bit_cast(bf16x8_t, xt), acc[i], 0, 0, 0);
+  }
+}
+
+__global__ __launch_bounds__(kPvWaves * 64) void pv_kernel(Args a, SeqMeta meta) {
+  __shared__ float red[2][128][64];       // 64 KB: two waves' accumulators
+  const int ct = blockIdx.x % a.n_col_tiles, sp = blockIdx.x / a.n_col_tiles, hb = blockIdx.y;
+  const int b = find_seq(meta.tbase, meta.n, sp);
+  const int L = meta.len[b];
+  const int t_begin = (sp - meta.tbase[b]) * a.split_tokens;
+  const int nrows = min(L - t_begin, a.split_tokens);
+  const bool anchor = ct < a.n_col_a;
+  const int c0 = (anchor ? ct : ct - a.n_col_a) * kColTile;
+  const int width = anchor ? a.D : a.m;
+  const int64_t row0 = meta.start[b] + t_begin;
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = c0 + 8 * lr;
+  const bool col_ok = col < width;
+
+  PvIo io;
+  io.rx = make_rsrc((anchor ? a.xa[1] : a.xr[1]) + row0 * width);
+  io.rs = make_rsrc(a.s + (int64_t)hb * kHB * a.s_ld + (int64_t)meta.sbase[b] * kSlotTokens + t_begin);
+  io.pitch2 = (uint32_t)width * 2;
+  io.colb = (uint32_t)(col_ok ? col : 0) * 2;
+  io.soff0 = ((uint32_t)lr * (uint32_t)a.s_ld + (uint32_t)lh * 8) * 4;
+  io.nrows = nrows; io.nsteps = (nrows + 15) / 16; io.lh8 = lh * 8;
+  const int head = hb * kHB + lr;
+  const float M = head < a.H_q ? a.ml[((int64_t)sp * a.H_pad + head) * 2] : 0.f;   // the split's own maximum
+
+  floatx16_t acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  // three register stages, branch-free body: rounds past the wave's last step
+  // re-read the split's last step with all probabilities masked to zero
+  PvStage s0, s1, s2;
+  const int n = io.nsteps;
+  const int nw = (n - wave + kPvWaves - 1) / kPvWaves;
+  pv_fetch(s0, io, wave);
+  pv_fetch(s1, io, wave + kPvWaves);
+  for (int it = 0; it < nw; it += 3) {
+    const int st = wave + it * kPvWaves;
+    pv_fetch(s2, io, st + 2 * kPvWaves);
+    pv_mma(acc, s0, io, st, M);
+    pv_fetch(s0, io, st + 3 * kPvWaves);
+    pv_mma(acc, s1, io, st + kPvWaves, M);
+    pv_fetch(s1, io, st + 4 * kPvWaves);
+    pv_mma(acc, s2, io, st + 2 * kPvWaves, M);
+  }
+
+  // tree reduction over the 4 waves: {2, 3} -> {0, 1}, then 1 -> 0
+  if (wave >= 2) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[wave - 2][i * 16 + r][lane] = acc[i][r];
+  }
+  __syncthreads();
+  if (wave < 2) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][r] += red[wave][i * 16 + r][lane];
+  }
+  __syncthreads();
+  if (wave == 1) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[0][i * 16 + r][lane] = acc[i][r];
+  }
+  __syncthreads();
+  if (wave != 0 || !col_ok) return;
+  float* yp = a.ypart + ((int64_t)sp * a.H_pad + hb * kHB) * a.d_in + (anchor ? 0 : a.D) + col;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int hr = 8 * (r >> 2) + 4 * lh + (r & 3);
+    float4 lo, hi;
+    lo.x = acc[0][r] + red[0][0 * 16 + r][lane]; lo.y = acc[1][r] + red[0][1 * 16 + r][lane];
+    lo.z = acc[2][r] + red[0][2 * 16 + r][lane]; lo.w = acc[3][r] + red[0][3 * 16 + r][lane];
+    hi.x = acc[4][r] + red[0][4 * 16 + r][lane]; hi.y = acc[5][r] + red[0][5 * 16 + r][lane];
+    hi.z = acc[6][r] + red[0][6 * 16 + r][lane]; hi.w = acc[7][r] + red[0][7 * 16 + r][lane];
+    float* dst = yp + (int64_t)hr * a.d_in;
+    *reinterpret_cast<float4*>(dst) = lo;
+    *reinterpret_cast<float4*>(dst + 4) = hi;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Merge of a sequence's token splits (exact re-association of the softmax):
+//   M = max_s M_s,  l = sum_s l_s 2^(M_s - M),  y[b, h, k] = sum_s 2^(M_s - M) ypart_s[h, k] / l
+// and the log-sum-exp.  grid = (d_in / 256, H_q, nseq); 256 threads = 64 column
+// quads x 4 groups that each take every 4th split.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void y_sum_kernel(Args a, SeqMeta meta) {
+  const int h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x, cq = tid & 63, sg = tid >> 6;
+  const int k = min(blockIdx.x * 256 + cq * 4, a.d_in - 4);    // tail threads repeat the last quad
+  const int s0 = meta.tbase[b], ns = meta.tbase[b + 1] - s0;
+  __shared__ float4 red[4][64];
+  const float* mlp = a.ml + ((int64_t)s0 * a.H_pad + h) * 2;
+  const int64_t mls = (int64_t)a.H_pad * 2;
+  float M = -INFINITY;
+  for (int i = 0; i < ns; ++i) M = fmaxf(M, mlp[i * mls]);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float l = 0.f;
+#pragma unroll 4
+  for (int i = sg; i < ns; i += 4) {
+    const float wgt = exp2f(mlp[i * mls] - M);
+    l += wgt * mlp[i * mls + 1];
+    const float4 v = *reinterpret_cast<const float4*>(a.ypart + ((int64_t)(s0 + i) * a.H_pad + h) * a.d_in + k);
+    acc.x = fmaf(wgt, v.x, acc.x); acc.y = fmaf(wgt, v.y, acc.y);
+    acc.z = fmaf(wgt, v.z, acc.z); acc.w = fmaf(wgt, v.w, acc.w);
+  }
+  red[sg][cq] = acc;
+  __shared__ float lred[4];
+  if (cq == 0) lred[sg] = l;
+  __syncthreads();
+  if (sg != 0) return;
+  l = (lred[0] + lred[1]) + (lred[2] + lred[3]);
+  const float inv = 1.f / l;
+  float4 r;
+  r.x = ((red[0][cq].x + red[1][cq].x) + (red[2][cq].x + red[3][cq].x)) * inv;
+  r.y = ((red[0][cq].y + red[1][cq].y) + (red[2][cq].y + red[3][cq].y)) * inv;
+  r.z = ((red[0][cq].z + red[1][cq].z) + (red[2][cq].z + red[3][cq].z)) * inv;
+  r.w = ((red[0][cq].w + red[1][cq].w) + (red[2][cq].w + red[3][cq].w)) * inv;
+  *reinterpret_cast<float4*>(a.y + ((int64_t)b * a.H_q + h) * a.d_in + k) = r;
+  if (a.lse && blockIdx.x == 0 && cq == 0)
+    a.lse[(a.out_seq0 + b) * a.H_q + h] = (M + log2f(l)) * 0.6931471805599453f;
+}
+
+// ---------------------------------------------------------------------------
+// opart[ks, b, h, i] = sum over k in slice ks of y[b, h, k] Wt_V[k, g*d + i], on MFMA:
+// C[pair, i] += Y[pair, k] Wt[k, i].  y goes in as a bf16 (high, low) pair, so
+// the product keeps fp32-like accuracy.  The contraction runs down the rows of
+// W_V, so a lane loads 8 rows x (d / 32) columns and transposes them in
+// registers; it owns columns (d / 32) * (lane % 32) + i.
+// grid = (H_kv, k_slices, ceil(nseq * G / 32)); the 4 waves take every 4th step
+// of 16 input rows and meet in LDS.
+// ---------------------------------------------------------------------------
+template <int HD>
+struct OutStage {
+  uint32_t x[8][HD / 64];     // 8 input rows x (d / 32) bf16 columns
+  float4 y[2];                // 8 consecutive y values of this lane's pair
+};
+
+template <int HD>
+__global__ __launch_bounds__(256) void out_partial_kernel(Args a, int nseq) {
+  constexpr int CPL = HD / 32, WPL = HD / 64;      // columns, 32-bit words per lane and row
+  __shared__ float red[3][CPL * 16][64];
+  const int g = blockIdx.x, ks = blockIdx.y, p0 = blockIdx.z * 32;
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 31, lh = lane >> 5, wave = tid >> 6;
+  const int npairs = nseq * a.G;
+  const int k0 = ks * a.k_slice, kn = min(a.k_slice, a.d_in - k0), nsteps = kn / 16;
+  const int pair = p0 + lr;
+  const bool ok = pair < npairs;
+  const int pc = ok ? pair : 0;
+  const float* yrow = a.y + ((int64_t)(pc / a.G) * a.H_q + g * a.G + pc % a.G) * a.d_in + k0 + lh * 8;
+  const int f0 = g * HD + CPL * lr;
+  const bool pred = f0 >= a.m;
+  const bf16_t* wcol = a.w[1] + (int64_t)(k0 + lh * 8) * a.d_out + (pred ? f0 - a.m : 0);
+
+  auto fetch = [&](OutStage<HD>& st, int step) {
+    step = min(step, nsteps - 1);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int kk = step * 16 + e;
+      if (pred) {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(wcol + (int64_t)kk * a.d_out);
+#pragma unroll
+        for (int w = 0; w < WPL; ++w) st.x[e][w] = src[w];
+      } else {
+        const int kg = k0 + lh * 8 + kk;           // selector columns of the retained dims (Eq. 6)
+#pragma unroll
+        for (int w = 0; w < WPL; ++w)
+          st.x[e][w] = (kg == a.D + f0 + 2 * w ? 0x3F80u : 0u) | (kg == a.D + f0 + 2 * w + 1 ? 0x3F800000u : 0u);
+      }
+    }
+    st.y[0] = *reinterpret_cast<const float4*>(yrow + step * 16);
+    st.y[1] = *reinterpret_cast<const float4*>(yrow + step * 16 + 4);
+  };
+  floatx16_t acc[CPL];
+#pragma unroll
+  for (int i = 0; i < CPL; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+  auto mma = [&](const OutStage<HD>& st, bool live) {
+    const float yv[8] = {st.y[0].x, st.y[0].y, st.y[0].z, st.y[0].w, st.y[1].x, st.y[1].y, st.y[1].z, st.y[1].w};
+    u32x4_t hi, lo;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      uint32_t h2[2], l2[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const float v = live ? yv[2 * p + q] : 0.f;
+        const bf16_t hb = f32_to_bf16(v);
+        h2[q] = hb; l2[q] = f32_to_bf16(v - bf16_to_f32(hb));
+      }
+      hi[p] = h2[0] | (h2[1] << 16); lo[p] = l2[0] | (l2[1] << 16);
+    }
+#pragma unroll
+    for (int i = 0; i < CPL; ++i) {
+      u32x4_t xt;
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        xt[p] = __builtin_amdgcn_perm(st.x[2 * p + 1][i >> 1], st.x[2 * p][i >> 1],
+                                      (i & 1) ? 0x07060302u : 0x05040100u);
+      const bf16x8_t xb = __builtin_bit_cast(bf16x8_t, xt);
+      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, hi), xb, acc[i], 0, 0, 0);
+      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, lo), xb, acc[i], 0, 0, 0);
+    }
+  };
+  OutStage<HD> s0, s1;
+  const int nw = (nsteps - wave + 3) / 4;
+  fetch(s0, wave);
+  for (int it = 0; it < nw; it += 2) {
+    const int st = wave + it * 4;
+    fetch(s1, st + 4);
+    mma(s0, ok);
+    fetch(s0, st + 8);
+    mma(s1, ok && it + 1 < nw);
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int i = 0; i < CPL; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[wave - 1][i * 16 + r][lane] = acc[i][r];
+  }
+  __syncthreads();
+  if (wave > 0) return;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int pr = p0 + 8 * (r >> 2) + 4 * lh + (r & 3);
+    if (pr >= npairs) continue;
+    float* dst = a.opart + (((int64_t)ks * nseq + pr / a.G) * a.H_q + g * a.G + pr % a.G) * HD + CPL * lr;
+#pragma unroll
+    for (int i = 0; i < CPL; ++i)
+      dst[i] = acc[i][r] + ((red[0][i * 16 + r][lane] + red[1][i * 16 + r][lane]) + red[2][i * 16 + r][lane]);
+  }
+}
+
+// out[b, h, :] = sum over k slices of opart.  grid = ceil(nseq * H_q * d / 256).
+template <typename TO>
+__global__ __launch_bounds__(256) void out_final_kernel(Args a, int nseq) {
+  const int64_t n = (int64_t)nseq * a.H_q * a.d;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= n) return;
+  float v = 0.f;
+#pragma unroll 4
+  for (int ks = 0; ks < a.k_slices; ++ks) v += a.opart[(int64_t)ks * n + idx];
+  TO* out = (TO*)a.out + a.out_seq0 * a.H_q * a.d;
+  if constexpr (sizeof(TO) == 2) out[idx] = f32_to_bf16(v);
+  else out[idx] = v;
+}
+
+}  // namespace absorbed
+}  // namespace echokv

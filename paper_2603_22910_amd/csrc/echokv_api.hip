@@ -15,6 +15,7 @@
 #include "fused_decode_f32.h"
 #include "fused_decode_dma.h"
 #include "prefill_kernels.h"
+#include "absorbed_decode.h"
 
 using namespace echokv;
 
@@ -422,6 +423,129 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
   return ECHOKV_OK;
 }
 
+// ---- weight-absorbed decode: workspace plan and launches ------------------
+struct AbsPlan {
+  size_t off_u, off_s, off_ml, off_yp, off_y, off_op, total;
+  int H_pad, n_col_a, n_col_tiles, k_slices, k_slice;
+};
+inline int abs_col_tiles(int width) { return (width + absorbed::kColTile - 1) / absorbed::kColTile; }
+// tokens per split of the value pass: enough workgroups to fill the chip, few partial sums
+int abs_split_tokens(const Dims& dm, int64_t tokens) {
+  const int nct = abs_col_tiles(dm.D) + abs_col_tiles(dm.m);
+  int ts = 1024;
+  while ((tokens / ts) * nct > 2048 && ts < 32768) ts <<= 1;
+  return ts;
+}
+AbsPlan plan_absorbed(const Dims& dm, int nseq, int64_t slots, int64_t splits) {
+  AbsPlan p;
+  p.H_pad = (dm.H_q + absorbed::kHB - 1) / absorbed::kHB * absorbed::kHB;
+  p.n_col_a = abs_col_tiles(dm.D);
+  p.n_col_tiles = p.n_col_a + abs_col_tiles(dm.m);
+  p.k_slices = std::max(1, std::min(16, dm.d_in / 512));
+  p.k_slice = ((dm.d_in + p.k_slices - 1) / p.k_slices + 63) / 64 * 64;
+  p.k_slices = (dm.d_in + p.k_slice - 1) / p.k_slice;
+  size_t o = 0;
+  p.off_u = o;  o += align_up((size_t)nseq * p.H_pad * dm.d_in * 2);
+  p.off_s = o;  o += align_up((size_t)p.H_pad * slots * kSlotTokens * 4);
+  p.off_ml = o; o += align_up((size_t)splits * p.H_pad * 2 * 4);
+  p.off_yp = o; o += align_up((size_t)splits * p.H_pad * dm.d_in * 4);
+  p.off_y = o;  o += align_up((size_t)nseq * dm.H_q * dm.d_in * 4);
+  p.off_op = o; o += align_up((size_t)p.k_slices * nseq * dm.H_q * dm.d * 4);
+  p.total = o;
+  return p;
+}
+// upper bound for any launch group of a batch holding total_tokens tokens
+size_t absorbed_ws_bytes(const Dims& dm, int batch, int64_t total_tokens) {
+  const int n = std::min(batch, kMaxSeqPerLaunch);
+  return plan_absorbed(dm, n, total_tokens / kSlotTokens + n, total_tokens / 1024 + n).total;
+}
+bool absorbed_supported(const Dims& dm, uint32_t flags) {
+  return dm.bf16 && !(flags & (ECHOKV_FLAG_UNFUSED | ECHOKV_FLAG_W_PACKED | ECHOKV_FLAG_STAGED));
+}
+
+// Fills mt for group [b0, b0 + n) and returns (slots, splits, split_tokens) through the plan inputs.
+int absorbed_group(const Dims& dm, const echokv_layer_cache* an, int b0, SeqMeta& mt,
+                   int* slots, int* splits, int* split_tokens) {
+  mt.n = std::min(kMaxSeqPerLaunch, an->batch - b0);
+  int64_t tokens = 0;
+  for (int b = 0; b < mt.n; ++b) {
+    mt.start[b] = an->seq_start[b0 + b]; mt.len[b] = an->seq_len[b0 + b]; tokens += mt.len[b];
+  }
+  *slots = fill_slots(mt);
+  *split_tokens = abs_split_tokens(dm, tokens);
+  *splits = fill_tiles(mt, *split_tokens);
+  // 32-bit byte offsets inside the score matrix
+  if ((int64_t)*slots * kSlotTokens * 4 * absorbed::kHB >= (int64_t)1 << 31) return ECHOKV_ERR_UNSUPPORTED;
+  return ECHOKV_OK;
+}
+
+size_t absorbed_need(const Dims& dm, const echokv_layer_cache* an) {
+  size_t need = 0;
+  for (int b0 = 0; b0 < an->batch; b0 += kMaxSeqPerLaunch) {
+    SeqMeta mt; int slots, splits, ts;
+    if (absorbed_group(dm, an, b0, mt, &slots, &splits, &ts)) return (size_t)-1;
+    need = std::max(need, plan_absorbed(dm, mt.n, slots, splits).total);
+  }
+  return need;
+}
+
+int absorbed_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_layer_cache* tg,
+                  const void* w_k, const void* w_v, const void* q, void* out, float* lse, char* ws,
+                  hipStream_t st) {
+  for (int b0 = 0; b0 < an->batch; b0 += kMaxSeqPerLaunch) {
+    SeqMeta mt; int slots, splits, ts;
+    int rc = absorbed_group(dm, an, b0, mt, &slots, &splits, &ts);
+    if (rc) return rc;
+    const AbsPlan pl = plan_absorbed(dm, mt.n, slots, splits);
+    absorbed::Args a;
+    a.xa[0] = (const bf16_t*)an->k; a.xa[1] = (const bf16_t*)an->v;
+    a.xr[0] = (const bf16_t*)tg->k; a.xr[1] = (const bf16_t*)tg->v;
+    a.w[0] = (const bf16_t*)w_k; a.w[1] = (const bf16_t*)w_v;
+    a.q = (const bf16_t*)q + (int64_t)b0 * dm.H_q * dm.d;
+    a.u = (bf16_t*)(ws + pl.off_u); a.s = (float*)(ws + pl.off_s); a.ml = (float*)(ws + pl.off_ml);
+    a.ypart = (float*)(ws + pl.off_yp); a.y = (float*)(ws + pl.off_y); a.opart = (float*)(ws + pl.off_op);
+    a.out = out; a.lse = lse; a.out_seq0 = b0;
+    a.D = dm.D; a.m = dm.m; a.d_in = dm.d_in; a.d_out = dm.d_out; a.H_q = dm.H_q; a.H_pad = pl.H_pad;
+    a.G = dm.G; a.d = dm.d;
+    a.s_ld = slots * kSlotTokens; a.split_tokens = ts; a.n_col_a = pl.n_col_a;
+    a.n_col_tiles = pl.n_col_tiles; a.k_slices = pl.k_slices; a.k_slice = pl.k_slice;
+    a.qscale = dm.scale * 1.4426950408889634f;
+    const int nhb = pl.H_pad / absorbed::kHB;
+    const int n = mt.n;
+
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (g_prof.on) {
+      if (!g_prof.get(&e0) || !g_prof.get(&e1)) return ECHOKV_ERR_HIP;
+      HIP_TRY(hipEventRecord(e0, st));
+    }
+    const dim3 qg((dm.d_in + 127) / 128, dm.H_kv);
+    if (dm.d == 128) hipLaunchKernelGGL((absorbed::absorb_q_kernel<128>), qg, dim3(256), 0, st, a, n);
+    else hipLaunchKernelGGL((absorbed::absorb_q_kernel<64>), qg, dim3(256), 0, st, a, n);
+    LAUNCH_CHECK();
+    hipLaunchKernelGGL(absorbed::scores_kernel, dim3(slots, nhb), dim3(absorbed::kScoreWaves * 64), 0, st, a, mt);
+    LAUNCH_CHECK();
+    hipLaunchKernelGGL(absorbed::softmax_stats_kernel, dim3(dm.H_q, splits), dim3(256), 0, st, a, mt);
+    LAUNCH_CHECK();
+    hipLaunchKernelGGL(absorbed::pv_kernel, dim3(splits * pl.n_col_tiles, nhb), dim3(absorbed::kPvWaves * 64), 0, st, a, mt);
+    LAUNCH_CHECK();
+    hipLaunchKernelGGL(absorbed::y_sum_kernel, dim3((dm.d_in + 255) / 256, dm.H_q, n), dim3(256), 0, st, a, mt);
+    LAUNCH_CHECK();
+    const dim3 og(dm.H_kv, pl.k_slices, (n * dm.G + 31) / 32);
+    if (dm.d == 128) hipLaunchKernelGGL((absorbed::out_partial_kernel<128>), og, dim3(256), 0, st, a, n);
+    else hipLaunchKernelGGL((absorbed::out_partial_kernel<64>), og, dim3(256), 0, st, a, n);
+    LAUNCH_CHECK();
+    const int fb = (int)(((int64_t)n * dm.H_q * dm.d + 255) / 256);
+    if (dm.out_bf16) hipLaunchKernelGGL((absorbed::out_final_kernel<bf16_t>), dim3(fb), dim3(256), 0, st, a, n);
+    else hipLaunchKernelGGL((absorbed::out_final_kernel<float>), dim3(fb), dim3(256), 0, st, a, n);
+    LAUNCH_CHECK();
+    if (g_prof.on) {
+      HIP_TRY(hipEventRecord(e1, st));
+      g_prof.pairs.emplace_back(e0, e1);
+    }
+  }
+  return ECHOKV_OK;
+}
+
 size_t decode_ws_bytes(const Dims& dm, int batch, int64_t total_tokens, bool unfused) {
   const int64_t slots = total_tokens / kSlotTokens + batch;
   return plan_ws(dm, slots, unfused ? slots * kSlotTokens : 0).total;
@@ -453,6 +577,8 @@ size_t echokv_workspace_bytes(const echokv_shape* shape, int32_t batch, int64_t 
   Dims dm;
   if (check_shape(shape, &dm) != ECHOKV_OK || batch <= 0 || total_tokens <= 0 || max_q < 0) return 0;
   size_t need = decode_ws_bytes(dm, batch, total_tokens, true);
+  if ((shape->flags & ECHOKV_FLAG_ABSORBED) && absorbed_supported(dm, shape->flags))
+    need = std::max(need, absorbed_ws_bytes(dm, batch, total_tokens));
   if (max_q > 1) need = std::max(need, prefill_ws_bytes(dm, total_tokens, max_q));
   return need;
 }
@@ -613,6 +739,15 @@ int echokv_decode_attn(const echokv_shape* shape, const echokv_layer_cache* anch
       s += slots_for(anchor->seq_len[b]);
     }
     max_chunk_slots = std::max(max_chunk_slots, s);
+  }
+  if (shape->flags & ECHOKV_FLAG_ABSORBED) {
+    if (!absorbed_supported(dm, shape->flags)) return ECHOKV_ERR_UNSUPPORTED;
+    const size_t need = absorbed_need(dm, anchor);
+    if (need == (size_t)-1) return ECHOKV_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < need) return ECHOKV_ERR_WORKSPACE;
+    if ((uintptr_t)workspace % 256) return ECHOKV_ERR_WORKSPACE;
+    return absorbed_impl(dm, anchor, target, w_k, w_v, q, out, lse_out, (char*)workspace,
+                         (hipStream_t)hip_stream);
   }
   if ((shape->flags & ECHOKV_FLAG_W_PACKED) &&
       (dm.r != 0 || (shape->flags & ECHOKV_FLAG_UNFUSED) || !dm.bf16 || !fused_decode_supported<bf16_t>(dm.d, dm.G)))

@@ -19,7 +19,8 @@ TOL = {"bf16": (2e-2, 5e-3), "f32": (1e-5, 1e-5)}
 PACKED = 1 << 20       # test-only marker: weights re-laid out once by echokv_pack_weights (direct-to-LDS kernel)
 MODES = [pytest.param(0, id="fused"), pytest.param(ek.FLAG_UNFUSED, id="unfused"),
          pytest.param(PACKED, id="packed"),
-         pytest.param(PACKED | ek.FLAG_STAGED, id="packed_staged")]
+         pytest.param(PACKED | ek.FLAG_STAGED, id="packed_staged"),
+         pytest.param(ek.FLAG_ABSORBED, id="absorbed")]
 
 
 def check(got, want, dtype, what=""):
@@ -43,6 +44,8 @@ def make_dw(inp, flags, **kw):
         dw.pack_weights()
         dw.shape.flags |= flags & ek.FLAG_STAGED
         return dw
+    if flags & ek.FLAG_ABSORBED and inp.w.dtype != "bf16":
+        pytest.skip("weight-absorbed decode: bf16 caches only")
     return DeviceWorkload(inp, flags=flags, **kw)
 
 
