@@ -35,7 +35,6 @@ using fused::rsrc_t; using fused::make_rsrc; using fused::u32x4_t;
 
 constexpr int kHB = 32;           // query heads per MFMA block
 constexpr int kTokTile = kSlotTokens;   // tokens per workgroup of the score pass
-constexpr int kScoreWaves = 8;
 constexpr int kColTile = 256;     // predictor-input columns per workgroup of the value pass
 constexpr int kPvWaves = 4;
 
@@ -125,31 +124,34 @@ __global__ __launch_bounds__(256) void absorb_q_kernel(Args a, int nseq) {
 }
 
 // ---------------------------------------------------------------------------
-// Score pass.  One workgroup (8 waves) = one 128-token slot of one sequence x
-// one block of 32 query heads.  MFMA form: C[head, token] += U[head, k] X[token, k],
-// so a lane owns a token column and the stores to S^T are 128-byte rows.
+// Score pass.  One workgroup (4 waves) = one 128-token slot of one sequence x
+// one block of 32 query heads; wave w owns tokens 32 w .. 32 w + 31 for the
+// whole of d_in, so no partial sums ever meet.  MFMA form:
+// C[head, token] += U[head, k] X[token, k]: a lane owns a token column and the
+// stores to S^T are 128-byte rows.
 //
 // The MFMA operand layout wants, per lane, 16 bytes of a different token row:
 // loaded straight from global memory that is 32 rows x 32 bytes per
-// instruction, a pattern that reaches about half of the streaming bandwidth.
-// So the X tile goes HBM -> LDS in stages of 256 input dims with
-// `buffer_load ... lds`, one instruction moving 2 rows x 512 contiguous bytes,
-// and the fragments are read back from LDS (chunk c of row r sits at slot
-// c ^ (r % 32): conflict-free 16-byte reads down a column).  Two stages of
-// 64 KB; inside a stage wave w multiplies input dims [32 w, 32 w + 32) for all
-// 128 tokens, with its U fragments loaded from global memory (L2-resident).
-// The waves' partial sums meet once in LDS at the end.
+// instruction, a pattern that reaches barely half of the streaming bandwidth.
+// So X and U go HBM / L2 -> LDS in stages of 128 input dims with
+// `buffer_load ... lds` (one instruction = 4 rows x 256 contiguous bytes) and
+// the fragments are read back from LDS (chunk c of row r sits at slot
+// c ^ (r % 16): conflict-free 16-byte reads down a column).  Two stages of
+// 40 KB, so two workgroups share a compute unit and cover each other's barriers.
 // ---------------------------------------------------------------------------
 #ifndef ECHOKV_LDS
 #define ECHOKV_LDS __attribute__((address_space(3)))
 #endif
-constexpr int kStageK = 256;                              // input dims per LDS stage
-constexpr int kStageBytes = kTokTile * kStageK * 2;       // 64 KB
+constexpr int kStageK = 128;                              // input dims per LDS stage
+constexpr int kRowBytes = kStageK * 2;                    // 256
+constexpr int kXBytes = kTokTile * kRowBytes;             // 32 KB
+constexpr int kUBytes = kHB * kRowBytes;                  // 8 KB
+constexpr int kStageBytes = kXBytes + kUBytes;            // 40 KB
 
 struct ScoreIo {
   const bf16_t* pa; const bf16_t* pr;
   rsrc_t ru;
-  uint32_t D2, m2, uoff;
+  uint32_t D2, m2, u2;
   int D, m, nsa, ns, last;
 };
 
@@ -164,30 +166,36 @@ __device__ __forceinline__ StageDesc stage_desc(const ScoreIo& io, int t) {
   return d;
 }
 
-// this wave's 8 direct-to-LDS loads of stage t (rows 16 w .. 16 w + 15) and its 2 U fragments
-__device__ __forceinline__ void score_issue(char* buf, u32x4_t (&u)[2], const ScoreIo& io, int t,
-                                            int wave, int lane) {
+// this wave's 10 direct-to-LDS loads of stage t: X rows 32 w .. 32 w + 31, U rows 8 w .. 8 w + 7
+__device__ __forceinline__ void score_issue(char* buf, const ScoreIo& io, int t, int wave, int lane) {
   const StageDesc d = stage_desc(io, t);
   const rsrc_t rx = make_rsrc(d.anchor ? io.pa : io.pr);
   const uint32_t ld2 = d.anchor ? io.D2 : io.m2;
   const int nchunk = d.kw / 8;
+  const int sub = lane >> 4, slot = lane & 15;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const int row = wave * 16 + 2 * i + (lane >> 5);
-    const int chunk = min((lane & 31) ^ (row & 31), nchunk - 1);     // a partial stage repeats its last chunk
+    const int row = wave * 32 + 4 * i + sub;
+    const int chunk = min(slot ^ (row & 15), nchunk - 1);            // a partial stage repeats its last chunk
     const uint32_t voff = __umul24((uint32_t)min(row, io.last), ld2) + (uint32_t)chunk * 16;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (ECHOKV_LDS void*)(buf + (wave * 16 + 2 * i) * (kStageK * 2)),
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rx, (ECHOKV_LDS void*)(buf + (wave * 32 + 4 * i) * kRowBytes),
                                              16, voff, d.k0 * 2, 0, 0);
   }
-  const int kw0 = 32 * wave < d.kw ? 32 * wave : 0;
 #pragma unroll
-  for (int s = 0; s < 2; ++s)
-    u[s] = __builtin_amdgcn_raw_buffer_load_b128(io.ru, io.uoff, (d.kg0 + kw0 + 16 * s) * 2, 0);
+  for (int i = 0; i < 2; ++i) {
+    const int row = wave * 8 + 4 * i + sub;
+    const int chunk = min(slot ^ (row & 15), nchunk - 1);
+    const uint32_t voff = __umul24((uint32_t)row, io.u2) + (uint32_t)chunk * 16;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(io.ru, (ECHOKV_LDS void*)(buf + kXBytes + (wave * 8 + 4 * i) * kRowBytes),
+                                             16, voff, d.kg0 * 2, 0, 0);
+  }
 }
 
+template <int NST>
 __device__ __forceinline__ void score_wait_landed() {
+  constexpr int N = 10 * (NST - 1);            // loads of the younger stages, which may stay in flight
   asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_waitcnt(0x0F70 | 10);     // vmcnt(10): only the younger stage (8 + 2 loads) may be in flight
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));     // vmcnt(N)
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 }
@@ -198,36 +206,36 @@ __device__ __forceinline__ void score_wait_read() {
   asm volatile("" ::: "memory");
 }
 
-__device__ __forceinline__ void score_stage(floatx16_t (&acc)[4], char* buf, u32x4_t (&u)[2],
-                                            const ScoreIo& io, int t, int wave, int lane, bool head_ok) {
+template <int NST>
+__device__ __forceinline__ void score_stage(floatx16_t& acc, char* buf, const ScoreIo& io, int t,
+                                            int wave, int lane, bool head_ok) {
   const int lr = lane & 31, lh = lane >> 5;
   const StageDesc d = stage_desc(io, t);
-  const bool active = head_ok && t < io.ns && 32 * wave < d.kw;
-  score_wait_landed();                          // stage t is in LDS for every wave
-  u32x4_t xf[4][2];
+  const int kw = (head_ok && t < io.ns) ? d.kw : 0;       // input dims of this stage that count
+  score_wait_landed<NST>();                     // stage t is in LDS for every wave
+  u32x4_t xf[8], uf[8];
+  const char* xrow = buf + (wave * 32 + lr) * kRowBytes;
+  const char* urow = buf + kXBytes + lr * kRowBytes;
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-    for (int s = 0; s < 2; ++s)
-      xf[tb][s] = *reinterpret_cast<const u32x4_t*>(buf + (tb * 32 + lr) * (kStageK * 2) +
-                                                    (((4 * wave + 2 * s + lh) ^ lr) << 4));
+  for (int s = 0; s < 8; ++s) {
+    const int off = ((2 * s + lh) ^ (lr & 15)) << 4;
+    xf[s] = *reinterpret_cast<const u32x4_t*>(xrow + off);
+    uf[s] = *reinterpret_cast<const u32x4_t*>(urow + off);
+  }
   score_wait_read();                            // every wave holds its fragments: the buffer is free
-  u32x4_t uc[2] = {u[0], u[1]};
-  score_issue(buf, u, io, t + 2, wave, lane);
+  score_issue(buf, io, t + NST, wave, lane);
 #pragma unroll
-  for (int s = 0; s < 2; ++s) {
-    u32x4_t uu = uc[s];
-    if (!active) uu = u32x4_t{0u, 0u, 0u, 0u};
-    const bf16x8_t ua = __builtin_bit_cast(bf16x8_t, uu);
-#pragma unroll
-    for (int tb = 0; tb < 4; ++tb)
-      acc[tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua, __builtin_bit_cast(bf16x8_t, xf[tb][s]),
-                                                        acc[tb], 0, 0, 0);
+  for (int s = 0; s < 8; ++s) {
+    u32x4_t uu = uf[s];
+    if (16 * s >= kw) uu = u32x4_t{0u, 0u, 0u, 0u};
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, uu),
+                                                  __builtin_bit_cast(bf16x8_t, xf[s]), acc, 0, 0, 0);
   }
 }
 
-__global__ __launch_bounds__(kScoreWaves * 64) void scores_kernel(Args a, SeqMeta meta) {
-  __shared__ __attribute__((aligned(1024))) char lds[2 * kStageBytes];     // 128 KB
+template <int NST>      // LDS stages: 2 (80 KB, two workgroups per compute unit) or 4 (160 KB, for small grids)
+__global__ __launch_bounds__(256, NST == 2 ? 2 : 1) void scores_kernel(Args a, SeqMeta meta) {
+  __shared__ __attribute__((aligned(1024))) char lds[NST * kStageBytes];
   const int slot = blockIdx.x, hb = blockIdx.y;
   const int b = find_seq(meta.sbase, meta.n, slot);
   const int L = meta.len[b];
@@ -239,48 +247,31 @@ __global__ __launch_bounds__(kScoreWaves * 64) void scores_kernel(Args a, SeqMet
   ScoreIo io;
   io.pa = a.xa[0] + row0 * a.D; io.pr = a.xr[0] + row0 * a.m;
   io.ru = make_rsrc(a.u + ((int64_t)b * a.H_pad + hb * kHB) * a.d_in);
-  io.D2 = (uint32_t)a.D * 2; io.m2 = (uint32_t)a.m * 2;
-  io.uoff = (uint32_t)lr * (uint32_t)a.d_in * 2 + (uint32_t)lh * 16;
+  io.D2 = (uint32_t)a.D * 2; io.m2 = (uint32_t)a.m * 2; io.u2 = (uint32_t)a.d_in * 2;
   io.D = a.D; io.m = a.m;
   io.nsa = (a.D + kStageK - 1) / kStageK; io.ns = io.nsa + (a.m + kStageK - 1) / kStageK;
   io.last = min(kTokTile, L - j0) - 1;
-  const bool head_ok = hb * kHB + lr < a.H_q;
+  const bool head_ok = hb * kHB + lr < a.H_q;    // rows of U past the last head hold nothing: count as zero
 
-  floatx16_t acc[4];
+  floatx16_t acc;
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[tb][r] = 0.f;
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
 
-  // stage t lives in buffer t % 2; stages past the last one repeat it with a zeroed U
-  // fragment, so every wave runs the same barriers
-  u32x4_t u0[2], u1[2];
-  score_issue(lds, u0, io, 0, wave, lane);
-  score_issue(lds + kStageBytes, u1, io, 1, wave, lane);
-  for (int t = 0; t < io.ns; t += 2) {
-    score_stage(acc, lds, u0, io, t, wave, lane, head_ok);
-    score_stage(acc, lds + kStageBytes, u1, io, t + 1, wave, lane, head_ok);
+  // stage t lives in buffer t % NST; stages past the last one repeat it with U counted as
+  // zero, so every wave runs the same barriers
+#pragma unroll
+  for (int i = 0; i < NST; ++i) score_issue(lds + i * kStageBytes, io, i, wave, lane);
+  for (int t = 0; t < io.ns; t += NST) {
+#pragma unroll
+    for (int i = 0; i < NST; ++i) score_stage<NST>(acc, lds + i * kStageBytes, io, t + i, wave, lane, head_ok);
   }
   asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): the look-ahead loads have landed
-  __syncthreads();
-
-  float* red = reinterpret_cast<float*>(lds);    // [wave][token block][acc row][lane]
+  __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): the look-ahead loads land before the block's LDS is released
+  float* srow = a.s + (int64_t)slot * kTokTile + wave * 32 + lr;
 #pragma unroll
-  for (int tb = 0; tb < 4; ++tb)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) red[((wave * 4 + tb) * 16 + r) * 64 + lane] = acc[tb][r];
-  __syncthreads();
-  // wave w adds up token block w / 2, accumulator rows 8 (w % 2) .. + 8
-  const int tb = wave >> 1, r0 = (wave & 1) * 8;
-  float* srow = a.s + (int64_t)slot * kTokTile + tb * 32 + lr;
-#pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    float v = 0.f;
-#pragma unroll
-    for (int w = 0; w < kScoreWaves; ++w) v += red[((w * 4 + tb) * 16 + r0 + r) * 64 + lane];
-    const int head = 8 * ((r0 + r) >> 2) + 4 * lh + (r & 3);      // accumulator row -> head
-    srow[(int64_t)(hb * kHB + head) * a.s_ld] = v;
+  for (int r = 0; r < 16; ++r) {
+    const int head = 8 * (r >> 2) + 4 * lh + (r & 3);      // accumulator row -> head
+    srow[(int64_t)(hb * kHB + head) * a.s_ld] = acc[r];
   }
 }
 
@@ -351,16 +342,21 @@ __device__ __forceinline__ void pv_mma(floatx16_t (&acc)[8], const PvStage& st, 
                                        int step, float M) {
   // probabilities of this lane's head for its 8 tokens (0 beyond the split's end)
   const int t0 = step * 16 + io.lh8;
-  u32x4_t pw;
+  // each probability goes in as a bf16 (high, low) pair: the value pass is far from
+  // MFMA-bound, and this keeps the rounding of p out of the result
+  u32x4_t pw, pl;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const float s0 = __uint_as_float(st.s[i >> 1][(2 * i) & 3]);
     const float s1 = __uint_as_float(st.s[i >> 1][(2 * i + 1) & 3]);
     const float p0 = (t0 + 2 * i < io.nrows) ? exp2f(s0 - M) : 0.f;
     const float p1 = (t0 + 2 * i + 1 < io.nrows) ? exp2f(s1 - M) : 0.f;
-    pw[i] = (uint32_t)f32_to_bf16(p0) | ((uint32_t)f32_to_bf16(p1) << 16);
+    const bf16_t h0 = f32_to_bf16(p0), h1 = f32_to_bf16(p1);
+    pw[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
+    pl[i] = (uint32_t)f32_to_bf16(p0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(p1 - bf16_to_f32(h1)) << 16);
   }
   const bf16x8_t pa = __builtin_bit_cast(bf16x8_t, pw);
+  const bf16x8_t pb = __builtin_bit_cast(bf16x8_t, pl);
   // 8 x 8 transpose: word p of output i holds tokens 2p, 2p + 1 of column i
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -370,10 +366,11 @@ __device__ __forceinline__ void pv_mma(floatx16_t (&acc)[8], const PvStage& st, 
       xt[p] = __builtin_amdgcn_perm(st.x[2 * p + 1][i >> 1], st.x[2 * p][i >> 1],
                                     (i & 1) ? 0x07060302u : 0x05040100u);
     acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, __builtin_bit_cast(bf16x8_t, xt), acc[i], 0, 0, 0);
+    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pb, __builtin_bit_cast(bf16x8_t, xt), acc[i], 0, 0, 0);
   }
 }
 
-__global__ __launch_bounds__(kPvWaves * 64) void pv_kernel(Args a, SeqMeta meta) {
+__global__ __launch_bounds__(kPvWaves * 64, 2) void pv_kernel(Args a, SeqMeta meta) {
   __shared__ float red[2][128][64];       // 64 KB: two waves' accumulators
   const int ct = blockIdx.x % a.n_col_tiles, sp = blockIdx.x / a.n_col_tiles, hb = blockIdx.y;
   const int b = find_seq(meta.tbase, meta.n, sp);
@@ -405,21 +402,18 @@ __global__ __launch_bounds__(kPvWaves * 64) void pv_kernel(Args a, SeqMeta meta)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
-  // three register stages, branch-free body: rounds past the wave's last step
+  // two register stages, branch-free body: rounds past the wave's last step
   // re-read the split's last step with all probabilities masked to zero
-  PvStage s0, s1, s2;
+  PvStage s0, s1;
   const int n = io.nsteps;
   const int nw = (n - wave + kPvWaves - 1) / kPvWaves;
   pv_fetch(s0, io, wave);
-  pv_fetch(s1, io, wave + kPvWaves);
-  for (int it = 0; it < nw; it += 3) {
+  for (int it = 0; it < nw; it += 2) {
     const int st = wave + it * kPvWaves;
-    pv_fetch(s2, io, st + 2 * kPvWaves);
+    pv_fetch(s1, io, st + kPvWaves);
     pv_mma(acc, s0, io, st, M);
-    pv_fetch(s0, io, st + 3 * kPvWaves);
+    pv_fetch(s0, io, st + 2 * kPvWaves);
     pv_mma(acc, s1, io, st + kPvWaves, M);
-    pv_fetch(s1, io, st + 4 * kPvWaves);
-    pv_mma(acc, s2, io, st + 2 * kPvWaves, M);
   }
 
   // tree reduction over the 4 waves: {2, 3} -> {0, 1}, then 1 -> 0
@@ -471,26 +465,45 @@ __global__ __launch_bounds__(256) void y_sum_kernel(Args a, SeqMeta meta) {
   const int k = min(blockIdx.x * 256 + cq * 4, a.d_in - 4);    // tail threads repeat the last quad
   const int s0 = meta.tbase[b], ns = meta.tbase[b + 1] - s0;
   __shared__ float4 red[4][64];
+  __shared__ float s_red[4];
+  __shared__ float s_w[256];
   const float* mlp = a.ml + ((int64_t)s0 * a.H_pad + h) * 2;
   const int64_t mls = (int64_t)a.H_pad * 2;
   float M = -INFINITY;
-  for (int i = 0; i < ns; ++i) M = fmaxf(M, mlp[i * mls]);
+  for (int i = tid; i < ns; i += 256) M = fmaxf(M, mlp[i * mls]);
+  M = wave_max(M, 64);
+  if (cq == 0) s_red[sg] = M;
+  __syncthreads();
+  M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float l = 0.f;
+  const float* yp = a.ypart + ((int64_t)s0 * a.H_pad + h) * a.d_in + k;
+  const int64_t yps = (int64_t)a.H_pad * a.d_in;
+  for (int c0 = 0; c0 < ns; c0 += 256) {
+    float wgt = 0.f;
+    if (c0 + tid < ns) {
+      wgt = exp2f(mlp[(c0 + tid) * mls] - M);
+      l += wgt * mlp[(c0 + tid) * mls + 1];
+    }
+    __syncthreads();            // the previous chunk's weights are no longer read
+    s_w[tid] = wgt;
+    __syncthreads();
+    const int cn = min(256, ns - c0);
 #pragma unroll 4
-  for (int i = sg; i < ns; i += 4) {
-    const float wgt = exp2f(mlp[i * mls] - M);
-    l += wgt * mlp[i * mls + 1];
-    const float4 v = *reinterpret_cast<const float4*>(a.ypart + ((int64_t)(s0 + i) * a.H_pad + h) * a.d_in + k);
-    acc.x = fmaf(wgt, v.x, acc.x); acc.y = fmaf(wgt, v.y, acc.y);
-    acc.z = fmaf(wgt, v.z, acc.z); acc.w = fmaf(wgt, v.w, acc.w);
+    for (int j = sg; j < cn; j += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(yp + (c0 + j) * yps);
+      const float wj = s_w[j];
+      acc.x = fmaf(wj, v.x, acc.x); acc.y = fmaf(wj, v.y, acc.y);
+      acc.z = fmaf(wj, v.z, acc.z); acc.w = fmaf(wj, v.w, acc.w);
+    }
   }
+  l = wave_sum(l, 64);
   red[sg][cq] = acc;
-  __shared__ float lred[4];
-  if (cq == 0) lred[sg] = l;
+  __syncthreads();              // also orders the reads of s_red above before its reuse
+  if (cq == 0) s_red[sg] = l;
   __syncthreads();
   if (sg != 0) return;
-  l = (lred[0] + lred[1]) + (lred[2] + lred[3]);
+  l = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
   const float inv = 1.f / l;
   float4 r;
   r.x = ((red[0][cq].x + red[1][cq].x) + (red[2][cq].x + red[3][cq].x)) * inv;

@@ -522,7 +522,9 @@ int absorbed_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_lay
     if (dm.d == 128) hipLaunchKernelGGL((absorbed::absorb_q_kernel<128>), qg, dim3(256), 0, st, a, n);
     else hipLaunchKernelGGL((absorbed::absorb_q_kernel<64>), qg, dim3(256), 0, st, a, n);
     LAUNCH_CHECK();
-    hipLaunchKernelGGL(absorbed::scores_kernel, dim3(slots, nhb), dim3(absorbed::kScoreWaves * 64), 0, st, a, mt);
+    // few workgroups: one per compute unit with a deeper pipeline; many: two per compute unit
+    if ((int64_t)slots * nhb <= 384) hipLaunchKernelGGL(absorbed::scores_kernel<4>, dim3(slots, nhb), dim3(256), 0, st, a, mt);
+    else hipLaunchKernelGGL(absorbed::scores_kernel<2>, dim3(slots, nhb), dim3(256), 0, st, a, mt);
     LAUNCH_CHECK();
     hipLaunchKernelGGL(absorbed::softmax_stats_kernel, dim3(dm.H_q, splits), dim3(256), 0, st, a, mt);
     LAUNCH_CHECK();
