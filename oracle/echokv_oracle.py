@@ -21,7 +21,14 @@ Readings taken where the paper is silent (each also listed in the design notes):
     y = x W with W of shape [d_in, d_out]; keys and values have separate W;
   * flattening is head-major: flattened index g*d + i is feature i of KV head g;
   * query head h reads KV head h // G, G = H_q / H_kv;
-  * keys are position-free on this path (no rotary embedding is applied);
+  * keys are position-free on the base path (no rotary embedding is applied);
+    echokv_decode_paper adds what the paper's own inference does on top: the
+    cache holds keys from before the rotary embedding (Sec. "Network
+    Architecture"), so the embedding is applied to the rebuilt keys, by token
+    position, just before Eq. 7; and the first 4 / latest 128 tokens of the
+    target layer are kept uncompressed (Sec. "Experimental Setup").  The
+    pairing of rotated features (i with i + d/2) and the ring placement of the
+    latest tokens are this build's readings: the paper fixes neither;
   * a prefill query at chunk offset i attends cached tokens 0 .. q_pos0 + i,
     all of them taken from the compressed cache (reconstructed where dropped).
 
@@ -266,3 +273,150 @@ def brute_force_decode(q, K_a, V_a, K_r, V_r, W_K, W_V, n_kv_heads: int,
     o, lse = brute_force_prefill(np.asarray(q, F64)[None], K_a, V_a, K_r, V_r,
                                  W_K, W_V, n_kv_heads, L - 1, scale)
     return o[0], lse[0]
+
+
+# --------------------------------------------------------------------------
+# paper-faithful decode: rotary embedding after reconstruction, and a window
+# of uncompressed tokens (Sec. "Network Architecture": predictor inputs are
+# the keys BEFORE the rotary embedding; Sec. "Experimental Setup": 4 sink
+# tokens and a local window of 128 tokens stay at full precision)
+# --------------------------------------------------------------------------
+def rope_rotate(X: np.ndarray, positions: Sequence[int], cos: np.ndarray, sin: np.ndarray,
+                n_heads: int) -> np.ndarray:
+    """Rotary embedding of flattened head-major rows X [L, n_heads * d].
+
+    Row j is rotated by the angles of table row positions[j]; cos, sin are
+    [P, d/2] (the caller's tables: angle of feature pair i at position p).
+    Feature i of a head is paired with feature i + d/2:
+        x'_i       = x_i cos_i - x_{i+d/2} sin_i
+        x'_{i+d/2} = x_{i+d/2} cos_i + x_i sin_i
+    """
+    X = np.asarray(X, F64)
+    L = X.shape[0]
+    d = X.shape[1] // n_heads
+    h = d // 2
+    pos = np.asarray(positions, np.int64)
+    c = np.asarray(cos, F64)[pos][:, None, :]          # [L, 1, d/2]
+    s = np.asarray(sin, F64)[pos][:, None, :]
+    Xh = X.reshape(L, n_heads, d)
+    a, b = Xh[:, :, :h], Xh[:, :, h:]
+    out = np.empty_like(Xh)
+    out[:, :, :h] = a * c - b * s
+    out[:, :, h:] = b * c + a * s
+    return out.reshape(L, n_heads * d)
+
+
+def window_row(p: int, n_sink: int, n_recent: int) -> int:
+    """Row of the uncompressed window that holds position p: the first n_sink
+    positions have a row each, later positions share a ring of n_recent rows."""
+    return p if p < n_sink else n_sink + (p - n_sink) % n_recent
+
+
+def in_window(p: int, L: int, n_sink: int, n_recent: int) -> bool:
+    """Is position p of a length-L sequence kept uncompressed?"""
+    return p < n_sink or p >= L - n_recent
+
+
+def window_append(win: np.ndarray, L_before: int, rows: np.ndarray, n_sink: int, n_recent: int):
+    """Write full-width rows of new tokens (positions L_before, L_before+1, ...)
+    into the window [n_sink + n_recent, D], in place; the ring overwrites the
+    token that leaves the local window."""
+    for i in range(rows.shape[0]):
+        p = L_before + i
+        if p < n_sink or n_recent > 0:
+            win[window_row(p, n_sink, n_recent)] = rows[i]
+
+
+def rebuilt_with_window(C_a, C_r, W, win, n_sink: int, n_recent: int) -> np.ndarray:
+    """C_tilde [L, D]: reconstruction (Eq. 3, 6) everywhere except the window
+    positions, which take their stored uncompressed rows."""
+    C_t = reconstruct(C_a, C_r, W)
+    L = C_t.shape[0]
+    if win is not None:
+        win = np.asarray(win, F64)
+        for p in range(L):
+            if in_window(p, L, n_sink, n_recent):
+                C_t[p] = win[window_row(p, n_sink, n_recent)]
+    return C_t
+
+
+def echokv_decode_paper(q, K_a, V_a, K_r, V_r, W_K, W_V, n_kv_heads: int,
+                        scale: Optional[float] = None,
+                        rope: Optional[Tuple[np.ndarray, np.ndarray]] = None,
+                        window: Optional[Tuple[np.ndarray, np.ndarray, int, int]] = None):
+    """Decode over one sequence as the paper's inference runs it.
+
+    rope = (cos, sin) tables [P, d/2]: cached keys are pre-rotation; token j's
+    rebuilt key is rotated to position j before the dot product.  q must come
+    in already rotated to its own position.  window = (win_k, win_v, n_sink,
+    n_recent): full-width pre-rotation rows of the target layer for the first
+    n_sink and the latest n_recent positions, laid out by window_row().
+    Returns (out [H_q, d], lse [H_q])."""
+    wk = wv = None
+    n_sink = n_recent = 0
+    if window is not None:
+        wk, wv, n_sink, n_recent = window
+    K_t = rebuilt_with_window(K_a, K_r, W_K, wk, n_sink, n_recent)
+    V_t = rebuilt_with_window(V_a, V_r, W_V, wv, n_sink, n_recent)
+    if rope is not None:
+        K_t = rope_rotate(K_t, range(K_t.shape[0]), rope[0], rope[1], n_kv_heads)
+    o, lse, _ = attention_rows(np.asarray(q, F64)[None], K_t, V_t, n_kv_heads, scale)
+    return o[0], lse[0]
+
+
+def brute_force_decode_paper(q, K_a, V_a, K_r, V_r, W_K, W_V, n_kv_heads: int,
+                             scale=None, rope=None, window=None):
+    """echokv_decode_paper again as scalar loops (tiny shapes)."""
+    q = np.asarray(q, F64)
+    H_q, d = q.shape
+    L, D = K_a.shape
+    m = K_r.shape[1]
+    G = H_q // n_kv_heads
+    sc = _scale(d, scale)
+    half = d // 2
+    n_sink = n_recent = 0
+    if window is not None:
+        win_k, win_v, n_sink, n_recent = window
+
+    def stored(C_a, C_r, W, win, j, col):
+        if window is not None and (j < n_sink or j >= L - n_recent):
+            r = j if j < n_sink else n_sink + (j - n_sink) % n_recent
+            return float(win[r][col])
+        if col < m:
+            return float(C_r[j][col])
+        acc = 0.0
+        for k in range(D + m):
+            x = float(C_a[j][k]) if k < D else float(C_r[j][k - D])
+            acc += x * float(W[k][col - m])
+        return acc
+
+    def key(j, g, i):
+        x = stored(K_a, K_r, W_K, win_k if window is not None else None, j, g * d + i)
+        if rope is None:
+            return x
+        if i < half:
+            y = stored(K_a, K_r, W_K, win_k if window is not None else None, j, g * d + i + half)
+            return x * float(rope[0][j][i]) - y * float(rope[1][j][i])
+        y = stored(K_a, K_r, W_K, win_k if window is not None else None, j, g * d + i - half)
+        return x * float(rope[0][j][i - half]) + y * float(rope[1][j][i - half])
+
+    out = [[0.0] * d for _ in range(H_q)]
+    lse = [0.0] * H_q
+    for h in range(H_q):
+        g = h // G
+        s = []
+        for j in range(L):
+            dot = 0.0
+            for i in range(d):
+                dot += float(q[h][i]) * key(j, g, i)
+            s.append(dot * sc)
+        mx = max(s)
+        e = [math.exp(x - mx) for x in s]
+        z = sum(e)
+        for i in range(d):
+            acc = 0.0
+            for j in range(L):
+                acc += (e[j] / z) * stored(V_a, V_r, W_V, win_v if window is not None else None, j, g * d + i)
+            out[h][i] = acc
+        lse[h] = mx + math.log(z)
+    return np.array(out, F64), np.array(lse, F64)

@@ -253,3 +253,36 @@ def selector_weights(w: Workload, source_cols: Sequence[int]) -> torch.Tensor:
     for c, s in enumerate(source_cols):
         W[int(s), c] = 1.0
     return W
+
+
+def rope_tables(head_dim: int, n_pos: int, base: float = 10000.0):
+    """Angle tables a caller of the rotary-embedding decode passes in: cos, sin
+    [n_pos, head_dim / 2] fp32 with angle(p, i) = p * base^(-2 i / head_dim)
+    (worked out in float64, stored as float32)."""
+    i = torch.arange(head_dim // 2, dtype=torch.float64)
+    ang = torch.arange(n_pos, dtype=torch.float64)[:, None] * base ** (-2.0 * i / head_dim)[None, :]
+    return torch.cos(ang).to(torch.float32), torch.sin(ang).to(torch.float32)
+
+
+def window_rows(inp: Inputs, n_sink: int, n_recent: int):
+    """Uncompressed rows of the target layer for the first n_sink and the latest
+    n_recent positions of every decode sequence: win_k, win_v
+    [n_decode, n_sink + n_recent, D].  The first m dims repeat what the
+    compressed cache stores for that token; the dropped dims are fresh seeded
+    draws (so they differ from anything the predictor would rebuild).  Position
+    p sits in row p (p < n_sink) or n_sink + (p - n_sink) % n_recent."""
+    w = inp.w
+    W_ = n_sink + n_recent
+    out = []
+    for tag, src in (("win_k", inp.K_r), ("win_v", inp.V_r)):
+        win = torch.zeros(inp.n_decode, W_, w.D, dtype=w.torch_dtype)
+        for b in range(inp.n_decode):
+            L = inp.seq_len[b]
+            rows = torch.randn(W_, w.D, generator=_gen(w.seed, f"{tag}_{b}"), dtype=torch.float32)
+            for p in list(range(min(n_sink, L))) + list(range(max(n_sink, L - n_recent), L)):
+                r = p if p < n_sink else n_sink + (p - n_sink) % n_recent
+                win[b, r] = rows[r].to(w.torch_dtype)
+                if w.n_retained:
+                    win[b, r, :w.n_retained] = src[inp.seq_start[b] + p]
+        out.append(win)
+    return out[0], out[1]

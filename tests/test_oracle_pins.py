@@ -448,3 +448,179 @@ def test_mutant_wrong_head_map_fails_gqa_pin():
         wrong[h] = p @ Vh[:, g]
     np.testing.assert_allclose(o, ref, rtol=1e-12, atol=1e-13)
     assert np.abs(wrong - ref).max() > 1e-3
+
+
+# ---- P13: rotary embedding of the rebuilt keys ----------------------------------
+def angle_tables(d, P, base=10000.0):
+    i = np.arange(d // 2)
+    ang = np.arange(P)[:, None] * base ** (-2.0 * i / d)[None, :]
+    return np.cos(ang), np.sin(ang)
+
+
+def test_rope_position_zero_is_identity_and_norms_are_kept():
+    cos, sin = angle_tables(8, 50)
+    X = rnd((50, 3 * 8), 1)
+    Y = orc.rope_rotate(X, range(50), cos, sin, 3)
+    np.testing.assert_allclose(Y[0], X[0], rtol=0, atol=1e-15)
+    # a rotation of each (i, i + d/2) plane: per-head norms do not change
+    nx = np.linalg.norm(X.reshape(50, 3, 8), axis=2)
+    ny = np.linalg.norm(Y.reshape(50, 3, 8), axis=2)
+    np.testing.assert_allclose(ny, nx, rtol=1e-13)
+    assert np.abs(Y[7] - X[7]).max() > 0.1
+
+
+def test_rope_plane_rotation_closed_form_and_pairing():
+    # d = 2: one plane with angle p (pair frequency base^0 = 1): (1, 0) -> (cos p, sin p)
+    cos, sin = angle_tables(2, 10)
+    Y = orc.rope_rotate(np.tile([[1.0, 0.0]], (10, 1)), range(10), cos, sin, 1)
+    for p in range(10):
+        np.testing.assert_allclose(Y[p], [math.cos(p), math.sin(p)], atol=1e-15)
+    # d = 4: feature 0 is paired with feature 2 (= 0 + d/2), never with feature 1
+    cos, sin = angle_tables(4, 4)
+    Y = orc.rope_rotate(np.array([[1.0, 0.0, 0.0, 0.0]]), [3], cos, sin, 1)
+    np.testing.assert_allclose(Y[0], [math.cos(3.0), 0.0, math.sin(3.0), 0.0], atol=1e-15)
+    # feature 1 turns with the slower frequency base^(-2/4) into feature 3
+    Y = orc.rope_rotate(np.array([[0.0, 1.0, 0.0, 0.0]]), [3], cos, sin, 1)
+    a = 3.0 * 10000.0 ** -0.5
+    np.testing.assert_allclose(Y[0], [0.0, math.cos(a), 0.0, math.sin(a)], atol=1e-15)
+
+
+def test_rope_scores_depend_on_relative_position_only():
+    d, P = 16, 64
+    cos, sin = angle_tables(d, P)
+    q, k = rnd((1, d), 2), rnd((1, d), 3)
+    def score(pq, pk):
+        return float(orc.rope_rotate(q, [pq], cos, sin, 1)[0] @ orc.rope_rotate(k, [pk], cos, sin, 1)[0])
+    base = score(20, 5)
+    for shift in (1, 7, 30):
+        assert abs(score(20 + shift, 5 + shift) - base) < 1e-12
+    assert abs(score(21, 5) - base) > 1e-3
+
+
+def test_rope_tables_of_the_input_generator_follow_the_published_angles():
+    from paper_2603_22910_amd import synth
+    cos, sin = synth.rope_tables(128, 300)
+    assert cos.shape == (300, 64) and cos.dtype == torch.float32
+    for p, i in ((0, 0), (1, 0), (299, 0), (17, 63), (250, 31)):
+        ang = p * 10000.0 ** (-2.0 * i / 128)
+        assert abs(float(cos[p, i]) - math.cos(ang)) < 1e-7
+        assert abs(float(sin[p, i]) - math.sin(ang)) < 1e-7
+
+
+def test_decode_paper_without_extras_is_plain_decode_and_rope_is_applied_after_rebuild():
+    c, Q = make_case(4, 2, 8, 8, 37, seed=5)
+    o0, l0 = orc.echokv_decode(Q[0], **c, n_kv_heads=2)
+    o1, l1 = orc.echokv_decode_paper(Q[0], **c, n_kv_heads=2)
+    np.testing.assert_array_equal(o0, o1); np.testing.assert_array_equal(l0, l1)
+    # with rotation: equal to library attention over keys rotated AFTER reconstruction
+    cos, sin = angle_tables(8, 64)
+    o2, _ = orc.echokv_decode_paper(Q[0], **c, n_kv_heads=2, rope=(cos, sin))
+    K_t = orc.reconstruct(c["K_a"], c["K_r"], c["W_K"]); V_t = orc.reconstruct(c["V_a"], c["V_r"], c["W_V"])
+    K_rot = K_t.reshape(37, 2, 8).copy()
+    for j in range(37):
+        for i in range(4):
+            a, b = K_t.reshape(37, 2, 8)[j, :, i], K_t.reshape(37, 2, 8)[j, :, i + 4]
+            K_rot[j, :, i] = a * cos[j, i] - b * sin[j, i]
+            K_rot[j, :, i + 4] = b * cos[j, i] + a * sin[j, i]
+    np.testing.assert_allclose(o2, sdpa(Q, K_rot.reshape(37, 16), V_t, 2)[0], rtol=1e-11, atol=1e-12)
+    # rotating the stored (pre-rebuild) caches instead is a different function
+    assert np.abs(o2 - o0).max() > 1e-3
+
+
+# ---- P14: uncompressed sink + local window --------------------------------------
+def test_window_ring_holds_exactly_the_sink_and_latest_tokens():
+    n_sink, n_recent, D = 4, 6, 3
+    win = np.full((n_sink + n_recent, D), -1.0)
+    for L in range(0, 40):                       # append token L (its id in every column)
+        orc.window_append(win, L, np.full((1, D), float(L)), n_sink, n_recent)
+        n = L + 1
+        for p in range(n):
+            if orc.in_window(p, n, n_sink, n_recent):
+                assert win[orc.window_row(p, n_sink, n_recent), 0] == p, (n, p)
+        kept = sorted(p for p in range(n) if orc.in_window(p, n, n_sink, n_recent))
+        assert kept == sorted(set(range(min(n_sink, n))) | set(range(max(0, n - n_recent), n)))
+    # several tokens in one call behave like one at a time
+    win2 = np.full_like(win, -1.0)
+    orc.window_append(win2, 0, np.arange(40, dtype=float)[:, None] * np.ones((1, D)), n_sink, n_recent)
+    np.testing.assert_array_equal(win2, win)
+
+
+def make_window(c, n_sink, n_recent, seed):
+    L, D = c["K_a"].shape
+    r = np.random.default_rng(seed)
+    Kf, Vf = r.standard_normal((L, D)), r.standard_normal((L, D))      # the target's true full rows
+    wk = np.zeros((n_sink + n_recent, D)); wv = np.zeros_like(wk)
+    orc.window_append(wk, 0, Kf, n_sink, n_recent); orc.window_append(wv, 0, Vf, n_sink, n_recent)
+    return Kf, Vf, wk, wv
+
+
+@pytest.mark.parametrize("L", [3, 10, 11, 29])
+def test_window_tokens_use_stored_rows_and_the_rest_the_rebuilt_ones(L):
+    n_sink, n_recent = 4, 6
+    c, Q = make_case(4, 2, 8, 8, L, seed=L)
+    Kf, Vf, wk, wv = make_window(c, n_sink, n_recent, 100 + L)
+    o, l = orc.echokv_decode_paper(Q[0], **c, n_kv_heads=2, window=(wk, wv, n_sink, n_recent))
+    K_t = orc.reconstruct(c["K_a"], c["K_r"], c["W_K"]); V_t = orc.reconstruct(c["V_a"], c["V_r"], c["W_V"])
+    for p in range(L):
+        if p < n_sink or p >= L - n_recent:
+            K_t[p], V_t[p] = Kf[p], Vf[p]
+    np.testing.assert_allclose(o, sdpa(Q, K_t, V_t, 2)[0], rtol=1e-11, atol=1e-12)
+    if L <= n_sink + n_recent:      # everything is in the window: the predictor plays no part
+        c2 = dict(c); c2["W_K"] = c["W_K"] * 7.0; c2["W_V"] = -c["W_V"]
+        o2, _ = orc.echokv_decode_paper(Q[0], **c2, n_kv_heads=2, window=(wk, wv, n_sink, n_recent))
+        np.testing.assert_array_equal(o, o2)
+        np.testing.assert_allclose(o, sdpa(Q, Kf, Vf, 2)[0], rtol=1e-11, atol=1e-12)
+
+
+def test_window_holding_the_rebuilt_rows_changes_nothing():
+    c, Q = make_case(2, 2, 8, 8, 25, seed=9)
+    K_t = orc.reconstruct(c["K_a"], c["K_r"], c["W_K"]); V_t = orc.reconstruct(c["V_a"], c["V_r"], c["W_V"])
+    wk = np.zeros((10, 16)); wv = np.zeros((10, 16))
+    orc.window_append(wk, 0, K_t, 4, 6); orc.window_append(wv, 0, V_t, 4, 6)
+    o0, l0 = orc.echokv_decode(Q[0], **c, n_kv_heads=2)
+    o1, l1 = orc.echokv_decode_paper(Q[0], **c, n_kv_heads=2, window=(wk, wv, 4, 6))
+    np.testing.assert_allclose(o1, o0, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(l1, l0, rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("use_rope,use_window", [(True, False), (False, True), (True, True)])
+def test_brute_force_matches_vectorised_decode_paper(use_rope, use_window):
+    c, Q = make_case(4, 2, 4, 4, 9, seed=31)
+    cos, sin = angle_tables(4, 16)
+    Kf, Vf, wk, wv = make_window(c, 2, 3, 77)
+    kw = dict(rope=(cos, sin) if use_rope else None, window=(wk, wv, 2, 3) if use_window else None)
+    o1, l1 = orc.echokv_decode_paper(Q[0], **c, n_kv_heads=2, **kw)
+    o2, l2 = orc.brute_force_decode_paper(Q[0], **c, n_kv_heads=2, **kw)
+    np.testing.assert_allclose(o1, o2, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(l1, l2, rtol=1e-11, atol=1e-12)
+
+
+def test_mutant_interleaved_pairing_fails_the_pairing_pin():
+    def interleaved(X, positions, cos, sin, n_heads):        # pairs (2i, 2i+1): the other convention
+        X = np.asarray(X, float); out = X.copy()
+        d = X.shape[1] // n_heads
+        for j, p in enumerate(positions):
+            for h in range(n_heads):
+                for i in range(d // 2):
+                    a, b = X[j, h * d + 2 * i], X[j, h * d + 2 * i + 1]
+                    out[j, h * d + 2 * i] = a * cos[p, i] - b * sin[p, i]
+                    out[j, h * d + 2 * i + 1] = b * cos[p, i] + a * sin[p, i]
+        return out
+    cos, sin = angle_tables(4, 4)
+    Y = interleaved(np.array([[1.0, 0.0, 0.0, 0.0]]), [3], cos, sin, 1)
+    assert np.abs(Y[0] - np.array([math.cos(3.0), 0.0, math.sin(3.0), 0.0])).max() > 0.1
+
+
+def test_synthetic_window_rows_agree_with_the_compressed_cache():
+    from paper_2603_22910_amd import synth
+    w = synth.Workload("win", "bf16", 4, 2, 64, 64, seed=3, seq_lens=(2, 140, 132, 133))
+    inp = synth.generate(w)
+    wk, wv = synth.window_rows(inp, 4, 128)
+    assert wk.shape == (4, 132, 128)
+    for b, L in enumerate(inp.seq_len[:4]):
+        for p in (0, 1, 3, 4, L - 129, L - 128, L - 1):
+            if 0 <= p < L and orc.in_window(p, L, 4, 128):
+                r = orc.window_row(p, 4, 128)
+                assert torch.equal(wk[b, r, :64], inp.K_r[inp.seq_start[b] + p])
+                assert torch.equal(wv[b, r, :64], inp.V_r[inp.seq_start[b] + p])
+                assert float(wk[b, r, 64:].abs().sum()) > 0
