@@ -160,6 +160,58 @@ int echokv_decode_attn(const echokv_shape *shape, const echokv_layer_cache *anch
                        const void *w_v, const void *q, void *out, float *lse_out,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* What the paper's own inference adds around Eq. 7 (both optional, independent):
+ *
+ * Rotary embedding (Sec. "Network Architecture": the predictor is fed keys taken
+ * BEFORE the rotary embedding, so the caches of both layers hold pre-rotation
+ * keys).  With rope_cos / rope_sin set, the key of cached token j -- retained or
+ * predicted -- is rotated to position j just before the dot product:
+ *   k'_i = k_i cos[j, i] - k_{i+d/2} sin[j, i],  k'_{i+d/2} = k_{i+d/2} cos[j, i] + k_i sin[j, i]
+ * for i < d/2 in every head (feature i pairs with i + d/2).  q must come in
+ * already rotated to its own position.  The tables are the caller's:
+ *   rope_cos, rope_sin : device [rope_positions, d/2] fp32; rope_positions >= every seq_len.
+ *
+ * Uncompressed window (Sec. "Experimental Setup": 4 sink tokens and a local
+ * window of 128 tokens stay uncompressed).  With win_k / win_v set, the first
+ * n_sink and the latest n_recent positions of every sequence take their keys
+ * and values from these full-width rows of the TARGET layer instead of the
+ * compressed cache; all other positions are rebuilt as usual.
+ *   win_k, win_v : device [batch, n_sink + n_recent, D], dtype of the caches,
+ *                  pre-rotation; position p of sequence b is row p if p < n_sink,
+ *                  else row n_sink + (p - n_sink) % n_recent (a ring).
+ * echokv_window_append keeps the rows current; the compressed cache still
+ * receives every token (echokv_cache_append), the window is an extra copy. */
+typedef struct {
+  const float *rope_cos;
+  const float *rope_sin;
+  int32_t rope_positions;
+  int32_t n_sink;
+  int32_t n_recent;
+  const void *win_k;
+  const void *win_v;
+} echokv_decode_extras;
+
+/* echokv_decode_attn with the extras above (extras == NULL, or all of its
+ * pointers NULL: the same as echokv_decode_attn).  Not available with
+ * ECHOKV_FLAG_ABSORBED (ECHOKV_ERR_UNSUPPORTED).  Same workspace size. */
+int echokv_decode_attn_ex(const echokv_shape *shape, const echokv_layer_cache *anchor,
+                          const echokv_layer_cache *target, const void *w_k,
+                          const void *w_v, const void *q,
+                          const echokv_decode_extras *extras, void *out, float *lse_out,
+                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Append the full-width rows of new tokens of the target layer to the window.
+ *   seq_len_before : HOST [batch] tokens each sequence held before this append
+ *   k_new, v_new   : device [sum n_new, D] packed by sequence (the same rows that
+ *                    echokv_cache_append is given for the target layer)
+ *   n_new          : HOST [batch]
+ * Rows that are outside the window once the call's tokens are all in are skipped;
+ * the ring row of a token that leaves the local window is overwritten. */
+int echokv_window_append(const echokv_shape *shape, void *win_k, void *win_v,
+                         int32_t n_sink, int32_t n_recent, int32_t batch,
+                         const int32_t *seq_len_before, const void *k_new,
+                         const void *v_new, const int32_t *n_new, void *hip_stream);
+
 /* Causal chunk of T_q queries of sequence `seq` (Eq. 7 with a causal mask):
  * query i sits at position q_pos0 + i and attends cached tokens
  * 0 .. q_pos0 + i inclusive, all read from the compressed cache (predicted

@@ -25,7 +25,7 @@ FLAG_ABSORBED = 8
 EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn",
            "echokv_profile_enable", "echokv_profile_read", "echokv_pack_weights",
-           "echokv_cache_compress")
+           "echokv_cache_compress", "echokv_decode_attn_ex", "echokv_window_append")
 
 
 class EchoKVError(RuntimeError):
@@ -44,6 +44,12 @@ class LayerCacheC(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("width", C.c_int32), ("batch", C.c_int32),
                 ("pool_tokens", C.c_int64), ("seq_start", C.POINTER(C.c_int64)),
                 ("seq_len", C.POINTER(C.c_int32)), ("seq_cap", C.POINTER(C.c_int32))]
+
+
+class DecodeExtras(C.Structure):
+    _fields_ = [("rope_cos", C.c_void_p), ("rope_sin", C.c_void_p), ("rope_positions", C.c_int32),
+                ("n_sink", C.c_int32), ("n_recent", C.c_int32), ("win_k", C.c_void_p),
+                ("win_v", C.c_void_p)]
 
 
 def load() -> C.CDLL:
@@ -72,6 +78,15 @@ def load() -> C.CDLL:
     lib.echokv_decode_attn.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
                                        C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.echokv_decode_attn_ex.restype = C.c_int
+    lib.echokv_decode_attn_ex.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
+                                          C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.POINTER(DecodeExtras), C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_size_t, C.c_void_p]
+    lib.echokv_window_append.restype = C.c_int
+    lib.echokv_window_append.argtypes = [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int32,
+                                         C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_void_p,
+                                         C.c_void_p, C.POINTER(C.c_int32), C.c_void_p]
     lib.echokv_prefill_attn.restype = C.c_int
     lib.echokv_prefill_attn.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
                                         C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_int32,
@@ -194,6 +209,33 @@ def decode_attn(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, 
     _check(load().echokv_decode_attn(C.byref(shape), C.byref(a), C.byref(t), _ptr(w_k), _ptr(w_v),
                                      _ptr(q), _ptr(out), _ptr(lse_out), _ptr(workspace), nbytes,
                                      _stream(stream)), "echokv_decode_attn")
+
+
+def decode_attn_ex(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, q, out,
+                   lse_out, workspace, rope=None, window=None, stream=None):
+    """rope = (cos, sin) device fp32 [positions, d/2]; window = (win_k, win_v, n_sink, n_recent)."""
+    a, t = anchor.as_c(), target.as_c()
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ex = DecodeExtras()
+    if rope is not None:
+        ex.rope_cos, ex.rope_sin, ex.rope_positions = _ptr(rope[0]), _ptr(rope[1]), int(rope[0].shape[0])
+    if window is not None:
+        ex.win_k, ex.win_v, ex.n_sink, ex.n_recent = _ptr(window[0]), _ptr(window[1]), int(window[2]), int(window[3])
+    _check(load().echokv_decode_attn_ex(C.byref(shape), C.byref(a), C.byref(t), _ptr(w_k), _ptr(w_v),
+                                        _ptr(q), C.byref(ex), _ptr(out), _ptr(lse_out),
+                                        _ptr(workspace), nbytes, _stream(stream)),
+           "echokv_decode_attn_ex")
+
+
+def window_append(shape: Shape, win_k, win_v, n_sink: int, n_recent: int, seq_len_before, k_new,
+                  v_new, n_new, stream=None):
+    before = np.ascontiguousarray(seq_len_before, dtype=np.int32)
+    nn = np.ascontiguousarray(n_new, dtype=np.int32)
+    _check(load().echokv_window_append(C.byref(shape), _ptr(win_k), _ptr(win_v), int(n_sink),
+                                       int(n_recent), len(nn),
+                                       before.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(k_new),
+                                       _ptr(v_new), nn.ctypes.data_as(C.POINTER(C.c_int32)),
+                                       _stream(stream)), "echokv_window_append")
 
 
 def prefill_attn(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, seq: int, q,

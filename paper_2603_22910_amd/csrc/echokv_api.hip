@@ -187,13 +187,13 @@ int pick_split_tokens(int64_t total_tokens, int n_heads_blocks) {
 
 template <typename T, typename TO>
 int merge_launch(const Dims& dm, const float* po, const float* pml, void* out, float* lse,
-                 int64_t out_seq0, int n_stream, int stream_step, int fused_step,
+                 int64_t out_seq0, int n_stream, int stream_step, int fused_step, int win_slot0,
                  SeqMeta& mt, hipStream_t st) {
   MergeArgs<TO> ma;
   ma.part_o = po; ma.part_ml = pml; ma.out = (TO*)out; ma.lse = lse;
   ma.H_q = dm.H_q; ma.G = dm.G; ma.d = dm.d;
   ma.n_stream_kv_heads = n_stream; ma.stream_step = stream_step; ma.fused_step = fused_step;
-  ma.out_seq0 = out_seq0;
+  ma.out_seq0 = out_seq0; ma.win_slot0 = win_slot0;
   hipLaunchKernelGGL((merge_kernel<TO>), dim3(dm.H_q, mt.n), dim3(256), 0, st, ma, mt);
   LAUNCH_CHECK();
   return ECHOKV_OK;
@@ -202,8 +202,14 @@ int merge_launch(const Dims& dm, const float* po, const float* pml, void* out, f
 template <typename T>
 int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
                 const echokv_layer_cache* tg, const void* w_k, const void* w_v, const void* q,
-                void* out, float* lse, char* ws, hipStream_t st) {
+                const echokv_decode_extras* ex, void* out, float* lse, char* ws, hipStream_t st) {
   const int n_ret_heads = dm.g0, n_rec_heads = dm.H_kv - n_ret_heads;
+  KvExtras kx;
+  if (ex) {
+    kx.rope_cos = ex->rope_cos; kx.rope_sin = ex->rope_sin;
+    if (ex->win_k) { kx.n_sink = ex->n_sink; kx.n_recent = ex->n_recent; }
+  }
+  const Window win = {kx.n_sink, kx.n_recent};
   const bool fused = !(flags & ECHOKV_FLAG_UNFUSED) && fused_decode_supported<T>(dm.d, dm.G);
   const T* wk = nullptr; const T* wv = nullptr;
   bool have_w = false;
@@ -215,7 +221,7 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
       mt.start[b] = an->seq_start[b0 + b]; mt.len[b] = an->seq_len[b0 + b]; tokens += mt.len[b];
     }
     const int slots = fill_slots(mt);
-    const WsPlan wp = plan_ws(dm, slots, fused ? 0 : (int64_t)slots * kSlotTokens);
+    const WsPlan wp = plan_ws(dm, slots + mt.n, fused ? 0 : (int64_t)slots * kSlotTokens);   // + one window partial per sequence
     if (!have_w) {      // the plan of the first (largest-index-independent) group places the extended weights
       int rcw = effective_weights<T>(dm, w_k, w_v, ws, wp, &wk, &wv, st);
       if (rcw) return rcw;
@@ -232,6 +238,7 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
       a.row_mode = 0; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
       a.split_tokens = pick_split_tokens(tokens, n_ret_heads);
       a.part_o = po; a.part_ml = pml;
+      a.rope_cos = kx.rope_cos; a.rope_sin = kx.rope_sin; a.win = win;
       stream_step = a.split_tokens / kSlotTokens;
       int rc = launch_attn_split<T>(dm, a, mt, n_ret_heads, st);
       if (rc) return rc;
@@ -248,18 +255,18 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
           rc = launch_fused_decode_f32(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale,
                                        (const float*)an->k, (const float*)an->v, (const float*)tg->k,
                                        (const float*)tg->v, (const float*)wk, (const float*)wv, qq,
-                                       po, pml, mt, &fused_step, st);
+                                       po, pml, mt, &fused_step, st, kx);
         else if ((flags & ECHOKV_FLAG_W_PACKED) && !(flags & ECHOKV_FLAG_STAGED))
           rc = launch_fused_decode_dma(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale,
                                        (const bf16_t*)an->k, (const bf16_t*)an->v,
                                        (const bf16_t*)tg->k, (const bf16_t*)tg->v,
                                        (const bf16_t*)wk, (const bf16_t*)wv, (const bf16_t*)qq, po,
-                                       pml, mt, &fused_step, st);
+                                       pml, mt, &fused_step, st, kx);
         else
           rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale,
                                       (const T*)an->k, (const T*)an->v, (const T*)tg->k,
                                       (const T*)tg->v, wk, wv, qq, po,
-                                      pml, mt, &fused_step, st, (flags & ECHOKV_FLAG_W_PACKED) != 0);
+                                      pml, mt, &fused_step, st, (flags & ECHOKV_FLAG_W_PACKED) != 0, kx);
         if (g_prof.on) {
           HIP_TRY(hipEventRecord(e1, st));
           g_prof.pairs.emplace_back(e0, e1);
@@ -289,14 +296,41 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
         a.row_mode = 1; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
         a.split_tokens = pick_split_tokens(tokens, n_rec_heads);
         a.part_o = po; a.part_ml = pml;
+        a.rope_cos = kx.rope_cos; a.rope_sin = kx.rope_sin; a.win = win;
         fused_step = a.split_tokens / kSlotTokens;
         rc = launch_attn_split<T>(dm, a, mt, n_rec_heads, st);
         if (rc) return rc;
       }
     }
+    int win_slot0 = -1;
+    if (win.on()) {
+      // the window's tokens: plain attention over its full-width rows, all KV heads, one
+      // partial per sequence placed after the regular slots
+      win_slot0 = slots;
+      AttnArgs<T> a;
+      a.k = (const T*)ex->win_k; a.v = (const T*)ex->win_v; a.ld = dm.D; a.col0 = 0; a.head0 = 0;
+      a.row_mode = 3; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
+      a.split_tokens = kSlotTokens;
+      a.part_o = po; a.part_ml = pml;
+      a.rope_cos = kx.rope_cos; a.rope_sin = kx.rope_sin; a.win = win;
+      a.seq0 = b0; a.win_slot0 = win_slot0;
+      SeqMeta wm = mt;                         // one chunk per sequence
+      for (int b = 0; b <= wm.n; ++b) wm.tbase[b] = b;
+      const int GT = (dm.G % 4 == 0) ? 4 : (dm.G % 2 == 0) ? 2 : 1;
+      dim3 grid(wm.n, dm.H_kv * (dm.G / GT));
+      constexpr int LPR64 = 64 * (int)sizeof(T) / 16, LPR128 = 128 * (int)sizeof(T) / 16;
+#define WIN_CASE(LPR_, GT_) hipLaunchKernelGGL((attn_split_kernel<T, LPR_, GT_>), grid, dim3(256), 0, st, a, wm)
+      if (dm.d == 64) {
+        if (GT == 4) WIN_CASE(LPR64, 4); else if (GT == 2) WIN_CASE(LPR64, 2); else WIN_CASE(LPR64, 1);
+      } else {
+        if (GT == 4) WIN_CASE(LPR128, 4); else if (GT == 2) WIN_CASE(LPR128, 2); else WIN_CASE(LPR128, 1);
+      }
+#undef WIN_CASE
+      LAUNCH_CHECK();
+    }
     int rc = dm.out_bf16
-        ? merge_launch<T, bf16_t>(dm, po, pml, out, lse, b0, n_ret_heads, stream_step, fused_step, mt, st)
-        : merge_launch<T, float>(dm, po, pml, out, lse, b0, n_ret_heads, stream_step, fused_step, mt, st);
+        ? merge_launch<T, bf16_t>(dm, po, pml, out, lse, b0, n_ret_heads, stream_step, fused_step, win_slot0, mt, st)
+        : merge_launch<T, float>(dm, po, pml, out, lse, b0, n_ret_heads, stream_step, fused_step, win_slot0, mt, st);
     if (rc) return rc;
   }
   return ECHOKV_OK;
@@ -416,8 +450,8 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
       if (rc) return rc;
     }
     int rc = dm.out_bf16
-        ? merge_launch<T, bf16_t>(dm, po, pml, out, lse, i0, n_ret_heads, stream_step, fused_step, mt, st)
-        : merge_launch<T, float>(dm, po, pml, out, lse, i0, n_ret_heads, stream_step, fused_step, mt, st);
+        ? merge_launch<T, bf16_t>(dm, po, pml, out, lse, i0, n_ret_heads, stream_step, fused_step, -1, mt, st)
+        : merge_launch<T, float>(dm, po, pml, out, lse, i0, n_ret_heads, stream_step, fused_step, -1, mt, st);
     if (rc) return rc;
   }
   return ECHOKV_OK;
@@ -549,7 +583,7 @@ int absorbed_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_lay
 }
 
 size_t decode_ws_bytes(const Dims& dm, int batch, int64_t total_tokens, bool unfused) {
-  const int64_t slots = total_tokens / kSlotTokens + batch;
+  const int64_t slots = total_tokens / kSlotTokens + 2 * (int64_t)batch;   // + one window partial per sequence
   return plan_ws(dm, slots, unfused ? slots * kSlotTokens : 0).total;
 }
 size_t prefill_ws_bytes(const Dims& dm, int64_t Ltot, int max_q) {
@@ -722,10 +756,11 @@ int echokv_reconstruct(const echokv_shape* shape, const echokv_layer_cache* anch
                  : reconstruct_impl<float>(dm, anchor, target, w_k, w_v, seq, tok_begin, tok_end, k_out, v_out, st);
 }
 
-int echokv_decode_attn(const echokv_shape* shape, const echokv_layer_cache* anchor,
-                       const echokv_layer_cache* target, const void* w_k, const void* w_v,
-                       const void* q, void* out, float* lse_out, void* workspace,
-                       size_t workspace_bytes, void* hip_stream) {
+int echokv_decode_attn_ex(const echokv_shape* shape, const echokv_layer_cache* anchor,
+                          const echokv_layer_cache* target, const void* w_k, const void* w_v,
+                          const void* q, const echokv_decode_extras* extras, void* out,
+                          float* lse_out, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
   Dims dm;
   int rc = check_shape(shape, &dm);
   if (rc) return rc;
@@ -734,16 +769,29 @@ int echokv_decode_attn(const echokv_shape* shape, const echokv_layer_cache* anch
   if (dm.d_out > 0 && (!w_k || !w_v)) return ECHOKV_ERR_NULL;
   if (!q || !out) return ECHOKV_ERR_NULL;
   int64_t max_chunk_slots = 0;
+  int32_t max_len = 0;
   for (int b0 = 0; b0 < anchor->batch; b0 += kMaxSeqPerLaunch) {
     int64_t s = 0;
-    for (int b = b0; b < std::min(anchor->batch, b0 + kMaxSeqPerLaunch); ++b) {
+    const int b1 = std::min(anchor->batch, b0 + kMaxSeqPerLaunch);
+    for (int b = b0; b < b1; ++b) {
       if (anchor->seq_len[b] < 1) return ECHOKV_ERR_SHAPE;
       s += slots_for(anchor->seq_len[b]);
+      max_len = std::max(max_len, anchor->seq_len[b]);
     }
-    max_chunk_slots = std::max(max_chunk_slots, s);
+    max_chunk_slots = std::max(max_chunk_slots, s + (b1 - b0));      // + one window partial per sequence
+  }
+  bool has_extras = false;
+  if (extras) {
+    if ((extras->rope_cos == nullptr) != (extras->rope_sin == nullptr)) return ECHOKV_ERR_NULL;
+    if ((extras->win_k == nullptr) != (extras->win_v == nullptr)) return ECHOKV_ERR_NULL;
+    if (extras->rope_cos && extras->rope_positions < max_len) return ECHOKV_ERR_SHAPE;
+    if (extras->win_k && (extras->n_sink < 0 || extras->n_recent < 0 ||
+                          extras->n_sink + extras->n_recent < 1)) return ECHOKV_ERR_SHAPE;
+    has_extras = extras->rope_cos || extras->win_k;
   }
   if (shape->flags & ECHOKV_FLAG_ABSORBED) {
-    if (!absorbed_supported(dm, shape->flags)) return ECHOKV_ERR_UNSUPPORTED;
+    // a rotation between reconstruction and the dot product breaks the re-association of the keys
+    if (has_extras || !absorbed_supported(dm, shape->flags)) return ECHOKV_ERR_UNSUPPORTED;
     const size_t need = absorbed_need(dm, anchor);
     if (need == (size_t)-1) return ECHOKV_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < need) return ECHOKV_ERR_WORKSPACE;
@@ -761,8 +809,57 @@ int echokv_decode_attn(const echokv_shape* shape, const echokv_layer_cache* anch
   if (!workspace || workspace_bytes < need) return ECHOKV_ERR_WORKSPACE;
   if ((uintptr_t)workspace % 256) return ECHOKV_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
-  return dm.bf16 ? decode_impl<bf16_t>(dm, shape->flags, anchor, target, w_k, w_v, q, out, lse_out, (char*)workspace, st)
-                 : decode_impl<float>(dm, shape->flags, anchor, target, w_k, w_v, q, out, lse_out, (char*)workspace, st);
+  const echokv_decode_extras* ex = has_extras ? extras : nullptr;
+  return dm.bf16 ? decode_impl<bf16_t>(dm, shape->flags, anchor, target, w_k, w_v, q, ex, out, lse_out, (char*)workspace, st)
+                 : decode_impl<float>(dm, shape->flags, anchor, target, w_k, w_v, q, ex, out, lse_out, (char*)workspace, st);
+}
+
+int echokv_decode_attn(const echokv_shape* shape, const echokv_layer_cache* anchor,
+                       const echokv_layer_cache* target, const void* w_k, const void* w_v,
+                       const void* q, void* out, float* lse_out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+  return echokv_decode_attn_ex(shape, anchor, target, w_k, w_v, q, nullptr, out, lse_out, workspace,
+                               workspace_bytes, hip_stream);
+}
+
+int echokv_window_append(const echokv_shape* shape, void* win_k, void* win_v, int32_t n_sink,
+                         int32_t n_recent, int32_t batch, const int32_t* seq_len_before,
+                         const void* k_new, const void* v_new, const int32_t* n_new,
+                         void* hip_stream) {
+  Dims dm;
+  int rc = check_shape(shape, &dm);
+  if (rc) return rc;
+  if (!win_k || !win_v || !seq_len_before || !n_new) return ECHOKV_ERR_NULL;
+  if (batch <= 0 || n_sink < 0 || n_recent < 0 || n_sink + n_recent < 1) return ECHOKV_ERR_SHAPE;
+  int64_t total = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (seq_len_before[b] < 0 || n_new[b] < 0) return ECHOKV_ERR_SHAPE;
+    total += n_new[b];
+  }
+  if (total == 0) return ECHOKV_OK;
+  if (!k_new || !v_new) return ECHOKV_ERR_NULL;
+  hipStream_t st = (hipStream_t)hip_stream;
+  int64_t src_row = 0;
+  for (int b0 = 0; b0 < batch; b0 += kMaxSeqPerLaunch) {
+    SeqMeta mt;
+    mt.n = std::min(kMaxSeqPerLaunch, batch - b0);
+    int rows = 0;
+    for (int b = 0; b < mt.n; ++b) {
+      mt.start[b] = seq_len_before[b0 + b]; mt.len[b] = n_new[b0 + b];
+      mt.tbase[b] = rows; rows += n_new[b0 + b];
+    }
+    mt.tbase[mt.n] = rows;
+    if (rows == 0) continue;
+    WinAppendArgs a;
+    const int64_t rb = (int64_t)dm.D * dm.es;
+    a.src[0] = (const char*)k_new + src_row * rb; a.src[1] = (const char*)v_new + src_row * rb;
+    a.dst[0] = (char*)win_k; a.dst[1] = (char*)win_v;
+    a.row_bytes = rb; a.rows = rows; a.seq0 = b0; a.win = Window{n_sink, n_recent};
+    hipLaunchKernelGGL(window_append_kernel, dim3(std::min(rows, 4096), 2), dim3(256), 0, st, a, mt);
+    LAUNCH_CHECK();
+    src_row += rows;
+  }
+  return ECHOKV_OK;
 }
 
 int echokv_prefill_attn(const echokv_shape* shape, const echokv_layer_cache* anchor,

@@ -48,6 +48,10 @@ struct Args {
   int32_t D, m, d_out, H_q, G, n_ret_heads;
   float scale;
   int32_t n_col_tiles, n_tiles;   // column tiles; token tiles * column tiles
+  // paper-faithful extras (null / zero: off): rotary tables [positions, d/2] applied to the rebuilt
+  // keys by token position; tokens held by the uncompressed window are masked out here
+  const float* rope_cos; const float* rope_sin;
+  int32_t n_sink, n_recent;
 };
 
 // LDS tile: [rows][64 k] bf16, a row is 8 chunks of 16 bytes; chunk c of row r
@@ -499,9 +503,25 @@ __device__ __forceinline__ void pin_acc(floatx16_t (&acc)[4][4]) {
     for (int j = 0; j < 4; ++j) asm volatile("" : "+a"(acc[i][j]));
 }
 
-template <int HD>
+// Extras of the score epilogue: rotary tables (null: none) and the token range [lo, hi) of the
+// sequence that counts (tokens outside are masked: past the end, or held by the window).
+struct KExtra {
+  const float* cos; const float* sin;
+  int lo, hi;
+};
+__device__ __forceinline__ KExtra make_kextra(const float* cos, const float* sin, int n_sink,
+                                              int n_recent, int L) {
+  KExtra x;
+  x.cos = cos; x.sin = sin;
+  const bool win = n_sink + n_recent > 0;
+  x.lo = win ? min(n_sink, L) : 0;
+  x.hi = win ? max(x.lo, L - n_recent) : L;
+  return x;
+}
+
+template <int HD, bool ROPE>
 __device__ __forceinline__ void k_epilogue(floatx16_t (&acc)[4][4], EpiSmem& e, int G,
-                                           int wave, int lane, int jw0, int L) {
+                                           int wave, int lane, int jw0, int L, const KExtra& x) {
   constexpr int HPW = WN / HD, CBH = HD / 32;
   const int wc = wave & 1, lr = lane & 31, lh = lane >> 5;
 #pragma unroll
@@ -510,27 +530,67 @@ __device__ __forceinline__ void k_epilogue(floatx16_t (&acc)[4][4], EpiSmem& e, 
       pin_acc(acc);
       const float* qs = &e.q[((wc * HPW + hw) * G + g) * HD];
       float s[4] = {0.f, 0.f, 0.f, 0.f};
+      if constexpr (!ROPE) {
 #pragma unroll
-      for (int cb = 0; cb < CBH; ++cb) {
+        for (int cb = 0; cb < CBH; ++cb) {
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const float4 qv = *reinterpret_cast<const float4*>(qs + cb * 32 + r4 * 8 + lh * 4);
+          for (int r4 = 0; r4 < 4; ++r4) {
+            const float4 qv = *reinterpret_cast<const float4*>(qs + cb * 32 + r4 * 8 + lh * 4);
 #pragma unroll
-          for (int ji = 0; ji < 4; ++ji) {
-            const floatx16_t& c = acc[hw * CBH + cb][ji];
-            s[ji] = fmaf(qv.x, c[r4 * 4 + 0], s[ji]);
-            s[ji] = fmaf(qv.y, c[r4 * 4 + 1], s[ji]);
-            s[ji] = fmaf(qv.z, c[r4 * 4 + 2], s[ji]);
-            s[ji] = fmaf(qv.w, c[r4 * 4 + 3], s[ji]);
+            for (int ji = 0; ji < 4; ++ji) {
+              const floatx16_t& c = acc[hw * CBH + cb][ji];
+              s[ji] = fmaf(qv.x, c[r4 * 4 + 0], s[ji]);
+              s[ji] = fmaf(qv.y, c[r4 * 4 + 1], s[ji]);
+              s[ji] = fmaf(qv.z, c[r4 * 4 + 2], s[ji]);
+              s[ji] = fmaf(qv.w, c[r4 * 4 + 3], s[ji]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
           }
-          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+        // Rotary embedding of the rebuilt key at its token's position, folded into the dot
+        // product: feature c pairs with c + HD/2, which this lane holds HD/64 column blocks
+        // further on.  With a = k_c, b = k_{c+HD/2}:
+        //   q_c (a cos - b sin) + q_{c+HD/2} (b cos + a sin)
+        //     = cos (a q_c + b q_{c+HD/2}) + sin (a q_{c+HD/2} - b q_c)
+        // The accumulators are only read.  Masked tokens borrow the last valid table row.
+        constexpr int HB = CBH / 2;
+#pragma unroll
+        for (int ji = 0; ji < 4; ++ji) {
+          const int pos = min(jw0 + ji * 32 + lr, L - 1);
+          const float* cr = x.cos + (int64_t)pos * (HD / 2) + lh * 4;
+          const float* sr = x.sin + (int64_t)pos * (HD / 2) + lh * 4;
+#pragma unroll
+          for (int cb = 0; cb < HB; ++cb) {
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+              const float4 c4 = *reinterpret_cast<const float4*>(cr + cb * 32 + r4 * 8);
+              const float4 s4 = *reinterpret_cast<const float4*>(sr + cb * 32 + r4 * 8);
+              const float4 qa = *reinterpret_cast<const float4*>(qs + cb * 32 + r4 * 8 + lh * 4);
+              const float4 qb = *reinterpret_cast<const float4*>(qs + (cb + HB) * 32 + r4 * 8 + lh * 4);
+              const floatx16_t& ka = acc[hw * CBH + cb][ji];
+              const floatx16_t& kb = acc[hw * CBH + cb + HB][ji];
+              const float cc[4] = {c4.x, c4.y, c4.z, c4.w}, ss[4] = {s4.x, s4.y, s4.z, s4.w};
+              const float q0[4] = {qa.x, qa.y, qa.z, qa.w}, q1[4] = {qb.x, qb.y, qb.z, qb.w};
+#pragma unroll
+              for (int i = 0; i < 4; ++i) {
+                const float a = ka[r4 * 4 + i], b = kb[r4 * 4 + i];
+                const float t1 = fmaf(a, q0[i], b * q1[i]);
+                const float t2 = fmaf(a, q1[i], -b * q0[i]);
+                s[ji] = fmaf(cc[i], t1, fmaf(ss[i], t2, s[ji]));
+              }
+              asm volatile("" ::: "memory");       // keep the table loads of later rounds from piling up
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
         }
       }
       float mx = -INFINITY;
 #pragma unroll
       for (int ji = 0; ji < 4; ++ji) {
         s[ji] += __shfl_xor(s[ji], 32, 64);
-        if (jw0 + ji * 32 + lr >= L) s[ji] = -INFINITY;
+        const int tok = jw0 + ji * 32 + lr;
+        if (tok < x.lo || tok >= x.hi) s[ji] = -INFINITY;
         mx = fmaxf(mx, s[ji]);
       }
       mx = wave_max(mx, 32);
@@ -597,7 +657,7 @@ __device__ __forceinline__ void v_epilogue(floatx16_t (&acc)[4][4], const EpiSme
   }
 }
 
-template <int HD, bool PACKED>
+template <int HD, bool PACKED, bool ROPE>
 __global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta meta) {
   __shared__ Smem sm;
   char* smem = reinterpret_cast<char*>(&sm);
@@ -631,7 +691,8 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta 
   make_io(io, a, a.xa[1] + row0 * a.D, a.xr[1] + row0 * a.m, a.w[1] + woff, last, nclamp, tid, rot);
   pass_prefetch<PACKED>(sa, io, a);
   const int jw0 = j0 + wt * WM;                 // first token of this wave
-  k_epilogue<HD>(acc, sm.e, a.G, wave, lane, jw0, L);
+  k_epilogue<HD, ROPE>(acc, sm.e, a.G, wave, lane, jw0, L,
+                       make_kextra(a.rope_cos, a.rope_sin, a.n_sink, a.n_recent, L));
   // ---- V_hat = X W_V (e.p / e.ml are wave-private; the pass's barriers order them anyway)
   gemm_pass<false, PACKED>(acc, smem, a, io, sa, sb, tid);
   if (jw0 >= L) return;                          // wave has no valid token: no partial
@@ -685,6 +746,12 @@ __global__ __launch_bounds__(NTHREADS) void recon_mfma_kernel(Args a, SeqMeta me
 }  // namespace fused
 
 // ---- host-side launchers ------------------------------------------------------------
+// Paper-faithful extras of a decode call as the launchers take them (all zero: off).
+struct KvExtras {
+  const float* rope_cos = nullptr; const float* rope_sin = nullptr;
+  int n_sink = 0, n_recent = 0;
+};
+
 template <typename T> inline bool fused_decode_supported(int d, int G) {
   return (d == 64 || d == 128) && (128 / d) * G <= fused::MAXPAIR;
 }
@@ -702,11 +769,13 @@ inline int launch_fused_decode(int H_q, int H_kv, int d, int m, int d_out, int n
                                float scale, const T* ka,
                                const T* va, const T* kr, const T* vr, const T* wk, const T* wv,
                                const T* q, float* part_o, float* part_ml, SeqMeta& mt,
-                               int* fused_step, hipStream_t st, bool packed = false) {
+                               int* fused_step, hipStream_t st, bool packed = false,
+                               const KvExtras& ex = KvExtras()) {
   if constexpr (sizeof(T) != 2) {
     return 6;
   } else {
     fused::Args a;
+    a.rope_cos = ex.rope_cos; a.rope_sin = ex.rope_sin; a.n_sink = ex.n_sink; a.n_recent = ex.n_recent;
     a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk; a.w[1] = wv;
     a.q = q; a.part_o = part_o; a.part_ml = part_ml;
     a.out[0] = a.out[1] = nullptr; a.ldo = 0; a.col0 = 0;
@@ -716,10 +785,15 @@ inline int launch_fused_decode(int H_q, int H_kv, int d, int m, int d_out, int n
     a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
     const int grid = ((a.n_tiles + 7) / 8) * 8;
     const dim3 g(grid), blk(fused::NTHREADS);
-    if (d == 128 && packed) hipLaunchKernelGGL((fused::fused_decode_kernel<128, true>), g, blk, 0, st, a, mt);
-    else if (d == 128) hipLaunchKernelGGL((fused::fused_decode_kernel<128, false>), g, blk, 0, st, a, mt);
-    else if (packed) hipLaunchKernelGGL((fused::fused_decode_kernel<64, true>), g, blk, 0, st, a, mt);
-    else hipLaunchKernelGGL((fused::fused_decode_kernel<64, false>), g, blk, 0, st, a, mt);
+    const bool rope = ex.rope_cos != nullptr;
+#define ECHOKV_FUSED_CASE(HD_, PK_) \
+    do { if (rope) hipLaunchKernelGGL((fused::fused_decode_kernel<HD_, PK_, true>), g, blk, 0, st, a, mt); \
+         else hipLaunchKernelGGL((fused::fused_decode_kernel<HD_, PK_, false>), g, blk, 0, st, a, mt); } while (0)
+    if (d == 128 && packed) ECHOKV_FUSED_CASE(128, true);
+    else if (d == 128) ECHOKV_FUSED_CASE(128, false);
+    else if (packed) ECHOKV_FUSED_CASE(64, true);
+    else ECHOKV_FUSED_CASE(64, false);
+#undef ECHOKV_FUSED_CASE
     if (hipGetLastError() != hipSuccess) return 7;
     *fused_step = 1;
     return 0;
@@ -738,6 +812,7 @@ inline int launch_recon_mfma(int D, int m, int d_out, const T* ka, const T* va, 
     fused::Args a;
     a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk; a.w[1] = wv;
     a.q = nullptr; a.part_o = nullptr; a.part_ml = nullptr;
+    a.rope_cos = a.rope_sin = nullptr; a.n_sink = a.n_recent = 0;
     a.out[0] = out_k; a.out[1] = out_v; a.ldo = ldo; a.col0 = col0;
     a.D = D; a.m = m; a.d_out = d_out; a.H_q = 0; a.G = 1; a.n_ret_heads = 0; a.scale = 0.f;
     a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;

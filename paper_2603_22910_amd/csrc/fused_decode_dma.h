@@ -177,7 +177,7 @@ __device__ __forceinline__ void pass_run(floatx16_t (&acc)[4][4], const Stages& 
   wait_loads_and_barrier<0>();           // drain: the stages are free for the next pass
 }
 
-template <int HD>
+template <int HD, bool ROPE>
 __global__ __launch_bounds__(NTHREADS) void fused_decode_dma_kernel(Args a, SeqMeta meta) {
   __shared__ __attribute__((aligned(1024))) char sx0[kTileBytes];
   __shared__ __attribute__((aligned(1024))) char sx1[kTileBytes];
@@ -220,7 +220,8 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_dma_kernel(Args a, SeqM
   io.pa = a.xa[1] + row0 * a.D; io.pr = a.xr[1] + row0 * a.m; io.pw = a.w[1] + (int64_t)n0 * d_in;
   pass_begin(st, ln, io, wave_u);
   const int jw0 = j0 + wt * WM;
-  fused::k_epilogue<HD>(acc, epi, a.G, wave, lane, jw0, L);
+  fused::k_epilogue<HD, ROPE>(acc, epi, a.G, wave, lane, jw0, L,
+                        fused::make_kextra(a.rope_cos, a.rope_sin, a.n_sink, a.n_recent, L));
   // ---- V_hat = X W_V
   pass_run<false>(acc, st, ln, io, wave_u);
   if (jw0 >= L) return;
@@ -234,8 +235,10 @@ inline int launch_fused_decode_dma(int H_q, int H_kv, int d, int m, int d_out, i
                                    float scale, const bf16_t* ka, const bf16_t* va,
                                    const bf16_t* kr, const bf16_t* vr, const bf16_t* wk_packed,
                                    const bf16_t* wv_packed, const bf16_t* q, float* part_o,
-                                   float* part_ml, SeqMeta& mt, int* fused_step, hipStream_t st) {
+                                   float* part_ml, SeqMeta& mt, int* fused_step, hipStream_t st,
+                                   const KvExtras& ex = KvExtras()) {
   fused::Args a;
+  a.rope_cos = ex.rope_cos; a.rope_sin = ex.rope_sin; a.n_sink = ex.n_sink; a.n_recent = ex.n_recent;
   a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk_packed; a.w[1] = wv_packed;
   a.q = q; a.part_o = part_o; a.part_ml = part_ml;
   a.out[0] = a.out[1] = nullptr; a.ldo = 0; a.col0 = 0;
@@ -244,8 +247,11 @@ inline int launch_fused_decode_dma(int H_q, int H_kv, int d, int m, int d_out, i
   a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;
   a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
   const dim3 g(((a.n_tiles + 7) / 8) * 8), blk(fused::NTHREADS);
-  if (d == 128) hipLaunchKernelGGL((fdma::fused_decode_dma_kernel<128>), g, blk, 0, st, a, mt);
-  else hipLaunchKernelGGL((fdma::fused_decode_dma_kernel<64>), g, blk, 0, st, a, mt);
+  const bool rope = ex.rope_cos != nullptr;
+  if (d == 128 && rope) hipLaunchKernelGGL((fdma::fused_decode_dma_kernel<128, true>), g, blk, 0, st, a, mt);
+  else if (d == 128) hipLaunchKernelGGL((fdma::fused_decode_dma_kernel<128, false>), g, blk, 0, st, a, mt);
+  else if (rope) hipLaunchKernelGGL((fdma::fused_decode_dma_kernel<64, true>), g, blk, 0, st, a, mt);
+  else hipLaunchKernelGGL((fdma::fused_decode_dma_kernel<64, false>), g, blk, 0, st, a, mt);
   if (hipGetLastError() != hipSuccess) return 7;
   *fused_step = 1;
   return 0;

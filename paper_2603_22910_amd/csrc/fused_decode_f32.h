@@ -28,6 +28,8 @@ struct Args {
   int32_t D, m, d_out, H_q, G, n_ret_heads;
   float scale;
   int32_t n_col_tiles, n_tiles;
+  const float* rope_cos; const float* rope_sin;     // rotary tables, or null
+  int32_t n_sink, n_recent;                         // uncompressed window (0, 0: none)
 };
 
 struct Smem {
@@ -92,7 +94,7 @@ __device__ __forceinline__ void gemm_pass(floatx16_t (&acc)[4][4], Smem& sm, con
   __syncthreads();
 }
 
-template <int HD>
+template <int HD, bool ROPE>
 __global__ __launch_bounds__(NTHREADS) void fused_decode_f32_kernel(Args a, SeqMeta meta) {
   __shared__ Smem sm;
   const int logical = blockIdx.x;
@@ -109,7 +111,8 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_f32_kernel(Args a, SeqM
   floatx16_t acc[4][4];
   gemm_pass<true>(acc, sm, a, a.xa[0] + row0 * a.D, a.xr[0] + row0 * a.m, a.w[0] + n0, last, n0, tid);
   const int jw0 = j0 + wt * WM;
-  fused::k_epilogue<HD>(acc, sm.e, a.G, wave, lane, jw0, L);
+  fused::k_epilogue<HD, ROPE>(acc, sm.e, a.G, wave, lane, jw0, L,
+                        fused::make_kextra(a.rope_cos, a.rope_sin, a.n_sink, a.n_recent, L));
   gemm_pass<false>(acc, sm, a, a.xa[1] + row0 * a.D, a.xr[1] + row0 * a.m, a.w[1] + n0, last, n0, tid);
   if (jw0 >= L) return;
   fused::v_epilogue<HD>(acc, sm.e, a.G, wave, lane, meta.sbase[b] + jw0 / kSlotTokens, a.H_q,
@@ -123,16 +126,21 @@ inline int launch_fused_decode_f32(int H_q, int H_kv, int d, int m, int d_out, i
                                    const float* va, const float* kr, const float* vr,
                                    const float* wk, const float* wv, const float* q,
                                    float* part_o, float* part_ml, SeqMeta& mt, int* fused_step,
-                                   hipStream_t st) {
+                                   hipStream_t st, const KvExtras& ex = KvExtras()) {
   fused32::Args a;
+  a.rope_cos = ex.rope_cos; a.rope_sin = ex.rope_sin; a.n_sink = ex.n_sink; a.n_recent = ex.n_recent;
   a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk; a.w[1] = wv;
   a.q = q; a.part_o = part_o; a.part_ml = part_ml;
   a.D = H_kv * d; a.m = m; a.d_out = d_out; a.H_q = H_q; a.G = H_q / H_kv;
   a.n_ret_heads = n_ret_heads; a.scale = scale;
   a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;
   a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
-  if (d == 128) hipLaunchKernelGGL((fused32::fused_decode_f32_kernel<128>), dim3(a.n_tiles), dim3(fused::NTHREADS), 0, st, a, mt);
-  else hipLaunchKernelGGL((fused32::fused_decode_f32_kernel<64>), dim3(a.n_tiles), dim3(fused::NTHREADS), 0, st, a, mt);
+  const dim3 g(a.n_tiles), blk(fused::NTHREADS);
+  const bool rope = ex.rope_cos != nullptr;
+  if (d == 128 && rope) hipLaunchKernelGGL((fused32::fused_decode_f32_kernel<128, true>), g, blk, 0, st, a, mt);
+  else if (d == 128) hipLaunchKernelGGL((fused32::fused_decode_f32_kernel<128, false>), g, blk, 0, st, a, mt);
+  else if (rope) hipLaunchKernelGGL((fused32::fused_decode_f32_kernel<64, true>), g, blk, 0, st, a, mt);
+  else hipLaunchKernelGGL((fused32::fused_decode_f32_kernel<64, false>), g, blk, 0, st, a, mt);
   if (hipGetLastError() != hipSuccess) return 7;
   *fused_step = 1;
   return 0;

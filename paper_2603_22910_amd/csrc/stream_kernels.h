@@ -35,6 +35,60 @@ __global__ __launch_bounds__(256) void append_rows_kernel(CopyArgs a, SeqMeta me
   }
 }
 
+// ---------------------------------------------------------------------------
+// Uncompressed window of the target layer (the first n_sink positions and a
+// ring of the n_recent latest, Sec. "Experimental Setup"): position p lives in
+// row p (p < n_sink) or n_sink + (p - n_sink) % n_recent.
+// ---------------------------------------------------------------------------
+struct Window {
+  int32_t n_sink, n_recent;      // n_sink + n_recent == 0: no window
+  __host__ __device__ int rows() const { return n_sink + n_recent; }
+  __host__ __device__ bool on() const { return n_sink + n_recent > 0; }
+  // compressed-cache tokens [lo, hi) of a length-L sequence are NOT in the window
+  __host__ __device__ int lo(int L) const { return on() ? (n_sink < L ? n_sink : L) : 0; }
+  __host__ __device__ int hi(int L) const {
+    if (!on()) return L;
+    const int h = L - n_recent, l = lo(L);
+    return h > l ? h : l;
+  }
+  __host__ __device__ int row_of(int p) const { return p < n_sink ? p : n_sink + (p - n_sink) % n_recent; }
+  // position held by window row w of a length-L sequence, or -1 if the row is empty / stale
+  __host__ __device__ int pos_of(int w, int L) const {
+    if (w < n_sink) return w < L ? w : -1;
+    if (n_recent == 0) return -1;
+    const int t = L - 1 - n_sink, r = w - n_sink;      // ring coordinates of the last token, of the row
+    if (t < 0) return -1;
+    int back = (t - r) % n_recent;
+    if (back < 0) back += n_recent;
+    return t - back >= 0 ? n_sink + t - back : -1;
+  }
+};
+
+// New full-width rows -> window.  meta: start[b] = length BEFORE the append, len[b] = new rows,
+// tbase = prefix sum of new rows.  A new row is written only if it is still inside the window
+// once all of the call's rows are in, so every window row has one writer.  blockIdx.y: K / V.
+struct WinAppendArgs {
+  const char* src[2];
+  char* dst[2];
+  int64_t row_bytes;
+  int32_t rows, seq0;
+  Window win;
+};
+__global__ __launch_bounds__(256) void window_append_kernel(WinAppendArgs a, SeqMeta meta) {
+  const int which = blockIdx.y;
+  const int pieces = (int)(a.row_bytes >> 4);
+  for (int r = blockIdx.x; r < a.rows; r += gridDim.x) {
+    const int b = find_seq(meta.tbase, meta.n, r);
+    const int p = (int)meta.start[b] + (r - meta.tbase[b]);
+    const int L_after = (int)meta.start[b] + meta.len[b];
+    if (p >= a.win.n_sink && p < L_after - a.win.n_recent) continue;
+    const int64_t drow = (int64_t)(a.seq0 + b) * a.win.rows() + a.win.row_of(p);
+    const uint4* s = reinterpret_cast<const uint4*>(a.src[which] + (int64_t)r * a.row_bytes);
+    uint4* d = reinterpret_cast<uint4*>(a.dst[which] + drow * a.row_bytes);
+    for (int i = threadIdx.x; i < pieces; i += blockDim.x) d[i] = s[i];
+  }
+}
+
 // Plain 2-D copy of `rows` rows (used to place the retained dims in front of
 // the predicted ones, Eq. 6).  blockIdx.y selects K or V.
 struct Copy2dArgs {
@@ -193,13 +247,20 @@ struct AttnArgs {
   int64_t ld;
   int32_t col0;             // column of the first head handled
   int32_t head0;            // its KV head index (for the query / output head)
-  int32_t row_mode;         // 0: row = start[b] + j ; 1: sbase[b]*kSlotTokens + j ; 2: j
+  int32_t row_mode;         // 0: row = start[b] + j ; 1: sbase[b]*kSlotTokens + j ; 2: j ;
+                            // 3: window rows, row = (seq0 + b) * win.rows() + j, one chunk per sequence
   const T* q;               // [nseq, H_q, d]
   int32_t H_q, G, d;
   float scale;
   int32_t split_tokens;     // multiple of kSlotTokens
   float* part_o;            // [slots, H_q, d]
   float* part_ml;           // [slots, H_q, 2]
+  // paper-faithful extras: rotary tables [positions, d/2] (null: none) applied to the key rows by
+  // token position; window: modes 0-2 skip the tokens the window holds, mode 3 attends them
+  const float* rope_cos = nullptr; const float* rope_sin = nullptr;
+  Window win = {0, 0};
+  int32_t seq0 = 0;         // mode 3: index of the launch's first sequence in the window buffers
+  int32_t win_slot0 = 0;    // mode 3: partial of sequence b goes to slot win_slot0 + b
 };
 
 template <typename T, int LPR, int GT>
@@ -216,11 +277,16 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs<T> a, SeqMeta 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int rg = wave * RPW + lane / LPR;        // row group in block
   const int li = lane % LPR;                     // lane within row
+  const bool wmode = a.row_mode == 3;
   const int64_t row0 = a.row_mode == 0 ? meta.start[b]
-                     : a.row_mode == 1 ? (int64_t)meta.sbase[b] * kSlotTokens : 0;
+                     : a.row_mode == 1 ? (int64_t)meta.sbase[b] * kSlotTokens
+                     : wmode ? (int64_t)(a.seq0 + b) * a.win.rows() : 0;
   const int col = a.col0 + hl * a.d + li * VEC;
-  const int jbeg = chunk * a.split_tokens;
-  const int jend = min(L, jbeg + a.split_tokens);
+  // tokens of this chunk: the compressed rows outside the window, or all window rows
+  const int jbeg = wmode ? 0 : max(chunk * a.split_tokens, a.win.lo(L));
+  const int jend = wmode ? a.win.rows() : min(a.win.hi(L), chunk * a.split_tokens + a.split_tokens);
+  const bool rope = a.rope_cos != nullptr;
+  const int hc = (li % (LPR / 2)) * VEC;          // this lane's first column in the d/2-wide tables
 
   float qv[GT][VEC];
 #pragma unroll
@@ -239,15 +305,34 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs<T> a, SeqMeta 
   constexpr int UN = 4;
   for (int j = jbeg + rg; j < jend; j += NRG * UN) {
     float kv[UN][VEC], vv[UN][VEC];
+    int pos[UN];
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
       int jj = j + u * NRG; if (jj >= jend) jj = jend - 1;
       load16<T>(a.k + (row0 + jj) * a.ld + col, kv[u]);
       load16<T>(a.v + (row0 + jj) * a.ld + col, vv[u]);
+      pos[u] = wmode ? a.win.pos_of(jj, L) : jj;
+      if (rope) {        // feature i pairs with i + d/2, held by the lane LPR / 2 away
+        const int pr = max(pos[u], 0);
+        float cs[VEC], sn[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) {
+          const float4 c4 = *reinterpret_cast<const float4*>(a.rope_cos + (int64_t)pr * (a.d / 2) + hc + i);
+          const float4 s4 = *reinterpret_cast<const float4*>(a.rope_sin + (int64_t)pr * (a.d / 2) + hc + i);
+          cs[i] = c4.x; cs[i + 1] = c4.y; cs[i + 2] = c4.z; cs[i + 3] = c4.w;
+          sn[i] = s4.x; sn[i + 1] = s4.y; sn[i + 2] = s4.z; sn[i + 3] = s4.w;
+        }
+        const float sgn = (li < LPR / 2) ? -1.f : 1.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+          const float other = __shfl_xor(kv[u][i], LPR / 2, 64);
+          kv[u][i] = fmaf(kv[u][i], cs[i], sgn * other * sn[i]);
+        }
+      }
     }
 #pragma unroll
     for (int u = 0; u < UN; ++u) {
-      const bool live = (j + u * NRG) < jend;
+      const bool live = (j + u * NRG) < jend && pos[u] >= 0;
 #pragma unroll
       for (int g = 0; g < GT; ++g) {
         float s = 0.f;
@@ -289,7 +374,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs<T> a, SeqMeta 
     if (lane == 0) { s_m[wave][g] = M; s_l[wave][g] = l; }
   }
   __syncthreads();
-  const int slot = meta.sbase[b] + chunk * (a.split_tokens / kSlotTokens);
+  const int slot = wmode ? a.win_slot0 + b : meta.sbase[b] + chunk * (a.split_tokens / kSlotTokens);
   for (int idx = threadIdx.x; idx < GT * a.d; idx += 256) {
     const int g = idx / a.d, c = idx % a.d;
     float M = fmaxf(fmaxf(s_m[0][g], s_m[1][g]), fmaxf(s_m[2][g], s_m[3][g]));
@@ -318,22 +403,29 @@ struct MergeArgs {
   int32_t H_q, G, d;
   int32_t n_stream_kv_heads, stream_step, fused_step;
   int64_t out_seq0;         // index of the launch's first sequence in out/lse
+  int32_t win_slot0 = -1;   // >= 0: one more partial per sequence (its window tokens) at slot win_slot0 + b
 };
 
 template <typename TO>
 __global__ __launch_bounds__(256) void merge_kernel(MergeArgs<TO> a, SeqMeta meta) {
   const int h = blockIdx.x, b = blockIdx.y;
   const int step = (h / a.G < a.n_stream_kv_heads) ? a.stream_step : a.fused_step;
-  const int n = (meta.sbase[b + 1] - meta.sbase[b] + step - 1) / step;   // partials of this head
+  const int nreg = (meta.sbase[b + 1] - meta.sbase[b] + step - 1) / step;   // regular partials of this head
+  const int n = nreg + (a.win_slot0 >= 0 ? 1 : 0);
   const int64_t slot0 = meta.sbase[b];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // partial i of this (sequence, head): its row in part_o / part_ml
+  auto ph_of = [&](int i) -> int64_t {
+    const int64_t slot = i < nreg ? slot0 + (int64_t)i * step : (int64_t)a.win_slot0 + b;
+    return slot * a.H_q + h;
+  };
   __shared__ float s_red[4];
   __shared__ float s_w[256];
   __shared__ float s_acc[8][128];
-  // 1. global max of the partial maxima (all partials' maxima are finite)
+  // 1. global max of the partial maxima (a partial that covers no token has -inf and weight 0;
+  //    at least one partial of every sequence covers a token)
   float M = -INFINITY;
-  for (int i = tid; i < n; i += 256)
-    M = fmaxf(M, a.part_ml[((slot0 + (int64_t)i * step) * a.H_q + h) * 2]);
+  for (int i = tid; i < n; i += 256) M = fmaxf(M, a.part_ml[ph_of(i) * 2]);
   M = wave_max(M, 64);
   if (lane == 0) s_red[wave] = M;
   __syncthreads();
@@ -349,7 +441,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs<TO> a, SeqMeta met
     const int i = c0 + tid;
     float w = 0.f;
     if (i < n) {
-      const int64_t ph = (slot0 + (int64_t)i * step) * a.H_q + h;
+      const int64_t ph = ph_of(i);
       w = __expf(a.part_ml[ph * 2] - M);
       lsum += w * a.part_ml[ph * 2 + 1];
     }
@@ -360,8 +452,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs<TO> a, SeqMeta met
     if (dim_ok) {
 #pragma unroll 4
       for (int j = grp; j < cn; j += 8) {
-        const int64_t ph = (slot0 + (int64_t)(c0 + j) * step) * a.H_q + h;
-        const float4 o = *reinterpret_cast<const float4*>(a.part_o + ph * a.d + q4);
+        const float4 o = *reinterpret_cast<const float4*>(a.part_o + ph_of(c0 + j) * a.d + q4);
         const float wj = s_w[j];
         acc.x = fmaf(wj, o.x, acc.x); acc.y = fmaf(wj, o.y, acc.y);
         acc.z = fmaf(wj, o.z, acc.z); acc.w = fmaf(wj, o.w, acc.w);

@@ -72,6 +72,18 @@ class DeviceWorkload:
                        self.lse, self.workspace, stream)
         return self.out, self.lse
 
+    def decode_ex(self, rope=None, window=None, stream=None):
+        """rope = (cos, sin) host or device fp32 tables; window = (win_k, win_v, n_sink, n_recent)."""
+        if rope is not None:
+            rope = tuple(t.to(self.dev).contiguous() for t in rope)
+        if window is not None:
+            window = (window[0].to(self.dev).contiguous(), window[1].to(self.dev).contiguous(),
+                      window[2], window[3])
+        self._keep = (rope, window)          # keep the device copies alive until the stream is done
+        ek.decode_attn_ex(self.shape, self.anchor, self.target, self.W_K, self.W_V, self.q, self.out,
+                          self.lse, self.workspace, rope, window, stream)
+        return self.out, self.lse
+
     def prefill(self, stream=None):
         saved = self.shape.flags
         self.shape.flags = saved & ~ek.FLAG_W_PACKED      # prefill takes row-major weights

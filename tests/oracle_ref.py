@@ -54,3 +54,19 @@ def decode_head_ref(inp, b, h, scale=None):
     w = inp.w
     return orc.echokv_decode_head(f64(inp.q[b, h]), K_a, V_a, K_r, V_r, W_K, W_V,
                                   h // w.group, w.head_dim, scale)
+
+
+def decode_paper_ref(inp, rope=None, window=None, seqs=None, scale=None):
+    """Paper-faithful decode: rope = (cos, sin) torch fp32 tables; window =
+    (win_k, win_v, n_sink, n_recent) with torch [n_decode, rows, D] buffers."""
+    seqs = range(inp.n_decode) if seqs is None else seqs
+    W_K, W_V = weights(inp)
+    r = None if rope is None else (f64(rope[0]), f64(rope[1]))
+    outs, lses = [], []
+    for b in seqs:
+        K_a, V_a, K_r, V_r = seq_arrays(inp, b)
+        wnd = None if window is None else (f64(window[0][b]), f64(window[1][b]), window[2], window[3])
+        o, l = orc.echokv_decode_paper(f64(inp.q[b]), K_a, V_a, K_r, V_r, W_K, W_V,
+                                       inp.w.n_kv_heads, scale, rope=r, window=wnd)
+        outs.append(o); lses.append(l)
+    return np.stack(outs), np.stack(lses)

@@ -172,3 +172,46 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(ek, "LIB_PATH", str(tmp_path / "libechokv.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         ek.load()
+
+
+class _Tbl:
+    """Device-table stand-in: fake pointer, claimed number of rows."""
+    def __init__(self, rows, ptr=FAKE):
+        self.shape = (rows, 32); self._p = ptr
+    def data_ptr(self): return self._p
+
+
+def test_decode_extras_argument_errors(lib):
+    sh = ek.make_shape(8, 8, 64, 256, "f32")
+    a, t = caches(lens=(100,))
+    big = _Ws(1 << 30)
+    base = (sh, a, t, FAKE, FAKE, FAKE, FAKE, None, big)
+    # tables shorter than the longest sequence
+    assert code(ek.decode_attn_ex, *base, rope=(_Tbl(99), _Tbl(99)), stream=0) == ek.ERR_SHAPE
+    # one table / one window buffer missing
+    half = ek.DecodeExtras(); half.rope_cos = FAKE; half.rope_positions = 200
+    a_c, t_c = a.as_c(), t.as_c()
+    import ctypes as C
+    def raw(ex):
+        return lib.echokv_decode_attn_ex(C.byref(sh), C.byref(a_c), C.byref(t_c), FAKE, FAKE, FAKE,
+                                         C.byref(ex), FAKE, None, FAKE, 1 << 30, None)
+    assert raw(half) == ek.ERR_NULL
+    halfw = ek.DecodeExtras(); halfw.win_k = FAKE; halfw.n_sink = 4; halfw.n_recent = 128
+    assert raw(halfw) == ek.ERR_NULL
+    # window sizes
+    assert code(ek.decode_attn_ex, *base, window=(_Tbl(1), _Tbl(1), -1, 128), stream=0) == ek.ERR_SHAPE
+    assert code(ek.decode_attn_ex, *base, window=(_Tbl(1), _Tbl(1), 0, 0), stream=0) == ek.ERR_SHAPE
+    # the absorbed mode cannot take a rotation between reconstruction and the dot product
+    shb = ek.make_shape(8, 8, 64, 256, "bf16", flags=ek.FLAG_ABSORBED)
+    assert code(ek.decode_attn_ex, shb, a, t, FAKE, FAKE, FAKE, FAKE, None, big,
+                rope=(_Tbl(200), _Tbl(200)), stream=0) == ek.ERR_UNSUPPORTED
+
+
+def test_window_append_argument_errors(lib):
+    sh = ek.make_shape(8, 8, 64, 256, "f32")
+    assert code(ek.window_append, sh, None, FAKE, 4, 128, [5], FAKE, FAKE, [1], stream=0) == ek.ERR_NULL
+    assert code(ek.window_append, sh, FAKE, FAKE, 0, 0, [5], FAKE, FAKE, [1], stream=0) == ek.ERR_SHAPE
+    assert code(ek.window_append, sh, FAKE, FAKE, 4, 128, [-1], FAKE, FAKE, [1], stream=0) == ek.ERR_SHAPE
+    assert code(ek.window_append, sh, FAKE, FAKE, 4, 128, [5], FAKE, FAKE, [-2], stream=0) == ek.ERR_SHAPE
+    assert code(ek.window_append, sh, FAKE, FAKE, 4, 128, [5], None, FAKE, [1], stream=0) == ek.ERR_NULL
+    assert code(ek.window_append, sh, FAKE, FAKE, 4, 128, [5, 6], None, None, [0, 0], stream=0) == ek.OK
