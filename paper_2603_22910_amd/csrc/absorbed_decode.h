@@ -153,11 +153,13 @@ struct ScoreIo {
   rsrc_t ru;
   uint32_t D2, m2, u2;
   int D, m, nsa, ns, last;
+  int rot;        // stage visited first: workgroups that run side by side read different columns
 };
 
 struct StageDesc { bool anchor; int k0, kw, kg0; };
 __device__ __forceinline__ StageDesc stage_desc(const ScoreIo& io, int t) {
-  t = min(t, io.ns - 1);
+  t = min(t, io.ns - 1) + io.rot;
+  if (t >= io.ns) t -= io.ns;
   StageDesc d;
   d.anchor = t < io.nsa;
   d.k0 = (d.anchor ? t : t - io.nsa) * kStageK;
@@ -251,6 +253,7 @@ __global__ __launch_bounds__(256, NST == 2 ? 2 : 1) void scores_kernel(Args a, S
   io.D = a.D; io.m = a.m;
   io.nsa = (a.D + kStageK - 1) / kStageK; io.ns = io.nsa + (a.m + kStageK - 1) / kStageK;
   io.last = min(kTokTile, L - j0) - 1;
+  io.rot = (slot * 5) % io.ns;
   const bool head_ok = hb * kHB + lr < a.H_q;    // rows of U past the last head hold nothing: count as zero
 
   floatx16_t acc;

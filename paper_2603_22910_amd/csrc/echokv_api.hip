@@ -463,9 +463,13 @@ struct AbsPlan {
   int H_pad, n_col_a, n_col_tiles, k_slices, k_slice;
 };
 inline int abs_col_tiles(int width) { return (width + absorbed::kColTile - 1) / absorbed::kColTile; }
-// tokens per split of the value pass: enough workgroups to fill the chip, few partial sums
-int abs_split_tokens(const Dims& dm, int64_t tokens) {
+// Tokens per split of the value pass: enough workgroups (one per split and column tile) to fill the
+// chip a few times over, few partial sums.  Measured: halving the split below this rule costs more
+// in partial-sum traffic (64 fp32 head rows per split against TS bf16 token rows) than it gains.
+int abs_split_tokens(const Dims& dm, const echokv_layer_cache* an, int b0, int n) {
   const int nct = abs_col_tiles(dm.D) + abs_col_tiles(dm.m);
+  int64_t tokens = 0;
+  for (int b = 0; b < n; ++b) tokens += an->seq_len[b0 + b];
   int ts = 1024;
   while ((tokens / ts) * nct > 2048 && ts < 32768) ts <<= 1;
   return ts;
@@ -506,7 +510,7 @@ int absorbed_group(const Dims& dm, const echokv_layer_cache* an, int b0, SeqMeta
     mt.start[b] = an->seq_start[b0 + b]; mt.len[b] = an->seq_len[b0 + b]; tokens += mt.len[b];
   }
   *slots = fill_slots(mt);
-  *split_tokens = abs_split_tokens(dm, tokens);
+  *split_tokens = abs_split_tokens(dm, an, b0, mt.n);
   *splits = fill_tiles(mt, *split_tokens);
   // 32-bit byte offsets inside the score matrix
   if ((int64_t)*slots * kSlotTokens * 4 * absorbed::kHB >= (int64_t)1 << 31) return ECHOKV_ERR_UNSUPPORTED;
