@@ -29,6 +29,9 @@ Readings taken where the paper is silent (each also listed in the design notes):
     target layer are kept uncompressed (Sec. "Experimental Setup").  The
     pairing of rotated features (i with i + d/2) and the ring placement of the
     latest tokens are this build's readings: the paper fixes neither;
+  * the one-hidden-layer predictor of Appendix "Prediction Network Architecture"
+    is read as C_hat = act([C_global ; C_local] W1) W2, bias-free like the
+    linear one, act = ReLU or SiLU (the paper names no activation);
   * a prefill query at chunk offset i attends cached tokens 0 .. q_pos0 + i,
     all of them taken from the compressed cache (reconstructed where dropped).
 
@@ -420,3 +423,48 @@ def brute_force_decode_paper(q, K_a, V_a, K_r, V_r, W_K, W_V, n_kv_heads: int,
             out[h][i] = acc
         lse[h] = mx + math.log(z)
     return np.array(out, F64), np.array(lse, F64)
+
+
+# --------------------------------------------------------------------------
+# one-hidden-layer predictor (Appendix "Prediction Network Architecture":
+# a parameter-matched hidden width, or hidden width = predictor input width)
+# --------------------------------------------------------------------------
+def activation(x: np.ndarray, kind: str) -> np.ndarray:
+    x = np.asarray(x, F64)
+    if kind == "relu":
+        return np.maximum(x, 0.0)
+    if kind == "silu":
+        return x / (1.0 + np.exp(-x))
+    raise ValueError(f"unknown activation {kind!r}")
+
+
+def reconstruct_mlp(C_anchor, C_local, W1, W2, act: str = "relu") -> np.ndarray:
+    """C_tilde [L, D] = [C_local ; act([C_anchor ; C_local] W1) W2], retained dims
+    first (Eq. 3 with the linear map replaced by the two-layer one, Eq. 6).
+    W1 [D + m, hidden], W2 [hidden, D - m]."""
+    C_local = np.asarray(C_local, F64)
+    D = C_anchor.shape[1]
+    m = C_local.shape[1]
+    W1 = np.asarray(W1, F64); W2 = np.asarray(W2, F64)
+    if W1.shape[0] != D + m or W2.shape != (W1.shape[1], D - m):
+        raise ValueError("need W1 [D + m, hidden] and W2 [hidden, D - m]")
+    H = activation(predictor_input(C_anchor, C_local) @ W1, act)
+    return np.concatenate([C_local, H @ W2], axis=1)
+
+
+def echokv_decode_mlp(q, K_a, V_a, K_r, V_r, W1_K, W2_K, W1_V, W2_V, n_kv_heads: int,
+                      act: str = "relu", scale: Optional[float] = None):
+    """Decode over one sequence with the one-hidden-layer predictor.
+    Returns (out [H_q, d], lse [H_q])."""
+    K_t = reconstruct_mlp(K_a, K_r, W1_K, W2_K, act)
+    V_t = reconstruct_mlp(V_a, V_r, W1_V, W2_V, act)
+    o, lse, _ = attention_rows(np.asarray(q, F64)[None], K_t, V_t, n_kv_heads, scale)
+    return o[0], lse[0]
+
+
+def mlp_param_matched_hidden(D: int, m: int, multiple: int = 64) -> int:
+    """Hidden width that keeps the two-layer predictor's parameter count closest to
+    the linear one's: hidden * (d_in + d_out) ~ d_in * d_out, rounded to `multiple`."""
+    d_in, d_out = predictor_dims(D, m)
+    h = d_in * d_out / (d_in + d_out)
+    return max(multiple, int(round(h / multiple)) * multiple)

@@ -624,3 +624,80 @@ def test_synthetic_window_rows_agree_with_the_compressed_cache():
                 assert torch.equal(wk[b, r, :64], inp.K_r[inp.seq_start[b] + p])
                 assert torch.equal(wv[b, r, :64], inp.V_r[inp.seq_start[b] + p])
                 assert float(wk[b, r, 64:].abs().sum()) > 0
+
+
+# ---- P15: one-hidden-layer predictor ---------------------------------------------
+def test_activations_against_library_and_closed_forms():
+    x = np.linspace(-6, 6, 41)
+    np.testing.assert_allclose(orc.activation(x, "silu"),
+                               torch.nn.functional.silu(torch.from_numpy(x)).numpy(), rtol=1e-13, atol=1e-15)
+    np.testing.assert_array_equal(orc.activation(x, "relu"),
+                                  torch.nn.functional.relu(torch.from_numpy(x)).numpy())
+    assert orc.activation(np.array([0.0]), "silu")[0] == 0.0
+    assert abs(orc.activation(np.array([1.0]), "silu")[0] - 1.0 / (1.0 + math.exp(-1.0))) < 1e-15
+    with pytest.raises(ValueError):
+        orc.activation(x, "tanh")
+
+
+def test_mlp_with_identity_first_layer_on_nonnegative_inputs_is_the_linear_predictor():
+    c, Q = make_case(4, 2, 8, 8, 21, seed=12)
+    for k in ("K_a", "V_a", "K_r", "V_r"):
+        c[k] = np.abs(c[k])                              # ReLU(x I) = x
+    d_in = 16 + 8
+    I = np.eye(d_in)
+    o_lin, l_lin = orc.echokv_decode(Q[0], **c, n_kv_heads=2)
+    o_mlp, l_mlp = orc.echokv_decode_mlp(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"], I, c["W_K"], I,
+                                         c["W_V"], 2, act="relu")
+    np.testing.assert_allclose(o_mlp, o_lin, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(l_mlp, l_lin, rtol=1e-12, atol=1e-13)
+    # a first layer of -I switches every hidden unit off: the rebuilt heads are zero
+    K_t = orc.reconstruct_mlp(c["K_a"], c["K_r"], -I, c["W_K"], "relu")
+    assert np.array_equal(K_t[:, :8], c["K_r"]) and np.all(K_t[:, 8:] == 0.0)
+
+
+def test_mlp_activation_sits_between_the_layers():
+    # hidden unit u = relu(x0 - x1); output = 3 u: checks order (act after W1, before W2) and sign
+    C_a = np.array([[2.0, 0.5], [0.5, 2.0]]); C_r = np.zeros((2, 0))
+    W1 = np.array([[1.0], [-1.0]]); W2 = np.array([[3.0, -1.0]])
+    out = orc.reconstruct_mlp(C_a, C_r, W1, W2, "relu")
+    np.testing.assert_array_equal(out, [[4.5, -1.5], [0.0, 0.0]])
+    out = orc.reconstruct_mlp(C_a, C_r, W1, W2, "silu")
+    s = lambda v: v / (1 + math.exp(-v))
+    np.testing.assert_allclose(out, [[3 * s(1.5), -s(1.5)], [3 * s(-1.5), -s(-1.5)]], rtol=1e-14)
+
+
+def test_mlp_brute_force_scalar_loops():
+    c, Q = make_case(2, 2, 4, 4, 7, seed=15)
+    r = np.random.default_rng(4)
+    hid = 5
+    W1k, W1v = r.standard_normal((12, hid)), r.standard_normal((12, hid))
+    W2k, W2v = r.standard_normal((hid, 4)), r.standard_normal((hid, 4))
+    for act in ("relu", "silu"):
+        o, l = orc.echokv_decode_mlp(Q[0], c["K_a"], c["V_a"], c["K_r"], c["V_r"], W1k, W2k, W1v, W2v, 2, act)
+        f = (lambda v: max(v, 0.0)) if act == "relu" else (lambda v: v / (1.0 + math.exp(-v)))
+        def rebuilt(C_a, C_r, W1, W2, j, col):
+            if col < 4:
+                return C_r[j][col]
+            acc = 0.0
+            for u in range(hid):
+                pre = 0.0
+                for k in range(12):
+                    pre += (C_a[j][k] if k < 8 else C_r[j][k - 8]) * W1[k][u]
+                acc += f(pre) * W2[u][col - 4]
+            return acc
+        for h in range(2):
+            s = [sum(Q[0][h][i] * rebuilt(c["K_a"], c["K_r"], W1k, W2k, j, h * 4 + i) for i in range(4)) / 2.0
+                 for j in range(7)]
+            mx = max(s); e = [math.exp(v - mx) for v in s]; z = sum(e)
+            for i in range(4):
+                want = sum(e[j] / z * rebuilt(c["V_a"], c["V_r"], W1v, W2v, j, h * 4 + i) for j in range(7))
+                assert abs(o[h][i] - want) < 1e-12
+            assert abs(l[h] - (mx + math.log(z))) < 1e-12
+
+
+def test_mlp_param_matched_width():
+    # Llama-3.1-8B layout at ratio 0.5 (S = 2, m = 0): linear 1024 x 1024; matched hidden = 512
+    assert orc.mlp_param_matched_hidden(1024, 0) == 512
+    h = orc.mlp_param_matched_hidden(4096, 2048)
+    d_in, d_out = 6144, 2048
+    assert h % 64 == 0 and abs(h * (d_in + d_out) - d_in * d_out) <= 32 * (d_in + d_out)
