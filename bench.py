@@ -83,6 +83,9 @@ def main():
     ap.add_argument("--rope-window", action="store_true",
                     help="time the paper-faithful decode instead: rotary embedding applied to the "
                          "rebuilt keys and 4 sink + 128 recent tokens attended uncompressed")
+    ap.add_argument("--mlp-hidden", type=int, default=0,
+                    help="time decode with the one-hidden-layer predictor of this hidden width (ReLU) "
+                         "instead of the linear one")
     ap.add_argument("--no-absorbed", action="store_true",
                     help="skip the extra timing of the weight-absorbed mode after the headline run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -106,7 +109,8 @@ def main():
     # the default run also times the weight-absorbed mode afterwards (reported beside the
     # headline, never as `value`): size the workspace for both
     also_absorbed = (not args.unfused and not args.absorbed and not args.packed_weights
-                     and w.dtype == "bf16" and not args.no_absorbed and not args.rope_window)
+                     and w.dtype == "bf16" and not args.no_absorbed and not args.rope_window
+                     and not args.mlp_hidden)
     dw = DeviceWorkload(inp, flags=flags | (ek.FLAG_ABSORBED if also_absorbed else 0))
     dw.set_flags(flags)
     if args.packed_weights:
@@ -134,6 +138,10 @@ def main():
         wk, wv = synth.window_rows(inp, 4, 128)
         extras = (rope, (wk.to(dev), wv.to(dev), 4, 128))
 
+    mlp = None
+    if args.mlp_hidden:
+        mlp = tuple(t.to(dev) for t in synth.mlp_weights(w, args.mlp_hidden))
+
     has_prefill = inp.q_prefill is not None
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
 
@@ -142,7 +150,9 @@ def main():
         ek.cache_append(dw.shape, dw.anchor, ka_new, va_new, ones)
         dw.target.seq_len[:] = full_len - 1
         ek.cache_append(dw.shape, dw.target, kt_new, vt_new, ones)
-        if extras is None:
+        if mlp is not None:
+            dw.decode_mlp(mlp, args.mlp_hidden, ek.ACT_RELU)
+        elif extras is None:
             dw.decode()
         else:
             dw.decode_ex(*extras)
@@ -188,6 +198,8 @@ def main():
     # algorithmic work = 4 * d_in * d_out flop per cached token (K and V products)
     dec_tokens = inp.total_decode_tokens
     flops = 4.0 * w.d_in * w.d_out * dec_tokens
+    if args.mlp_hidden:      # two layers, for keys and for values
+        flops = 4.0 * args.mlp_hidden * (w.d_in + w.d_out) * dec_tokens
     bytes_alg = dec_tokens * 2.0 * w.d_in * w.elem_size + 2.0 * w.d_in * w.d_out * w.elem_size
     def absorbed_roofline(kern_ms, launches):
         # the absorbed path's kernels together read every cache row and both weight matrices once
@@ -205,7 +217,9 @@ def main():
         k_s = kern_ms / launches * 1e-3
         ach = flops / k_s / 1e12
         peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
-        roofline = {"bound": "mfma", "kernel": "fused_decode_kernel", "achieved": ach,
+        roofline = {"bound": "mfma",
+                    "kernel": "recon_mfma_kernel + fused_decode_kernel" if args.mlp_hidden else "fused_decode_kernel",
+                    "achieved": ach,
                     "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
                     "traffic": read_traffic(w.name), "kernel_ms": k_s * 1e3,
                     "algorithmic_flop": flops, "algorithmic_bytes": bytes_alg,
@@ -221,6 +235,7 @@ def main():
                    "n_retained": w.n_retained, "d_in": w.d_in, "d_out": w.d_out,
                    "path": "unfused" if args.unfused else "absorbed" if args.absorbed else "fused",
                    "extras": "rope + 4 sink + 128 recent window" if args.rope_window else None,
+                   "predictor": f"one hidden layer of {args.mlp_hidden}, ReLU" if args.mlp_hidden else "linear",
                    "weights": "packed [d_out,d_in]" if args.packed_weights else "row-major [d_in,d_out]",
                    "step": "cache_append(anchor)+cache_append(target)+decode_attn"
                            + ("+prefill_attn" if has_prefill else ""),

@@ -212,6 +212,31 @@ int echokv_window_append(const echokv_shape *shape, void *win_k, void *win_v,
                          const int32_t *seq_len_before, const void *k_new,
                          const void *v_new, const int32_t *n_new, void *hip_stream);
 
+/* Decode with the one-hidden-layer predictor of Appendix "Prediction Network
+ * Architecture" in place of the linear one:
+ *   C_hat = act([C_global ; C_local] W1) W2        (Eq. 3 with two layers, bias-free)
+ * for keys (w1_k, w2_k) and values (w1_v, w2_v); everything else as
+ * echokv_decode_attn.  The paper evaluates a parameter-matched hidden width and
+ * hidden = D + m; it names no activation: ECHOKV_ACT_RELU and ECHOKV_ACT_SILU
+ * are offered.
+ *   w1_* : device [D + m, hidden] row-major;  w2_* : device [hidden, D - m] row-major
+ *   hidden : multiple of 64
+ * bf16 caches only, m a multiple of the head dim, shape->flags == 0; otherwise
+ * ECHOKV_ERR_UNSUPPORTED.  The hidden activations are rounded to bf16 between
+ * the layers (they are the second layer's MFMA operand).  Workspace:
+ * echokv_mlp_workspace_bytes (it holds the hidden activations of all cached
+ * tokens, 2 * hidden * 2 bytes per token, and the split partials). */
+#define ECHOKV_ACT_RELU 1
+#define ECHOKV_ACT_SILU 2
+size_t echokv_mlp_workspace_bytes(const echokv_shape *shape, int32_t batch,
+                                  int64_t total_tokens, int32_t hidden);
+int echokv_decode_attn_mlp(const echokv_shape *shape, const echokv_layer_cache *anchor,
+                           const echokv_layer_cache *target, const void *w1_k,
+                           const void *w2_k, const void *w1_v, const void *w2_v,
+                           int32_t hidden, int32_t activation, const void *q, void *out,
+                           float *lse_out, void *workspace, size_t workspace_bytes,
+                           void *hip_stream);
+
 /* Causal chunk of T_q queries of sequence `seq` (Eq. 7 with a causal mask):
  * query i sits at position q_pos0 + i and attends cached tokens
  * 0 .. q_pos0 + i inclusive, all read from the compressed cache (predicted

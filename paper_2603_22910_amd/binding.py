@@ -25,7 +25,9 @@ FLAG_ABSORBED = 8
 EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn",
            "echokv_profile_enable", "echokv_profile_read", "echokv_pack_weights",
-           "echokv_cache_compress", "echokv_decode_attn_ex", "echokv_window_append")
+           "echokv_cache_compress", "echokv_decode_attn_ex", "echokv_window_append",
+           "echokv_mlp_workspace_bytes", "echokv_decode_attn_mlp")
+ACT_RELU, ACT_SILU = 1, 2
 
 
 class EchoKVError(RuntimeError):
@@ -83,6 +85,13 @@ def load() -> C.CDLL:
                                           C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.POINTER(DecodeExtras), C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_size_t, C.c_void_p]
+    lib.echokv_mlp_workspace_bytes.restype = C.c_size_t
+    lib.echokv_mlp_workspace_bytes.argtypes = [C.POINTER(Shape), C.c_int32, C.c_int64, C.c_int32]
+    lib.echokv_decode_attn_mlp.restype = C.c_int
+    lib.echokv_decode_attn_mlp.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
+                                           C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.echokv_window_append.restype = C.c_int
     lib.echokv_window_append.argtypes = [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_void_p,
@@ -225,6 +234,20 @@ def decode_attn_ex(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_
                                         _ptr(q), C.byref(ex), _ptr(out), _ptr(lse_out),
                                         _ptr(workspace), nbytes, _stream(stream)),
            "echokv_decode_attn_ex")
+
+
+def mlp_workspace_bytes(shape: Shape, batch: int, total_tokens: int, hidden: int) -> int:
+    return int(load().echokv_mlp_workspace_bytes(C.byref(shape), int(batch), int(total_tokens), int(hidden)))
+
+
+def decode_attn_mlp(shape: Shape, anchor: LayerCache, target: LayerCache, w1_k, w2_k, w1_v, w2_v,
+                    hidden: int, activation: int, q, out, lse_out, workspace, stream=None):
+    a, t = anchor.as_c(), target.as_c()
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().echokv_decode_attn_mlp(C.byref(shape), C.byref(a), C.byref(t), _ptr(w1_k), _ptr(w2_k),
+                                         _ptr(w1_v), _ptr(w2_v), int(hidden), int(activation), _ptr(q),
+                                         _ptr(out), _ptr(lse_out), _ptr(workspace), nbytes,
+                                         _stream(stream)), "echokv_decode_attn_mlp")
 
 
 def window_append(shape: Shape, win_k, win_v, n_sink: int, n_recent: int, seq_len_before, k_new,

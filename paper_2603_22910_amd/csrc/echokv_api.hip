@@ -457,6 +457,88 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
   return ECHOKV_OK;
 }
 
+// ---- one-hidden-layer predictor (Appendix "Prediction Network Architecture") ----------------
+// H = act([anchor ; retained] W1) is written to the workspace in bf16 by the MFMA predictor-product
+// kernel (activation in its store epilogue); the fused decode kernel then runs on H as its only
+// input matrix with W2 as the weights.  Retained heads and the merge are unchanged.
+struct MlpPlan { size_t off_po, off_pml, off_hk, off_hv, total; };
+MlpPlan plan_mlp(const Dims& dm, int64_t slots, int hidden) {
+  MlpPlan p;
+  size_t o = 0;
+  p.off_po = o;  o += align_up((size_t)slots * dm.H_q * dm.d * 4);
+  p.off_pml = o; o += align_up((size_t)slots * dm.H_q * 2 * 4);
+  p.off_hk = o;  o += align_up((size_t)slots * kSlotTokens * hidden * 2);
+  p.off_hv = o;  o += align_up((size_t)slots * kSlotTokens * hidden * 2);
+  p.total = o;
+  return p;
+}
+int check_mlp(const Dims& dm, uint32_t flags, int hidden, int act) {
+  if (!dm.bf16 || dm.r != 0 || flags != 0) return ECHOKV_ERR_UNSUPPORTED;
+  if (!fused_decode_supported<bf16_t>(dm.d, dm.G)) return ECHOKV_ERR_UNSUPPORTED;
+  if (hidden < 64 || hidden % 64 || hidden > (1 << 20)) return ECHOKV_ERR_SHAPE;
+  if (act != ECHOKV_ACT_RELU && act != ECHOKV_ACT_SILU) return ECHOKV_ERR_SHAPE;
+  return ECHOKV_OK;
+}
+
+int mlp_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_layer_cache* tg,
+             const bf16_t* w1k, const bf16_t* w2k, const bf16_t* w1v, const bf16_t* w2v, int hidden,
+             int act, const bf16_t* q, void* out, float* lse, char* ws, hipStream_t st) {
+  typedef bf16_t T;
+  const int n_ret_heads = dm.g0, n_rec_heads = dm.H_kv - n_ret_heads;
+  for (int b0 = 0; b0 < an->batch; b0 += kMaxSeqPerLaunch) {
+    SeqMeta mt;
+    mt.n = std::min(kMaxSeqPerLaunch, an->batch - b0);
+    int64_t tokens = 0;
+    for (int b = 0; b < mt.n; ++b) {
+      mt.start[b] = an->seq_start[b0 + b]; mt.len[b] = an->seq_len[b0 + b]; tokens += mt.len[b];
+    }
+    const int slots = fill_slots(mt);
+    const MlpPlan wp = plan_mlp(dm, slots, hidden);
+    float* po = (float*)(ws + wp.off_po);
+    float* pml = (float*)(ws + wp.off_pml);
+    const T* qq = q + (int64_t)b0 * dm.H_q * dm.d;
+    int stream_step = 1, fused_step = 1;
+    if (n_ret_heads > 0) {
+      AttnArgs<T> a;
+      a.k = (const T*)tg->k; a.v = (const T*)tg->v; a.ld = dm.m; a.col0 = 0; a.head0 = 0;
+      a.row_mode = 0; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
+      a.split_tokens = pick_split_tokens(tokens, n_ret_heads);
+      a.part_o = po; a.part_ml = pml;
+      stream_step = a.split_tokens / kSlotTokens;
+      int rc = launch_attn_split<T>(dm, a, mt, n_ret_heads, st);
+      if (rc) return rc;
+    }
+    if (n_rec_heads > 0) {
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      if (g_prof.on) {
+        if (!g_prof.get(&e0) || !g_prof.get(&e1)) return ECHOKV_ERR_HIP;
+        HIP_TRY(hipEventRecord(e0, st));
+      }
+      T* hk = (T*)(ws + wp.off_hk);
+      T* hv = (T*)(ws + wp.off_hv);
+      int rc = launch_recon_mfma<T>(dm.D, dm.m, hidden, (const T*)an->k, (const T*)an->v,
+                                    (const T*)tg->k, (const T*)tg->v, w1k, w1v, hk, hv, hidden, 0,
+                                    mt, st, act);
+      if (rc) return rc;
+      SeqMeta hm = mt;                       // H rows of sequence b start at its first slot
+      for (int b = 0; b < hm.n; ++b) hm.start[b] = (int64_t)mt.sbase[b] * kSlotTokens;
+      rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, 0, dm.d_out, dm.g0, dm.scale, hk, hv,
+                                  (const T*)nullptr, (const T*)nullptr, w2k, w2v, qq, po, pml, hm,
+                                  &fused_step, st, false, KvExtras(), hidden);
+      if (g_prof.on) {
+        HIP_TRY(hipEventRecord(e1, st));
+        g_prof.pairs.emplace_back(e0, e1);
+      }
+      if (rc) return rc;
+    }
+    int rc = dm.out_bf16
+        ? merge_launch<T, bf16_t>(dm, po, pml, out, lse, b0, n_ret_heads, stream_step, fused_step, -1, mt, st)
+        : merge_launch<T, float>(dm, po, pml, out, lse, b0, n_ret_heads, stream_step, fused_step, -1, mt, st);
+    if (rc) return rc;
+  }
+  return ECHOKV_OK;
+}
+
 // ---- weight-absorbed decode: workspace plan and launches ------------------
 struct AbsPlan {
   size_t off_u, off_s, off_ml, off_yp, off_y, off_op, total;
@@ -864,6 +946,45 @@ int echokv_window_append(const echokv_shape* shape, void* win_k, void* win_v, in
     src_row += rows;
   }
   return ECHOKV_OK;
+}
+
+size_t echokv_mlp_workspace_bytes(const echokv_shape* shape, int32_t batch, int64_t total_tokens,
+                                  int32_t hidden) {
+  Dims dm;
+  if (check_shape(shape, &dm) != ECHOKV_OK || batch <= 0 || total_tokens <= 0) return 0;
+  if (check_mlp(dm, shape->flags, hidden, ECHOKV_ACT_RELU) != ECHOKV_OK) return 0;
+  return plan_mlp(dm, total_tokens / kSlotTokens + batch, hidden).total;
+}
+
+int echokv_decode_attn_mlp(const echokv_shape* shape, const echokv_layer_cache* anchor,
+                           const echokv_layer_cache* target, const void* w1_k, const void* w2_k,
+                           const void* w1_v, const void* w2_v, int32_t hidden, int32_t activation,
+                           const void* q, void* out, float* lse_out, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  Dims dm;
+  int rc = check_shape(shape, &dm);
+  if (rc) return rc;
+  rc = check_pair(dm, anchor, target);
+  if (rc) return rc;
+  rc = check_mlp(dm, shape->flags, hidden, activation);
+  if (rc) return rc;
+  if (dm.d_out > 0 && (!w1_k || !w2_k || !w1_v || !w2_v)) return ECHOKV_ERR_NULL;
+  if (!q || !out) return ECHOKV_ERR_NULL;
+  int64_t max_chunk_slots = 0;
+  for (int b0 = 0; b0 < anchor->batch; b0 += kMaxSeqPerLaunch) {
+    int64_t s = 0;
+    for (int b = b0; b < std::min(anchor->batch, b0 + kMaxSeqPerLaunch); ++b) {
+      if (anchor->seq_len[b] < 1) return ECHOKV_ERR_SHAPE;
+      s += slots_for(anchor->seq_len[b]);
+    }
+    max_chunk_slots = std::max(max_chunk_slots, s);
+  }
+  const size_t need = plan_mlp(dm, max_chunk_slots, hidden).total;
+  if (!workspace || workspace_bytes < need) return ECHOKV_ERR_WORKSPACE;
+  if ((uintptr_t)workspace % 256) return ECHOKV_ERR_WORKSPACE;
+  return mlp_impl(dm, anchor, target, (const bf16_t*)w1_k, (const bf16_t*)w2_k, (const bf16_t*)w1_v,
+                  (const bf16_t*)w2_v, hidden, activation, (const bf16_t*)q, out, lse_out,
+                  (char*)workspace, (hipStream_t)hip_stream);
 }
 
 int echokv_prefill_attn(const echokv_shape* shape, const echokv_layer_cache* anchor,

@@ -702,7 +702,10 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta 
 
 // Stand-alone predictor product (Eq. 3) with the same main loop: K_hat or V_hat
 // (blockIdx.y) of the tile is rounded to bf16 and stored at
-// out[row, col0 + column].  Output row = sbase[b]*kSlotTokens + j.
+// out[row, col0 + column].  Output row = sbase[b]*kSlotTokens + j.  With an
+// activation it is the first layer of the one-hidden-layer predictor
+// (Appendix "Prediction Network Architecture").
+template <int ACT>      // activation before rounding: 0 none, 1 ReLU, 2 SiLU
 __global__ __launch_bounds__(NTHREADS) void recon_mfma_kernel(Args a, SeqMeta meta) {
   __shared__ Smem sm;
   char* smem = reinterpret_cast<char*>(&sm);
@@ -726,6 +729,23 @@ __global__ __launch_bounds__(NTHREADS) void recon_mfma_kernel(Args a, SeqMeta me
           tid, (ttile * 3) % ((a.D + a.m) / BK));
   pass_prefetch<false>(sa, io, a);
   gemm_pass<false, false>(acc, smem, a, io, sa, sb, tid);
+  // activation of a hidden layer (a compile-time choice: a run-time branch over 256 live
+  // accumulators costs hundreds of spilled registers)
+  if constexpr (ACT == 1) {
+#pragma unroll
+    for (int ji = 0; ji < 4; ++ji)
+#pragma unroll
+      for (int ci = 0; ci < 4; ++ci)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[ji][ci][r] = fmaxf(acc[ji][ci][r], 0.f);
+  } else if constexpr (ACT == 2) {
+#pragma unroll
+    for (int ji = 0; ji < 4; ++ji)
+#pragma unroll
+      for (int ci = 0; ci < 4; ++ci)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[ji][ci][r] = acc[ji][ci][r] / (1.f + __expf(-acc[ji][ci][r]));
+  }
   bf16_t* out = a.out[which];
   const int64_t orow0 = (int64_t)meta.sbase[b] * kSlotTokens;
 #pragma unroll
@@ -770,7 +790,7 @@ inline int launch_fused_decode(int H_q, int H_kv, int d, int m, int d_out, int n
                                const T* va, const T* kr, const T* vr, const T* wk, const T* wv,
                                const T* q, float* part_o, float* part_ml, SeqMeta& mt,
                                int* fused_step, hipStream_t st, bool packed = false,
-                               const KvExtras& ex = KvExtras()) {
+                               const KvExtras& ex = KvExtras(), int x_width = 0) {
   if constexpr (sizeof(T) != 2) {
     return 6;
   } else {
@@ -780,6 +800,7 @@ inline int launch_fused_decode(int H_q, int H_kv, int d, int m, int d_out, int n
     a.q = q; a.part_o = part_o; a.part_ml = part_ml;
     a.out[0] = a.out[1] = nullptr; a.ldo = 0; a.col0 = 0;
     a.D = H_kv * d; a.m = m; a.d_out = d_out; a.H_q = H_q; a.G = H_q / H_kv;
+    if (x_width > 0) { a.D = x_width; a.m = 0; }     // predictor input = one matrix of that width (ka / va)
     a.n_ret_heads = n_ret_heads; a.scale = scale;
     a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;
     a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
@@ -805,7 +826,7 @@ inline int launch_fused_decode(int H_q, int H_kv, int d, int m, int d_out, int n
 template <typename T>
 inline int launch_recon_mfma(int D, int m, int d_out, const T* ka, const T* va, const T* kr, const T* vr,
                              const T* wk, const T* wv, T* out_k, T* out_v, int64_t ldo, int col0,
-                             SeqMeta& mt, hipStream_t st) {
+                             SeqMeta& mt, hipStream_t st, int act = 0) {
   if constexpr (sizeof(T) != 2) {
     return 6;
   } else {
@@ -818,7 +839,10 @@ inline int launch_recon_mfma(int D, int m, int d_out, const T* ka, const T* va, 
     a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;
     a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
     const int grid = ((a.n_tiles + 7) / 8) * 8;
-    hipLaunchKernelGGL(fused::recon_mfma_kernel, dim3(grid, 2), dim3(fused::NTHREADS), 0, st, a, mt);
+    const dim3 g(grid, 2), blk(fused::NTHREADS);
+    if (act == 1) hipLaunchKernelGGL(fused::recon_mfma_kernel<1>, g, blk, 0, st, a, mt);
+    else if (act == 2) hipLaunchKernelGGL(fused::recon_mfma_kernel<2>, g, blk, 0, st, a, mt);
+    else hipLaunchKernelGGL(fused::recon_mfma_kernel<0>, g, blk, 0, st, a, mt);
     if (hipGetLastError() != hipSuccess) return 7;
     return 0;
   }

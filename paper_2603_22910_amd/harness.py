@@ -84,6 +84,19 @@ class DeviceWorkload:
                           self.lse, self.workspace, rope, window, stream)
         return self.out, self.lse
 
+    def decode_mlp(self, weights, hidden: int, activation: int, stream=None):
+        """weights = (W1_K, W2_K, W1_V, W2_V) host or device tensors."""
+        wts = tuple(t.to(self.dev).contiguous() for t in weights)
+        need = ek.mlp_workspace_bytes(self.shape, self.inp.n_decode, self.inp.total_decode_tokens, hidden)
+        if need == 0:
+            raise RuntimeError("echokv_mlp_workspace_bytes rejected the shape")
+        if getattr(self, "_mlp_ws", None) is None or self._mlp_ws.numel() < need:
+            self._mlp_ws = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        self._keep = wts
+        ek.decode_attn_mlp(self.shape, self.anchor, self.target, wts[0], wts[1], wts[2], wts[3], hidden,
+                           activation, self.q, self.out, self.lse, self._mlp_ws, stream)
+        return self.out, self.lse
+
     def prefill(self, stream=None):
         saved = self.shape.flags
         self.shape.flags = saved & ~ek.FLAG_W_PACKED      # prefill takes row-major weights

@@ -286,3 +286,17 @@ def window_rows(inp: Inputs, n_sink: int, n_recent: int):
                     win[b, r, :w.n_retained] = src[inp.seq_start[b] + p]
         out.append(win)
     return out[0], out[1]
+
+
+def mlp_weights(w: Workload, hidden: int):
+    """Weights of a one-hidden-layer predictor for workload w: W1 [d_in, hidden] ~
+    N(0, 1/sqrt(d_in)), W2 [hidden, d_out] ~ N(0, sqrt(2/hidden)) (keeps the
+    rebuilt dims near unit variance behind a ReLU), for keys and for values."""
+    out = []
+    for tag in ("K", "V"):
+        w1 = torch.randn(w.d_in, hidden, generator=_gen(w.seed, "mlp_W1_" + tag),
+                         dtype=torch.float32) / math.sqrt(w.d_in)
+        w2 = torch.randn(hidden, w.d_out, generator=_gen(w.seed, "mlp_W2_" + tag),
+                         dtype=torch.float32) * math.sqrt(2.0 / hidden)
+        out += [w1.to(w.torch_dtype), w2.to(w.torch_dtype)]
+    return tuple(out)          # W1_K, W2_K, W1_V, W2_V

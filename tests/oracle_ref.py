@@ -70,3 +70,16 @@ def decode_paper_ref(inp, rope=None, window=None, seqs=None, scale=None):
                                        inp.w.n_kv_heads, scale, rope=r, window=wnd)
         outs.append(o); lses.append(l)
     return np.stack(outs), np.stack(lses)
+
+
+def decode_mlp_ref(inp, weights, act, seqs=None, scale=None):
+    """weights = (W1_K, W2_K, W1_V, W2_V) torch tensors; act = "relu" | "silu"."""
+    seqs = range(inp.n_decode) if seqs is None else seqs
+    W = [f64(t) for t in weights]
+    outs, lses = [], []
+    for b in seqs:
+        K_a, V_a, K_r, V_r = seq_arrays(inp, b)
+        o, l = orc.echokv_decode_mlp(f64(inp.q[b]), K_a, V_a, K_r, V_r, W[0], W[1], W[2], W[3],
+                                     inp.w.n_kv_heads, act, scale)
+        outs.append(o); lses.append(l)
+    return np.stack(outs), np.stack(lses)

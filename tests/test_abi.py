@@ -215,3 +215,20 @@ def test_window_append_argument_errors(lib):
     assert code(ek.window_append, sh, FAKE, FAKE, 4, 128, [5], FAKE, FAKE, [-2], stream=0) == ek.ERR_SHAPE
     assert code(ek.window_append, sh, FAKE, FAKE, 4, 128, [5], None, FAKE, [1], stream=0) == ek.ERR_NULL
     assert code(ek.window_append, sh, FAKE, FAKE, 4, 128, [5, 6], None, None, [0, 0], stream=0) == ek.OK
+
+
+def test_mlp_argument_errors(lib):
+    sh = ek.make_shape(8, 8, 64, 256, "bf16")
+    a, t = caches()
+    big = _Ws(1 << 30)
+    ok = (FAKE, FAKE, FAKE, FAKE)
+    assert code(ek.decode_attn_mlp, sh, a, t, *ok, 100, ek.ACT_RELU, FAKE, FAKE, None, big, stream=0) == ek.ERR_SHAPE
+    assert code(ek.decode_attn_mlp, sh, a, t, *ok, 128, 0, FAKE, FAKE, None, big, stream=0) == ek.ERR_SHAPE
+    assert code(ek.decode_attn_mlp, sh, a, t, None, FAKE, FAKE, FAKE, 128, ek.ACT_SILU, FAKE, FAKE, None, big,
+                stream=0) == ek.ERR_NULL
+    assert code(ek.decode_attn_mlp, sh, a, t, *ok, 128, ek.ACT_RELU, FAKE, FAKE, None, _Ws(64), stream=0) == ek.ERR_WORKSPACE
+    f32 = ek.make_shape(8, 8, 64, 256, "f32")
+    assert code(ek.decode_attn_mlp, f32, a, t, *ok, 128, ek.ACT_RELU, FAKE, FAKE, None, big, stream=0) == ek.ERR_UNSUPPORTED
+    assert ek.mlp_workspace_bytes(f32, 1, 100, 128) == 0
+    assert ek.mlp_workspace_bytes(sh, 1, 100, 128) > 0
+    assert ek.mlp_workspace_bytes(sh, 1, 100, 96) == 0
