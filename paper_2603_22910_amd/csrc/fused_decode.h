@@ -225,9 +225,6 @@ struct Frags {
 
 __device__ __forceinline__ void load_frags(Frags& f, const char* smem, int stage, int kk,
                                            const Addr& ad) {
-#if defined(ECHOKV_EXP_NOFRAG)
-  if (kk >= 0) return;
-#endif
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     f.x[i] = *reinterpret_cast<const bf16x8_t*>(smem + ad.frx[kk][i & 1] + (i >> 1) * 8192 + stage * kStageBytes);
@@ -240,9 +237,6 @@ __device__ __forceinline__ void load_frags(Frags& f, const char* smem, int stage
 // lanes = output columns).
 template <bool SWAP>
 __device__ __forceinline__ void mma16(floatx16_t (&acc)[4][4], const Frags& f) {
-#if defined(ECHOKV_EXP_NOMMA)
-  return;
-#endif
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
@@ -255,11 +249,7 @@ __device__ __forceinline__ void mma16(floatx16_t (&acc)[4][4], const Frags& f) {
 }
 
 // scheduling-group masks of __builtin_amdgcn_sched_group_barrier
-#ifndef ECHOKV_NO_SGB
 #define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
-#else
-#define SGB(mask, n)
-#endif
 constexpr int SG_VALU = 0x2, SG_MFMA = 0x8, SG_VMEM_RD = 0x20, SG_DS_RD = 0x100, SG_DS_WR = 0x200;
 
 // One k-tile (64 input dims) of the pipeline, for the LDS stage STAGE.  Every
@@ -351,9 +341,7 @@ __device__ __forceinline__ void k_tile(floatx16_t (&acc)[4][4], Frags& f0, Frags
   __builtin_amdgcn_sched_barrier(0);
   // every wave has read all it needs from STAGE and (STORE) finished writing the
   // other stage; __syncthreads waits for this wave's LDS traffic first
-#if !defined(ECHOKV_EXP_NOBARRIER)
   __syncthreads();
-#endif
   // ---- step 3
   load_frags(f0, smem, STAGE ^ 1, 0, ad);
   if constexpr (FETCH) fetch_w<PACKED>(st, g, src, D + m, d_out, kfetch);
@@ -442,16 +430,8 @@ __device__ __forceinline__ void gemm_pass(floatx16_t (&acc)[4][4], char* smem, c
   fetch_tile<PACKED>(sa, g, src, D, m, d_out, nka, io.ktile(2));
   __syncthreads();
   load_frags(f0, smem, 0, 0, ad);
-#if defined(ECHOKV_EXP_NOFETCH)
-#define ECHOKV_KT(STAGE, ST) \
-  k_tile<SWAP, PACKED, STAGE, true, false>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, io.ktile(kt + 3))
-#elif defined(ECHOKV_EXP_NOSTORE)
-#define ECHOKV_KT(STAGE, ST) \
-  k_tile<SWAP, PACKED, STAGE, false, false>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, io.ktile(kt + 3))
-#else
 #define ECHOKV_KT(STAGE, ST) \
   k_tile<SWAP, PACKED, STAGE, true, true>(acc, f0, f1, ST, smem, ad, g, src, D, m, d_out, nka, io.ktile(kt + 3))
-#endif
   int kt = 0;
   for (; kt + 1 < nk; kt += 2) {
     ECHOKV_KT(0, sb);
