@@ -60,6 +60,10 @@ def load() -> C.CDLL:
     if _LIB is not None:
         return _LIB
     path = os.environ.get("ECHOKV_LIB", LIB_PATH)   # A/B builds of the same ABI
+    # The tensors handed to this library live in PyTorch's HIP runtime: bring that copy of the
+    # runtime into the process first, so that the library's own dependency resolves to it and
+    # kernels are launched in the context that owns the memory.
+    import torch  # noqa: F401
     if not os.path.exists(path):
         raise RuntimeError(f"{path} not found: build it with "
                            "`python -m paper_2603_22910_amd.build` (needs hipcc); "
