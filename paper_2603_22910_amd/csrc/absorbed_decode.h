@@ -460,22 +460,24 @@ __global__ __launch_bounds__(kPvWaves * 64, 2) void pv_kernel(Args a, SeqMeta me
 // ---------------------------------------------------------------------------
 // Merge of a sequence's token splits (exact re-association of the softmax):
 //   M = max_s M_s,  l = sum_s l_s 2^(M_s - M),  y[b, h, k] = sum_s 2^(M_s - M) ypart_s[h, k] / l
-// and the log-sum-exp.  grid = (d_in / 256, H_q, nseq); 256 threads = 64 column
-// quads x 4 groups that each take every 4th split.
+// and the log-sum-exp.  grid = (ceil(d_in / (1024 / SG)), H_q, nseq).
 // ---------------------------------------------------------------------------
+template <int SG>       // thread groups that share a column quad and split the splits: 1 (few splits) or 4
 __global__ __launch_bounds__(256) void y_sum_kernel(Args a, SeqMeta meta) {
-  const int h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x, cq = tid & 63, sg = tid >> 6;
-  const int k = min(blockIdx.x * 256 + cq * 4, a.d_in - 4);    // tail threads repeat the last quad
+  constexpr int CQ = 256 / SG;                   // column quads per workgroup
+  const int h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int cq = tid % CQ, sg = tid / CQ;
+  const int k = min((blockIdx.x * CQ + cq) * 4, a.d_in - 4);     // tail threads repeat the last quad
   const int s0 = meta.tbase[b], ns = meta.tbase[b + 1] - s0;
-  __shared__ float4 red[4][64];
   __shared__ float s_red[4];
   __shared__ float s_w[256];
+  __shared__ float4 s_acc[SG][CQ];
   const float* mlp = a.ml + ((int64_t)s0 * a.H_pad + h) * 2;
   const int64_t mls = (int64_t)a.H_pad * 2;
   float M = -INFINITY;
   for (int i = tid; i < ns; i += 256) M = fmaxf(M, mlp[i * mls]);
   M = wave_max(M, 64);
-  if (cq == 0) s_red[sg] = M;
+  if (lane == 0) s_red[wave] = M;
   __syncthreads();
   M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -492,8 +494,8 @@ __global__ __launch_bounds__(256) void y_sum_kernel(Args a, SeqMeta meta) {
     s_w[tid] = wgt;
     __syncthreads();
     const int cn = min(256, ns - c0);
-#pragma unroll 4
-    for (int j = sg; j < cn; j += 4) {
+#pragma unroll 8
+    for (int j = sg; j < cn; j += SG) {
       const float4 v = *reinterpret_cast<const float4*>(yp + (c0 + j) * yps);
       const float wj = s_w[j];
       acc.x = fmaf(wj, v.x, acc.x); acc.y = fmaf(wj, v.y, acc.y);
@@ -501,20 +503,20 @@ __global__ __launch_bounds__(256) void y_sum_kernel(Args a, SeqMeta meta) {
     }
   }
   l = wave_sum(l, 64);
-  red[sg][cq] = acc;
-  __syncthreads();              // also orders the reads of s_red above before its reuse
-  if (cq == 0) s_red[sg] = l;
+  s_acc[sg][cq] = acc;
+  __syncthreads();              // s_red was read above by every thread
+  if (lane == 0) s_red[wave] = l;
   __syncthreads();
   if (sg != 0) return;
   l = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
   const float inv = 1.f / l;
-  float4 r;
-  r.x = ((red[0][cq].x + red[1][cq].x) + (red[2][cq].x + red[3][cq].x)) * inv;
-  r.y = ((red[0][cq].y + red[1][cq].y) + (red[2][cq].y + red[3][cq].y)) * inv;
-  r.z = ((red[0][cq].z + red[1][cq].z) + (red[2][cq].z + red[3][cq].z)) * inv;
-  r.w = ((red[0][cq].w + red[1][cq].w) + (red[2][cq].w + red[3][cq].w)) * inv;
-  *reinterpret_cast<float4*>(a.y + ((int64_t)b * a.H_q + h) * a.d_in + k) = r;
-  if (a.lse && blockIdx.x == 0 && cq == 0)
+#pragma unroll
+  for (int g = 1; g < SG; ++g) {
+    acc.x += s_acc[g][cq].x; acc.y += s_acc[g][cq].y; acc.z += s_acc[g][cq].z; acc.w += s_acc[g][cq].w;
+  }
+  acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
+  *reinterpret_cast<float4*>(a.y + ((int64_t)b * a.H_q + h) * a.d_in + k) = acc;
+  if (a.lse && blockIdx.x == 0 && tid == 0)
     a.lse[(a.out_seq0 + b) * a.H_q + h] = (M + log2f(l)) * 0.6931471805599453f;
 }
 
@@ -599,15 +601,16 @@ __global__ __launch_bounds__(256) void out_partial_kernel(Args a, int nseq) {
       acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, lo), xb, acc[i], 0, 0, 0);
     }
   };
-  OutStage<HD> s0, s1;
+  // four register stages: a slice of 256 input rows is 4 steps per wave, all in flight at once
+  OutStage<HD> s0, s1, s2, s3;
   const int nw = (nsteps - wave + 3) / 4;
-  fetch(s0, wave);
-  for (int it = 0; it < nw; it += 2) {
+  for (int it = 0; it < nw; it += 4) {
     const int st = wave + it * 4;
-    fetch(s1, st + 4);
+    fetch(s0, st); fetch(s1, st + 4); fetch(s2, st + 8); fetch(s3, st + 12);
     mma(s0, ok);
-    fetch(s0, st + 8);
     mma(s1, ok && it + 1 < nw);
+    mma(s2, ok && it + 2 < nw);
+    mma(s3, ok && it + 3 < nw);
   }
   if (wave > 0) {
 #pragma unroll

@@ -561,7 +561,7 @@ AbsPlan plan_absorbed(const Dims& dm, int nseq, int64_t slots, int64_t splits) {
   p.H_pad = (dm.H_q + absorbed::kHB - 1) / absorbed::kHB * absorbed::kHB;
   p.n_col_a = abs_col_tiles(dm.D);
   p.n_col_tiles = p.n_col_a + abs_col_tiles(dm.m);
-  p.k_slices = std::max(1, std::min(16, dm.d_in / 512));
+  p.k_slices = std::max(1, std::min(64, dm.d_in / 256));
   p.k_slice = ((dm.d_in + p.k_slices - 1) / p.k_slices + 63) / 64 * 64;
   p.k_slices = (dm.d_in + p.k_slice - 1) / p.k_slice;
   size_t o = 0;
@@ -650,7 +650,10 @@ int absorbed_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_lay
     LAUNCH_CHECK();
     hipLaunchKernelGGL(absorbed::pv_kernel, dim3(splits * pl.n_col_tiles, nhb), dim3(absorbed::kPvWaves * 64), 0, st, a, mt);
     LAUNCH_CHECK();
-    hipLaunchKernelGGL(absorbed::y_sum_kernel, dim3((dm.d_in + 255) / 256, dm.H_q, n), dim3(256), 0, st, a, mt);
+    int max_splits = 0;
+    for (int b = 0; b < n; ++b) max_splits = std::max(max_splits, mt.tbase[b + 1] - mt.tbase[b]);
+    if (max_splits > 8) hipLaunchKernelGGL(absorbed::y_sum_kernel<4>, dim3((dm.d_in + 255) / 256, dm.H_q, n), dim3(256), 0, st, a, mt);
+    else hipLaunchKernelGGL(absorbed::y_sum_kernel<1>, dim3((dm.d_in + 1023) / 1024, dm.H_q, n), dim3(256), 0, st, a, mt);
     LAUNCH_CHECK();
     const dim3 og(dm.H_kv, pl.k_slices, (n * dm.G + 31) / 32);
     if (dm.d == 128) hipLaunchKernelGGL((absorbed::out_partial_kernel<128>), og, dim3(256), 0, st, a, n);
