@@ -160,11 +160,17 @@ class LayerCache:
         return c
 
     def as_c(self) -> LayerCacheC:
-        return LayerCacheC(
-            _ptr(self.k), _ptr(self.v), self.width, self.batch, self.pool_tokens,
-            self.seq_start.ctypes.data_as(C.POINTER(C.c_int64)),
-            self.seq_len.ctypes.data_as(C.POINTER(C.c_int32)),
-            self.seq_cap.ctypes.data_as(C.POINTER(C.c_int32)))
+        # built once per (tensors, arrays): a decode loop calls this three times a step
+        key = (id(self.k), id(self.v), id(self.seq_start), id(self.seq_len), id(self.seq_cap),
+               self.width, self.pool_tokens)
+        if getattr(self, "_c_key", None) != key:
+            self._c = LayerCacheC(
+                _ptr(self.k), _ptr(self.v), self.width, self.batch, self.pool_tokens,
+                self.seq_start.ctypes.data_as(C.POINTER(C.c_int64)),
+                self.seq_len.ctypes.data_as(C.POINTER(C.c_int32)),
+                self.seq_cap.ctypes.data_as(C.POINTER(C.c_int32)))
+            self._c_key = key
+        return self._c
 
 
 def _ptr(t) -> Optional[int]:

@@ -78,6 +78,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void prefill_attn_kernel(Args a) {
     for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
   const float scale2 = a.scale * 1.44269504088896340736f;    // softmax in base 2: exp(x) = 2^(x log2 e)
+  // smallest query position among this wave's lanes (lane 0 of either half)
+  const int qpos_min = a.q_pos0 + min(i0 + wave * 32, a.T_q - 1);
 
   const int kv_end = min(Ltot, a.q_pos0 + min(i0 + BQ, a.T_q));   // keys any query of the block sees
   const int ntiles = (kv_end + BKV - 1) / BKV;
@@ -145,28 +147,36 @@ __global__ __launch_bounds__(NTHREADS, 2) void prefill_attn_kernel(Args a) {
         const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sk[cur] + (row * C::CH + (c ^ C::kswz(row))) * 16);
         sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[mb], 0, 0, 0);
       }
-    // ---- online softmax for this lane's query (keys: mb*32 + 8*(r/4) + 4*lh + r%4)
+    // ---- online softmax for this lane's query (keys: mb*32 + 8*(r/4) + 4*lh + r%4).
+    //      The running maximum is kept in raw score units; the scale is folded into the
+    //      exponent: p = 2^(s * scale2 - m * scale2).  Only tiles that reach a query's own
+    //      position need the causal mask (a wave-uniform test).
     const int kv0 = t * BKV;
     float mx = -INFINITY;
+    if (kv0 + BKV - 1 > qpos_min) {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kv0 + mb * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+          if (key > qpos) sacc[mb][r] = -INFINITY;
+        }
+    }
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = kv0 + mb * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-        const float s = (key <= qpos) ? sacc[mb][r] * scale2 : -INFINITY;   // base-2 logits
-        sacc[mb][r] = s;
-        mx = fmaxf(mx, s);
-      }
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mb][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);          // finite from the first tile on (key 0 is visible)
-    const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+    const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
+    const float mneg = -m_new * scale2;
     float lsum = 0.f;
     bf16x8_t pf[4];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(sacc[mb][r] - m_new);
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][r], scale2, mneg));
         lsum += p;
         pf[mb * 2 + (r >> 3)][r & 7] = (__bf16)p;
       }
@@ -218,7 +228,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void prefill_attn_kernel(Args a) {
         }
       }
     if (a.lse && lh == 0)
-      a.lse[(int64_t)qi * a.H_q + h] = (m_run + __log2f(l_tot)) * 0.69314718055994530942f;
+      a.lse[(int64_t)qi * a.H_q + h] = (m_run * scale2 + __log2f(l_tot)) * 0.69314718055994530942f;
   }
 }
 
