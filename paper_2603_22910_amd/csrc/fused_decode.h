@@ -499,18 +499,44 @@ __device__ __forceinline__ KExtra make_kextra(const float* cos, const float* sin
   return x;
 }
 
+// Softmax numerators of one (head, query head) pair from the lane-partial scores s[4]
+// (token ji * 32 + lane % 32; the two lane halves hold the two halves of the head dims).
+__device__ __forceinline__ void score_tail(float (&s)[4], EpiSmem& e, int wave, int lane, int pair,
+                                           int jw0, const KExtra& x) {
+  const int lr = lane & 31, lh = lane >> 5;
+  float mx = -INFINITY;
+#pragma unroll
+  for (int ji = 0; ji < 4; ++ji) {
+    s[ji] += __shfl_xor(s[ji], 32, 64);
+    const int tok = jw0 + ji * 32 + lr;
+    if (tok < x.lo || tok >= x.hi) s[ji] = -INFINITY;
+    mx = fmaxf(mx, s[ji]);
+  }
+  mx = wave_max(mx, 32);
+  float sum = 0.f;
+  float* pp = e.p[wave][pair];
+#pragma unroll
+  for (int ji = 0; ji < 4; ++ji) {
+    const float p = (s[ji] == -INFINITY) ? 0.f : __expf(s[ji] - mx);
+    sum += p;
+    if (lh == 0) pp[ji * 32 + lr] = p;
+  }
+  sum = wave_sum(sum, 32);
+  if (lane == 0) { e.ml[wave][pair][0] = mx; e.ml[wave][pair][1] = sum; }
+}
+
 template <int HD, bool ROPE>
 __device__ __forceinline__ void k_epilogue(floatx16_t (&acc)[4][4], EpiSmem& e, int G,
                                            int wave, int lane, int jw0, int L, const KExtra& x) {
   constexpr int HPW = WN / HD, CBH = HD / 32;
   const int wc = wave & 1, lr = lane & 31, lh = lane >> 5;
+  if constexpr (!ROPE) {
 #pragma unroll
-  for (int hw = 0; hw < HPW; ++hw) {
-    for (int g = 0; g < G; ++g) {
-      pin_acc(acc);
-      const float* qs = &e.q[((wc * HPW + hw) * G + g) * HD];
-      float s[4] = {0.f, 0.f, 0.f, 0.f};
-      if constexpr (!ROPE) {
+    for (int hw = 0; hw < HPW; ++hw) {
+      for (int g = 0; g < G; ++g) {
+        pin_acc(acc);
+        const float* qs = &e.q[((wc * HPW + hw) * G + g) * HD];
+        float s[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int cb = 0; cb < CBH; ++cb) {
 #pragma unroll
@@ -527,63 +553,74 @@ __device__ __forceinline__ void k_epilogue(floatx16_t (&acc)[4][4], EpiSmem& e, 
             __builtin_amdgcn_sched_barrier(0);
           }
         }
-      } else {
-        // Rotary embedding of the rebuilt key at its token's position, folded into the dot
-        // product: feature c pairs with c + HD/2, which this lane holds HD/64 column blocks
-        // further on.  With a = k_c, b = k_{c+HD/2}:
-        //   q_c (a cos - b sin) + q_{c+HD/2} (b cos + a sin)
-        //     = cos (a q_c + b q_{c+HD/2}) + sin (a q_{c+HD/2} - b q_c)
-        // The accumulators are only read.  Masked tokens borrow the last valid table row.
-        constexpr int HB = CBH / 2;
+        score_tail(s, e, wave, lane, hw * G + g, jw0, x);
+      }
+    }
+  } else {
+    // Rotary embedding of the rebuilt key at its token's position, folded into the dot
+    // product: feature c pairs with c + HD/2, which this lane holds HD/64 column blocks
+    // further on.  With a = k_c, b = k_{c+HD/2}:
+    //   q_c (a cos - b sin) + q_{c+HD/2} (b cos + a sin)
+    //     = cos (a q_c + b q_{c+HD/2}) + sin (a q_{c+HD/2} - b q_c)
+    // The accumulators are only read.  Masked tokens borrow the last valid table row.  The
+    // table values and the accumulator reads of a (token block, column block) are shared by
+    // the query heads of the group: the loop over them is innermost, unrolled to the
+    // largest group size with a uniform skip.
+    constexpr int HB = CBH / 2;
 #pragma unroll
-        for (int ji = 0; ji < 4; ++ji) {
-          const int pos = min(jw0 + ji * 32 + lr, L - 1);
-          const float* cr = x.cos + (int64_t)pos * (HD / 2) + lh * 4;
-          const float* sr = x.sin + (int64_t)pos * (HD / 2) + lh * 4;
+    for (int hw = 0; hw < HPW; ++hw) {
+      float s[MAXPAIR][4];
 #pragma unroll
-          for (int cb = 0; cb < HB; ++cb) {
+      for (int g = 0; g < MAXPAIR; ++g)
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-              const float4 c4 = *reinterpret_cast<const float4*>(cr + cb * 32 + r4 * 8);
-              const float4 s4 = *reinterpret_cast<const float4*>(sr + cb * 32 + r4 * 8);
-              const float4 qa = *reinterpret_cast<const float4*>(qs + cb * 32 + r4 * 8 + lh * 4);
-              const float4 qb = *reinterpret_cast<const float4*>(qs + (cb + HB) * 32 + r4 * 8 + lh * 4);
-              const floatx16_t& ka = acc[hw * CBH + cb][ji];
-              const floatx16_t& kb = acc[hw * CBH + cb + HB][ji];
-              const float cc[4] = {c4.x, c4.y, c4.z, c4.w}, ss[4] = {s4.x, s4.y, s4.z, s4.w};
-              const float q0[4] = {qa.x, qa.y, qa.z, qa.w}, q1[4] = {qb.x, qb.y, qb.z, qb.w};
+        for (int ji = 0; ji < 4; ++ji) s[g][ji] = 0.f;
 #pragma unroll
-              for (int i = 0; i < 4; ++i) {
-                const float a = ka[r4 * 4 + i], b = kb[r4 * 4 + i];
-                const float t1 = fmaf(a, q0[i], b * q1[i]);
-                const float t2 = fmaf(a, q1[i], -b * q0[i]);
-                s[ji] = fmaf(cc[i], t1, fmaf(ss[i], t2, s[ji]));
+      for (int ji = 0; ji < 4; ++ji) {
+        const int pos = min(jw0 + ji * 32 + lr, L - 1);
+        const float* cr = x.cos + (int64_t)pos * (HD / 2) + lh * 4;
+        const float* sr = x.sin + (int64_t)pos * (HD / 2) + lh * 4;
+#pragma unroll
+        for (int cb = 0; cb < HB; ++cb) {
+          pin_acc(acc);
+          float cc[16], ss[16], ka[16], kb[16];
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            const float4 c4 = *reinterpret_cast<const float4*>(cr + cb * 32 + r4 * 8);
+            const float4 s4 = *reinterpret_cast<const float4*>(sr + cb * 32 + r4 * 8);
+            cc[r4 * 4] = c4.x; cc[r4 * 4 + 1] = c4.y; cc[r4 * 4 + 2] = c4.z; cc[r4 * 4 + 3] = c4.w;
+            ss[r4 * 4] = s4.x; ss[r4 * 4 + 1] = s4.y; ss[r4 * 4 + 2] = s4.z; ss[r4 * 4 + 3] = s4.w;
+          }
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            ka[r] = acc[hw * CBH + cb][ji][r];
+            kb[r] = acc[hw * CBH + cb + HB][ji][r];
+          }
+#pragma unroll
+          for (int g = 0; g < MAXPAIR; ++g) {
+            if (g < G) {
+              const float* qs = &e.q[((wc * HPW + hw) * G + g) * HD];
+#pragma unroll
+              for (int r4 = 0; r4 < 4; ++r4) {
+                const float4 qa = *reinterpret_cast<const float4*>(qs + cb * 32 + r4 * 8 + lh * 4);
+                const float4 qb = *reinterpret_cast<const float4*>(qs + (cb + HB) * 32 + r4 * 8 + lh * 4);
+                const float q0[4] = {qa.x, qa.y, qa.z, qa.w}, q1[4] = {qb.x, qb.y, qb.z, qb.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                  const float a = ka[r4 * 4 + i], b = kb[r4 * 4 + i];
+                  const float t1 = fmaf(a, q0[i], b * q1[i]);
+                  const float t2 = fmaf(a, q1[i], -b * q0[i]);
+                  s[g][ji] = fmaf(cc[r4 * 4 + i], t1, fmaf(ss[r4 * 4 + i], t2, s[g][ji]));
+                }
               }
-              asm volatile("" ::: "memory");       // keep the table loads of later rounds from piling up
-              __builtin_amdgcn_sched_barrier(0);
             }
           }
+          asm volatile("" ::: "memory");       // keep the table loads of later rounds from piling up
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
-      float mx = -INFINITY;
 #pragma unroll
-      for (int ji = 0; ji < 4; ++ji) {
-        s[ji] += __shfl_xor(s[ji], 32, 64);
-        const int tok = jw0 + ji * 32 + lr;
-        if (tok < x.lo || tok >= x.hi) s[ji] = -INFINITY;
-        mx = fmaxf(mx, s[ji]);
-      }
-      mx = wave_max(mx, 32);
-      float sum = 0.f;
-      float* pp = e.p[wave][hw * G + g];
-#pragma unroll
-      for (int ji = 0; ji < 4; ++ji) {
-        const float p = (s[ji] == -INFINITY) ? 0.f : __expf(s[ji] - mx);
-        sum += p;
-        if (lh == 0) pp[ji * 32 + lr] = p;
-      }
-      sum = wave_sum(sum, 32);
-      if (lane == 0) { e.ml[wave][hw * G + g][0] = mx; e.ml[wave][hw * G + g][1] = sum; }
+      for (int g = 0; g < MAXPAIR; ++g)
+        if (g < G) score_tail(s[g], e, wave, lane, hw * G + g, jw0, x);
     }
   }
 }
