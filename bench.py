@@ -201,6 +201,18 @@ def main():
     if args.mlp_hidden:      # two layers, for keys and for values
         flops = 4.0 * args.mlp_hidden * (w.d_in + w.d_out) * dec_tokens
     bytes_alg = dec_tokens * 2.0 * w.d_in * w.elem_size + 2.0 * w.d_in * w.d_out * w.elem_size
+    stream_ceiling = None
+
+    def measured_stream_read():
+        # what a plain streaming-read kernel gets out of this GPU's memory, over the anchor K cache
+        # (or a scratch buffer when that is small): context for the nominal 8 TB/s
+        nonlocal stream_ceiling
+        if stream_ceiling is None:
+            buf = dw.K_a if dw.K_a.numel() * dw.K_a.element_size() >= (1 << 29) else \
+                torch.ones(1 << 29, dtype=torch.uint8, device=dev)
+            stream_ceiling = ek.profile_stream_read(buf, 5)
+        return stream_ceiling
+
     def absorbed_roofline(kern_ms, launches):
         # the absorbed path's kernels together read every cache row and both weight matrices once
         k_s = kern_ms / launches * 1e-3
@@ -208,7 +220,7 @@ def main():
         return {"bound": "hbm", "kernel": "absorbed decode (scores_kernel + pv_kernel and 5 small ones)",
                 "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
                 "traffic": read_traffic(w.name + "_absorbed"), "kernel_ms": k_s * 1e3,
-                "algorithmic_bytes": bytes_alg}
+                "algorithmic_bytes": bytes_alg, "measured_stream_read_GBs": measured_stream_read()}
 
     roofline = None
     if args.absorbed and launches > 0 and kern_ms > 0:

@@ -260,6 +260,15 @@ int echokv_prefill_attn(const echokv_shape *shape, const echokv_layer_cache *anc
 int echokv_profile_enable(int on);
 int echokv_profile_read(double *total_ms, int64_t *launches);
 
+/* Measurement aid: the rate at which a plain kernel streams `bytes` of device
+ * memory at `buf` (16-byte aligned, at least 403 MB to mean anything; the
+ * tail beyond a multiple of 384 MiB is not read) through the chip, best of
+ * `repeats` timed passes on the default stream, in GB/s.  The yardstick for the
+ * HBM-bound kernels: what the memory system delivers to the simplest possible
+ * reader, as opposed to the nominal peak.  Synchronous. */
+int echokv_profile_stream_read(const void *buf, size_t bytes, int32_t repeats,
+                               double *gb_per_s);
+
 #ifdef __cplusplus
 }
 #endif

@@ -26,7 +26,7 @@ EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn",
            "echokv_profile_enable", "echokv_profile_read", "echokv_pack_weights",
            "echokv_cache_compress", "echokv_decode_attn_ex", "echokv_window_append",
-           "echokv_mlp_workspace_bytes", "echokv_decode_attn_mlp")
+           "echokv_mlp_workspace_bytes", "echokv_decode_attn_mlp", "echokv_profile_stream_read")
 ACT_RELU, ACT_SILU = 1, 2
 
 
@@ -114,6 +114,8 @@ def load() -> C.CDLL:
     lib.echokv_profile_enable.argtypes = [C.c_int]
     lib.echokv_profile_read.restype = C.c_int
     lib.echokv_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.echokv_profile_stream_read.restype = C.c_int
+    lib.echokv_profile_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.POINTER(C.c_double)]
     _LIB = lib
     return lib
 
@@ -284,6 +286,14 @@ def prefill_attn(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v,
 def pack_weights(shape: Shape, w, w_packed, stream=None):
     _check(load().echokv_pack_weights(C.byref(shape), _ptr(w), _ptr(w_packed), _stream(stream)),
            "echokv_pack_weights")
+
+
+def profile_stream_read(buf, repeats: int = 5) -> float:
+    """GB/s a plain streaming-read kernel reaches over the tensor `buf`."""
+    out = C.c_double(0.0)
+    _check(load().echokv_profile_stream_read(_ptr(buf), buf.numel() * buf.element_size(), int(repeats),
+                                             C.byref(out)), "echokv_profile_stream_read")
+    return float(out.value)
 
 
 def profile_enable(on: bool):

@@ -746,6 +746,34 @@ int echokv_profile_read(double* total_ms, int64_t* launches) {
   return rc;
 }
 
+int echokv_profile_stream_read(const void* buf, size_t bytes, int32_t repeats, double* gb_per_s) {
+  if (!buf || !gb_per_s) return ECHOKV_ERR_NULL;
+  const int blocks = 12288;
+  const size_t per_block = (size_t)8 * 256 * 16;              // bytes one loop round of a block covers
+  const size_t rounds = bytes / (per_block * blocks);
+  if (rounds == 0 || repeats < 1 || (uintptr_t)buf % 16) return ECHOKV_ERR_SHAPE;
+  const int64_t n16 = (int64_t)(rounds * per_block / 16);
+  hipEvent_t e0, e1;
+  HIP_TRY(hipEventCreate(&e0));
+  HIP_TRY(hipEventCreate(&e1));
+  float best = 0.f;
+  int rc = ECHOKV_OK;
+  for (int r = 0; r < repeats + 1 && rc == ECHOKV_OK; ++r) {      // the first pass warms up
+    if (hipEventRecord(e0, 0) != hipSuccess) { rc = ECHOKV_ERR_HIP; break; }
+    hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(256), 0, 0, (const uint4*)buf, n16,
+                       (uint32_t*)nullptr);
+    float ms = 0.f;
+    if (hipGetLastError() != hipSuccess || hipEventRecord(e1, 0) != hipSuccess ||
+        hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+      rc = ECHOKV_ERR_HIP;
+    else if (r > 0 && (best == 0.f || ms < best)) best = ms;
+  }
+  hipEventDestroy(e0); hipEventDestroy(e1);
+  if (rc) return rc;
+  *gb_per_s = (double)n16 * 16 * blocks / (best * 1e-3) / 1e9;
+  return ECHOKV_OK;
+}
+
 int echokv_cache_append(const echokv_shape* shape, echokv_layer_cache* dst, const void* k_new,
                         const void* v_new, const int32_t* n_new, void* hip_stream) {
   Dims dm;

@@ -89,6 +89,22 @@ __global__ __launch_bounds__(256) void window_append_kernel(WinAppendArgs a, Seq
   }
 }
 
+// Plain streaming read of a buffer, 8 independent 16-byte loads in flight per thread: the
+// yardstick the HBM-bound kernels are compared with (measurement aid, not part of the method).
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4* p, int64_t n16_per_block,
+                                                          uint32_t* sink) {
+  const uint4* base = p + (int64_t)blockIdx.x * n16_per_block + threadIdx.x;
+  uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+  for (int64_t o = 0; o < n16_per_block; o += 8 * 256) {
+    uint4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = base[o + j * 256];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { acc.x ^= v[j].x; acc.y ^= v[j].y; acc.z ^= v[j].z; acc.w ^= v[j].w; }
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u && sink) *sink = 1u;   // keeps the loads alive
+}
+
 // Plain 2-D copy of `rows` rows (used to place the retained dims in front of
 // the predicted ones, Eq. 6).  blockIdx.y selects K or V.
 struct Copy2dArgs {
