@@ -1,0 +1,45 @@
+"""Host-side contract of bench.py and the entry module (no GPU needed)."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
+    assert r.stdout.strip() == ""
+
+
+def test_bench_refuses_a_multi_rank_launch():
+    env = dict(os.environ, WORLD_SIZE="2", RANK="0")
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True,
+                       timeout=120, env=env)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_traffic_files_parse():
+    sys.path.insert(0, ROOT)
+    import bench
+    for name in ("cfg1_7b_mha_r50_b8_l4096", "cfg1_7b_mha_r50_b8_l4096_absorbed"):
+        v = bench.read_traffic(name)
+        assert v is not None and v > 5e8
+    assert bench.read_traffic("no_such_workload") is None
+
+
+def test_entry_module_has_build_and_smoke():
+    sys.path.insert(0, ROOT)
+    import __graft_entry__ as g
+    assert callable(g.build) and callable(g.smoke)
+
+
+def test_gpu_marker_is_registered():
+    ini = open(os.path.join(ROOT, "pytest.ini")).read() if os.path.exists(os.path.join(ROOT, "pytest.ini")) else ""
+    conf = open(os.path.join(ROOT, "tests", "conftest.py")).read()
+    assert "gpu" in ini or "gpu" in conf
