@@ -80,6 +80,9 @@ def main():
     ap.add_argument("--absorbed", action="store_true",
                     help="time the weight-absorbed decode (same output, other association "
                          "order, HBM-bound) instead of the fused reconstruct-then-attend kernel")
+    ap.add_argument("--absorb-v", action="store_true",
+                    help="time the value-absorbed decode (keys through the fused predictor product, "
+                         "values in the other association order); combines with --rope-window")
     ap.add_argument("--rope-window", action="store_true",
                     help="time the paper-faithful decode instead: rotary embedding applied to the "
                          "rebuilt keys and 4 sink + 128 recent tokens attended uncompressed")
@@ -105,12 +108,13 @@ def main():
 
     w = synth.CONFIGS[args.config]
     inp = synth.generate(w)
-    flags = ek.FLAG_UNFUSED if args.unfused else ek.FLAG_ABSORBED if args.absorbed else 0
+    flags = (ek.FLAG_UNFUSED if args.unfused else ek.FLAG_ABSORBED if args.absorbed
+             else ek.FLAG_ABSORB_V if args.absorb_v else 0)
     # the default run also times the weight-absorbed mode afterwards (reported beside the
     # headline, never as `value`): size the workspace for both
     also_absorbed = (not args.unfused and not args.absorbed and not args.packed_weights
                      and w.dtype == "bf16" and not args.no_absorbed and not args.rope_window
-                     and not args.mlp_hidden)
+                     and not args.mlp_hidden and not args.absorb_v)
     dw = DeviceWorkload(inp, flags=flags | (ek.FLAG_ABSORBED if also_absorbed else 0))
     dw.set_flags(flags)
     if args.packed_weights:
@@ -223,7 +227,15 @@ def main():
                 "algorithmic_bytes": bytes_alg, "measured_stream_read_GBs": measured_stream_read()}
 
     roofline = None
-    if args.absorbed and launches > 0 and kern_ms > 0:
+    if args.absorb_v and launches > 0 and kern_ms > 0:
+        # keys: the predictor product as it is; values: absorbed -> half of the dense matrix work
+        k_s = kern_ms / launches * 1e-3
+        ach = 0.5 * flops / k_s / 1e12
+        roofline = {"bound": "mfma", "kernel": "fused_kscores_kernel + value-side absorbed kernels",
+                    "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": None, "kernel_ms": k_s * 1e3,
+                    "algorithmic_flop": 0.5 * flops, "algorithmic_bytes": bytes_alg}
+    elif args.absorbed and launches > 0 and kern_ms > 0:
         roofline = absorbed_roofline(kern_ms, launches)
     elif launches > 0 and kern_ms > 0:
         k_s = kern_ms / launches * 1e-3
@@ -245,7 +257,8 @@ def main():
         "config": {"workload": w.name, "batch": B, "context_tokens": tokens,
                    "H_q": w.n_q_heads, "H_kv": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_retained": w.n_retained, "d_in": w.d_in, "d_out": w.d_out,
-                   "path": "unfused" if args.unfused else "absorbed" if args.absorbed else "fused",
+                   "path": ("unfused" if args.unfused else "absorbed" if args.absorbed
+                            else "value-absorbed" if args.absorb_v else "fused"),
                    "extras": "rope + 4 sink + 128 recent window" if args.rope_window else None,
                    "predictor": f"one hidden layer of {args.mlp_hidden}, ReLU" if args.mlp_hidden else "linear",
                    "weights": "packed [d_out,d_in]" if args.packed_weights else "row-major [d_in,d_out]",

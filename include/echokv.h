@@ -64,6 +64,13 @@ typedef enum { ECHOKV_BF16 = 0, ECHOKV_F32 = 1 } echokv_dtype;
                                   never formed and every cache row is read once.
                                   bf16 caches, row-major weights only; include the
                                   flag in the shape passed to echokv_workspace_bytes */
+#define ECHOKV_FLAG_ABSORB_V 16u /* decode: absorb the value side only.  Keys are rebuilt
+                                  by the fused predictor product and turned into scores
+                                  (so a rotary embedding and the uncompressed window of
+                                  echokv_decode_attn_ex stay available); the weighted sum
+                                  of predictor inputs is multiplied by W_V afterwards,
+                                  which halves the matrix work.  Same conditions as
+                                  ECHOKV_FLAG_ABSORBED; the two exclude each other */
 
 /* One (anchor, target) layer pair. */
 typedef struct {
@@ -193,7 +200,8 @@ typedef struct {
 
 /* echokv_decode_attn with the extras above (extras == NULL, or all of its
  * pointers NULL: the same as echokv_decode_attn).  Not available with
- * ECHOKV_FLAG_ABSORBED (ECHOKV_ERR_UNSUPPORTED).  Same workspace size. */
+ * ECHOKV_FLAG_ABSORBED (ECHOKV_ERR_UNSUPPORTED); available with
+ * ECHOKV_FLAG_ABSORB_V.  Same workspace size. */
 int echokv_decode_attn_ex(const echokv_shape *shape, const echokv_layer_cache *anchor,
                           const echokv_layer_cache *target, const void *w_k,
                           const void *w_v, const void *q,

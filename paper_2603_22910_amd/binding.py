@@ -21,6 +21,7 @@ FLAG_UNFUSED = 1
 FLAG_W_PACKED = 2
 FLAG_STAGED = 4
 FLAG_ABSORBED = 8
+FLAG_ABSORB_V = 16
 
 EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn",

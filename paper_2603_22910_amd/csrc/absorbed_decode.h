@@ -27,6 +27,7 @@
 #pragma once
 #include "common.h"
 #include "fused_decode.h"
+#include "stream_kernels.h"
 
 namespace echokv {
 namespace absorbed {
@@ -49,6 +50,12 @@ struct Args {
   float* ypart;          // [splits, H_pad, d_in]
   float* y;              // [nseq, H_q, d_in]      normalised
   float* opart;          // [k_slices, nseq, H_q, d]
+  float* y_ml;           // [nseq, H_q, 2]         (max in base-2 units, sum) of the merged splits
+  // uncompressed window (value-absorbed mode only): its tokens are left out of the statistics
+  // and the value pass, and its own partial (natural-exponent units, unnormalised o) joins at the end
+  Window win;
+  const float* win_po;   // [nseq, H_q, d] or null
+  const float* win_pml;  // [nseq, H_q, 2]
   void* out; float* lse;
   int64_t out_seq0;
   int32_t D, m, d_in, d_out, H_q, H_pad, G, d;
@@ -286,17 +293,19 @@ __global__ __launch_bounds__(256) void softmax_stats_kernel(Args a, SeqMeta meta
   const int h = blockIdx.x, sp = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = find_seq(meta.tbase, meta.n, sp);
   const int t_begin = (sp - meta.tbase[b]) * a.split_tokens;
-  const int n = min(meta.len[b] - t_begin, a.split_tokens);
+  const int L = meta.len[b];
+  const int j0 = max(0, a.win.lo(L) - t_begin);                       // window tokens are left out
+  const int n = min(min(L, a.win.hi(L)) - t_begin, a.split_tokens);   // (an empty piece gets (-inf, 0))
   const float* row = a.s + (int64_t)h * a.s_ld + (int64_t)meta.sbase[b] * kSlotTokens + t_begin;
   __shared__ float s_red[4];
   float M = -INFINITY;
-  for (int j = tid; j < n; j += 256) M = fmaxf(M, row[j]);
+  for (int j = j0 + tid; j < n; j += 256) M = fmaxf(M, row[j]);
   M = wave_max(M, 64);
   if (lane == 0) s_red[wave] = M;
   __syncthreads();
   M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
   float l = 0.f;
-  for (int j = tid; j < n; j += 256) l += exp2f(row[j] - M);
+  for (int j = j0 + tid; j < n; j += 256) l += exp2f(row[j] - M);
   l = wave_sum(l, 64);
   __syncthreads();
   if (lane == 0) s_red[wave] = l;
@@ -326,6 +335,7 @@ struct PvIo {
   uint32_t pitch2, colb, soff0;
   int nrows, nsteps;
   int lh8;
+  int vlo, vhi;      // rows [vlo, vhi) of the split count (the others are past the end or in the window)
 };
 
 __device__ __forceinline__ void pv_fetch(PvStage& st, const PvIo& io, int step) {
@@ -352,8 +362,8 @@ __device__ __forceinline__ void pv_mma(floatx16_t (&acc)[8], const PvStage& st, 
   for (int i = 0; i < 4; ++i) {
     const float s0 = __uint_as_float(st.s[i >> 1][(2 * i) & 3]);
     const float s1 = __uint_as_float(st.s[i >> 1][(2 * i + 1) & 3]);
-    const float p0 = (t0 + 2 * i < io.nrows) ? exp2f(s0 - M) : 0.f;
-    const float p1 = (t0 + 2 * i + 1 < io.nrows) ? exp2f(s1 - M) : 0.f;
+    const float p0 = (t0 + 2 * i >= io.vlo && t0 + 2 * i < io.vhi) ? exp2f(s0 - M) : 0.f;
+    const float p1 = (t0 + 2 * i + 1 >= io.vlo && t0 + 2 * i + 1 < io.vhi) ? exp2f(s1 - M) : 0.f;
     const bf16_t h0 = f32_to_bf16(p0), h1 = f32_to_bf16(p1);
     pw[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
     pl[i] = (uint32_t)f32_to_bf16(p0 - bf16_to_f32(h0)) | ((uint32_t)f32_to_bf16(p1 - bf16_to_f32(h1)) << 16);
@@ -396,8 +406,10 @@ __global__ __launch_bounds__(kPvWaves * 64, 2) void pv_kernel(Args a, SeqMeta me
   io.colb = (uint32_t)(col_ok ? col : 0) * 2;
   io.soff0 = ((uint32_t)lr * (uint32_t)a.s_ld + (uint32_t)lh * 8) * 4;
   io.nrows = nrows; io.nsteps = (nrows + 15) / 16; io.lh8 = lh * 8;
+  io.vlo = max(0, a.win.lo(L) - t_begin); io.vhi = min(nrows, a.win.hi(L) - t_begin);
   const int head = hb * kHB + lr;
-  const float M = head < a.H_q ? a.ml[((int64_t)sp * a.H_pad + head) * 2] : 0.f;   // the split's own maximum
+  float M = head < a.H_q ? a.ml[((int64_t)sp * a.H_pad + head) * 2] : 0.f;   // the split's own maximum
+  if (M == -INFINITY) M = 0.f;                    // a piece with no counted token: every p is masked
 
   floatx16_t acc[8];
 #pragma unroll
@@ -460,7 +472,7 @@ __global__ __launch_bounds__(kPvWaves * 64, 2) void pv_kernel(Args a, SeqMeta me
 // ---------------------------------------------------------------------------
 // Merge of a sequence's token splits (exact re-association of the softmax):
 //   M = max_s M_s,  l = sum_s l_s 2^(M_s - M),  y[b, h, k] = sum_s 2^(M_s - M) ypart_s[h, k] / l
-// and the log-sum-exp.  grid = (ceil(d_in / (1024 / SG)), H_q, nseq).
+// and (M, l) for the last kernel.  grid = (ceil(d_in / (1024 / SG)), H_q, nseq).
 // ---------------------------------------------------------------------------
 template <int SG>       // thread groups that share a column quad and split the splits: 1 (few splits) or 4
 __global__ __launch_bounds__(256) void y_sum_kernel(Args a, SeqMeta meta) {
@@ -487,7 +499,8 @@ __global__ __launch_bounds__(256) void y_sum_kernel(Args a, SeqMeta meta) {
   for (int c0 = 0; c0 < ns; c0 += 256) {
     float wgt = 0.f;
     if (c0 + tid < ns) {
-      wgt = exp2f(mlp[(c0 + tid) * mls] - M);
+      const float ms = mlp[(c0 + tid) * mls];
+      wgt = ms == -INFINITY ? 0.f : exp2f(ms - M);
       l += wgt * mlp[(c0 + tid) * mls + 1];
     }
     __syncthreads();            // the previous chunk's weights are no longer read
@@ -509,15 +522,17 @@ __global__ __launch_bounds__(256) void y_sum_kernel(Args a, SeqMeta meta) {
   __syncthreads();
   if (sg != 0) return;
   l = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
-  const float inv = 1.f / l;
+  const float inv = l > 0.f ? 1.f / l : 0.f;       // l == 0: every counted token sits in the window
 #pragma unroll
   for (int g = 1; g < SG; ++g) {
     acc.x += s_acc[g][cq].x; acc.y += s_acc[g][cq].y; acc.z += s_acc[g][cq].z; acc.w += s_acc[g][cq].w;
   }
   acc.x *= inv; acc.y *= inv; acc.z *= inv; acc.w *= inv;
   *reinterpret_cast<float4*>(a.y + ((int64_t)b * a.H_q + h) * a.d_in + k) = acc;
-  if (a.lse && blockIdx.x == 0 && tid == 0)
-    a.lse[(a.out_seq0 + b) * a.H_q + h] = (M + log2f(l)) * 0.6931471805599453f;
+  if (blockIdx.x == 0 && tid == 0) {
+    a.y_ml[((int64_t)b * a.H_q + h) * 2] = M;
+    a.y_ml[((int64_t)b * a.H_q + h) * 2 + 1] = l;
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -631,7 +646,9 @@ __global__ __launch_bounds__(256) void out_partial_kernel(Args a, int nseq) {
   }
 }
 
-// out[b, h, :] = sum over k slices of opart.  grid = ceil(nseq * H_q * d / 256).
+// out[b, h, :] = sum over k slices of opart, joined with the window's partial if there is one
+// (exact re-association of the softmax over {compressed tokens} + {window tokens}), and the
+// log-sum-exp.  grid = ceil(nseq * H_q * d / 256).
 template <typename TO>
 __global__ __launch_bounds__(256) void out_final_kernel(Args a, int nseq) {
   const int64_t n = (int64_t)nseq * a.H_q * a.d;
@@ -640,9 +657,23 @@ __global__ __launch_bounds__(256) void out_final_kernel(Args a, int nseq) {
   float v = 0.f;
 #pragma unroll 4
   for (int ks = 0; ks < a.k_slices; ++ks) v += a.opart[(int64_t)ks * n + idx];
+  const int64_t bh = idx / a.d;
+  const float M2 = a.y_ml[bh * 2], lY = a.y_ml[bh * 2 + 1];
+  float M = lY > 0.f ? M2 * 0.6931471805599453f : -INFINITY;     // natural-exponent units
+  float denom = lY;
+  if (a.win_po) {
+    const float mw = a.win_pml[bh * 2], lw = a.win_pml[bh * 2 + 1];
+    const float Mn = fmaxf(M, mw);
+    const float wy = lY > 0.f ? __expf(M - Mn) * lY : 0.f;
+    const float ww = lw > 0.f ? __expf(mw - Mn) : 0.f;
+    denom = wy + ww * lw;
+    v = (wy * v + ww * a.win_po[idx]) / denom;
+    M = Mn;
+  }
   TO* out = (TO*)a.out + a.out_seq0 * a.H_q * a.d;
   if constexpr (sizeof(TO) == 2) out[idx] = f32_to_bf16(v);
   else out[idx] = v;
+  if (a.lse && idx % a.d == 0) a.lse[a.out_seq0 * a.H_q + bh] = M + __logf(denom);
 }
 
 }  // namespace absorbed

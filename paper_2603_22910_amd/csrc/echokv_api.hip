@@ -541,7 +541,7 @@ int mlp_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_layer_ca
 
 // ---- weight-absorbed decode: workspace plan and launches ------------------
 struct AbsPlan {
-  size_t off_u, off_s, off_ml, off_yp, off_y, off_op, total;
+  size_t off_u, off_s, off_ml, off_yp, off_y, off_op, off_yml, total;
   int H_pad, n_col_a, n_col_tiles, k_slices, k_slice;
 };
 inline int abs_col_tiles(int width) { return (width + absorbed::kColTile - 1) / absorbed::kColTile; }
@@ -571,16 +571,28 @@ AbsPlan plan_absorbed(const Dims& dm, int nseq, int64_t slots, int64_t splits) {
   p.off_yp = o; o += align_up((size_t)splits * p.H_pad * dm.d_in * 4);
   p.off_y = o;  o += align_up((size_t)nseq * dm.H_q * dm.d_in * 4);
   p.off_op = o; o += align_up((size_t)p.k_slices * nseq * dm.H_q * dm.d * 4);
+  p.off_yml = o; o += align_up((size_t)nseq * dm.H_q * 2 * 4);
   p.total = o;
   return p;
+}
+// workspace of the absorbed modes: [extended weights (split head, value-absorbed mode only)]
+// [absorbed plan][window partial o, (max, sum)]
+size_t abs_pre_bytes(const Dims& dm) { return plan_ws(dm, 0, 0).total; }
+size_t abs_win_bytes(const Dims& dm, int nseq) {
+  return align_up((size_t)nseq * dm.H_q * dm.d * 4) + align_up((size_t)nseq * dm.H_q * 2 * 4);
 }
 // upper bound for any launch group of a batch holding total_tokens tokens
 size_t absorbed_ws_bytes(const Dims& dm, int batch, int64_t total_tokens) {
   const int n = std::min(batch, kMaxSeqPerLaunch);
-  return plan_absorbed(dm, n, total_tokens / kSlotTokens + n, total_tokens / 1024 + n).total;
+  return abs_pre_bytes(dm) + plan_absorbed(dm, n, total_tokens / kSlotTokens + n, total_tokens / 1024 + n).total +
+         abs_win_bytes(dm, n);
 }
+constexpr uint32_t kAbsModes = ECHOKV_FLAG_ABSORBED | ECHOKV_FLAG_ABSORB_V;
 bool absorbed_supported(const Dims& dm, uint32_t flags) {
-  return dm.bf16 && !(flags & (ECHOKV_FLAG_UNFUSED | ECHOKV_FLAG_W_PACKED | ECHOKV_FLAG_STAGED));
+  if (!dm.bf16 || (flags & (ECHOKV_FLAG_UNFUSED | ECHOKV_FLAG_W_PACKED | ECHOKV_FLAG_STAGED))) return false;
+  if ((flags & kAbsModes) == kAbsModes) return false;
+  if ((flags & ECHOKV_FLAG_ABSORB_V) && !fused_decode_supported<bf16_t>(dm.d, dm.G)) return false;
+  return true;
 }
 
 // Fills mt for group [b0, b0 + n) and returns (slots, splits, split_tokens) through the plan inputs.
@@ -604,19 +616,37 @@ size_t absorbed_need(const Dims& dm, const echokv_layer_cache* an) {
   for (int b0 = 0; b0 < an->batch; b0 += kMaxSeqPerLaunch) {
     SeqMeta mt; int slots, splits, ts;
     if (absorbed_group(dm, an, b0, mt, &slots, &splits, &ts)) return (size_t)-1;
-    need = std::max(need, plan_absorbed(dm, mt.n, slots, splits).total);
+    need = std::max(need, abs_pre_bytes(dm) + plan_absorbed(dm, mt.n, slots, splits).total + abs_win_bytes(dm, mt.n));
   }
   return need;
 }
 
-int absorbed_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_layer_cache* tg,
-                  const void* w_k, const void* w_v, const void* q, void* out, float* lse, char* ws,
-                  hipStream_t st) {
+// value_only: keys go through the fused predictor product (scores written out, rotary embedding
+// and window allowed); values are absorbed either way.
+int absorbed_impl(const Dims& dm, bool value_only, const echokv_layer_cache* an,
+                  const echokv_layer_cache* tg, const void* w_k, const void* w_v, const void* q,
+                  const echokv_decode_extras* ex, void* out, float* lse, char* ws0, hipStream_t st) {
+  typedef bf16_t T;
+  KvExtras kx;
+  if (ex) {
+    kx.rope_cos = ex->rope_cos; kx.rope_sin = ex->rope_sin;
+    if (ex->win_k) { kx.n_sink = ex->n_sink; kx.n_recent = ex->n_recent; }
+  }
+  const Window win = {kx.n_sink, kx.n_recent};
+  const WsPlan pre = plan_ws(dm, 0, 0);
+  const T* wk = (const T*)w_k; const T* wv_unused = nullptr;
+  if (value_only) {
+    int rcw = effective_weights<T>(dm, w_k, w_v, ws0, pre, &wk, &wv_unused, st);
+    if (rcw) return rcw;
+  }
+  char* ws = ws0 + pre.total;
   for (int b0 = 0; b0 < an->batch; b0 += kMaxSeqPerLaunch) {
     SeqMeta mt; int slots, splits, ts;
     int rc = absorbed_group(dm, an, b0, mt, &slots, &splits, &ts);
     if (rc) return rc;
     const AbsPlan pl = plan_absorbed(dm, mt.n, slots, splits);
+    float* win_po = (float*)(ws + pl.total);
+    float* win_pml = (float*)(ws + pl.total + align_up((size_t)mt.n * dm.H_q * dm.d * 4));
     absorbed::Args a;
     a.xa[0] = (const bf16_t*)an->k; a.xa[1] = (const bf16_t*)an->v;
     a.xr[0] = (const bf16_t*)tg->k; a.xr[1] = (const bf16_t*)tg->v;
@@ -624,6 +654,8 @@ int absorbed_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_lay
     a.q = (const bf16_t*)q + (int64_t)b0 * dm.H_q * dm.d;
     a.u = (bf16_t*)(ws + pl.off_u); a.s = (float*)(ws + pl.off_s); a.ml = (float*)(ws + pl.off_ml);
     a.ypart = (float*)(ws + pl.off_yp); a.y = (float*)(ws + pl.off_y); a.opart = (float*)(ws + pl.off_op);
+    a.y_ml = (float*)(ws + pl.off_yml); a.win = win;
+    a.win_po = win.on() ? win_po : nullptr; a.win_pml = win_pml;
     a.out = out; a.lse = lse; a.out_seq0 = b0;
     a.D = dm.D; a.m = dm.m; a.d_in = dm.d_in; a.d_out = dm.d_out; a.H_q = dm.H_q; a.H_pad = pl.H_pad;
     a.G = dm.G; a.d = dm.d;
@@ -638,14 +670,67 @@ int absorbed_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_lay
       if (!g_prof.get(&e0) || !g_prof.get(&e1)) return ECHOKV_ERR_HIP;
       HIP_TRY(hipEventRecord(e0, st));
     }
-    const dim3 qg((dm.d_in + 127) / 128, dm.H_kv);
-    if (dm.d == 128) hipLaunchKernelGGL((absorbed::absorb_q_kernel<128>), qg, dim3(256), 0, st, a, n);
-    else hipLaunchKernelGGL((absorbed::absorb_q_kernel<64>), qg, dim3(256), 0, st, a, n);
-    LAUNCH_CHECK();
-    // few workgroups: one per compute unit with a deeper pipeline; many: two per compute unit
-    if ((int64_t)slots * nhb <= 384) hipLaunchKernelGGL(absorbed::scores_kernel<4>, dim3(slots, nhb), dim3(256), 0, st, a, mt);
-    else hipLaunchKernelGGL(absorbed::scores_kernel<2>, dim3(slots, nhb), dim3(256), 0, st, a, mt);
-    LAUNCH_CHECK();
+    if (!value_only) {
+      const dim3 qg((dm.d_in + 127) / 128, dm.H_kv);
+      if (dm.d == 128) hipLaunchKernelGGL((absorbed::absorb_q_kernel<128>), qg, dim3(256), 0, st, a, n);
+      else hipLaunchKernelGGL((absorbed::absorb_q_kernel<64>), qg, dim3(256), 0, st, a, n);
+      LAUNCH_CHECK();
+      // few workgroups: one per compute unit with a deeper pipeline; many: two per compute unit
+      if ((int64_t)slots * nhb <= 384) hipLaunchKernelGGL(absorbed::scores_kernel<4>, dim3(slots, nhb), dim3(256), 0, st, a, mt);
+      else hipLaunchKernelGGL(absorbed::scores_kernel<2>, dim3(slots, nhb), dim3(256), 0, st, a, mt);
+      LAUNCH_CHECK();
+    } else {
+      // scores of the retained heads straight from the target cache, of the predicted heads from
+      // the fused predictor product; both in base-2 units, rotated by token position if asked
+      SeqMeta km = mt;
+      if (dm.g0 > 0) {
+        AttnArgs<T> ra;
+        ra.k = (const T*)tg->k; ra.v = nullptr; ra.ld = dm.m; ra.col0 = 0; ra.head0 = 0; ra.row_mode = 0;
+        ra.q = a.q; ra.H_q = dm.H_q; ra.G = dm.G; ra.d = dm.d; ra.scale = a.qscale;
+        ra.split_tokens = pick_split_tokens((int64_t)slots * kSlotTokens, dm.g0);
+        ra.part_o = nullptr; ra.part_ml = nullptr;
+        ra.rope_cos = kx.rope_cos; ra.rope_sin = kx.rope_sin;
+        const int tiles = fill_tiles(km, ra.split_tokens);
+        const int GT = (dm.G % 4 == 0) ? 4 : (dm.G % 2 == 0) ? 2 : 1;
+        dim3 grid(tiles, dm.g0 * (dm.G / GT));
+        constexpr int LPR64 = 8, LPR128 = 16;
+#define RS_CASE(LPR_, GT_) hipLaunchKernelGGL((row_scores_kernel<T, LPR_, GT_>), grid, dim3(256), 0, st, ra, a.s, (int64_t)a.s_ld, km)
+        if (dm.d == 64) {
+          if (GT == 4) RS_CASE(LPR64, 4); else if (GT == 2) RS_CASE(LPR64, 2); else RS_CASE(LPR64, 1);
+        } else {
+          if (GT == 4) RS_CASE(LPR128, 4); else if (GT == 2) RS_CASE(LPR128, 2); else RS_CASE(LPR128, 1);
+        }
+#undef RS_CASE
+        LAUNCH_CHECK();
+      }
+      if (dm.H_kv - dm.g0 > 0) {
+        rc = launch_fused_kscores<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, a.qscale,
+                                     (const T*)an->k, (const T*)tg->k, wk, a.q, a.s, a.s_ld, km, st, kx);
+        if (rc) return rc;
+      }
+      if (win.on()) {       // the window's tokens: one o-space partial per sequence
+        AttnArgs<T> wa;
+        wa.k = (const T*)ex->win_k; wa.v = (const T*)ex->win_v; wa.ld = dm.D; wa.col0 = 0; wa.head0 = 0;
+        wa.row_mode = 3; wa.q = a.q; wa.H_q = dm.H_q; wa.G = dm.G; wa.d = dm.d; wa.scale = dm.scale;
+        wa.split_tokens = kSlotTokens;
+        wa.part_o = win_po; wa.part_ml = win_pml;
+        wa.rope_cos = kx.rope_cos; wa.rope_sin = kx.rope_sin; wa.win = win;
+        wa.seq0 = b0; wa.win_slot0 = 0;
+        SeqMeta wm = mt;
+        for (int b = 0; b <= wm.n; ++b) wm.tbase[b] = b;
+        const int GT = (dm.G % 4 == 0) ? 4 : (dm.G % 2 == 0) ? 2 : 1;
+        dim3 grid(wm.n, dm.H_kv * (dm.G / GT));
+        constexpr int LPR64 = 8, LPR128 = 16;
+#define WIN_CASE(LPR_, GT_) hipLaunchKernelGGL((attn_split_kernel<T, LPR_, GT_>), grid, dim3(256), 0, st, wa, wm)
+        if (dm.d == 64) {
+          if (GT == 4) WIN_CASE(LPR64, 4); else if (GT == 2) WIN_CASE(LPR64, 2); else WIN_CASE(LPR64, 1);
+        } else {
+          if (GT == 4) WIN_CASE(LPR128, 4); else if (GT == 2) WIN_CASE(LPR128, 2); else WIN_CASE(LPR128, 1);
+        }
+#undef WIN_CASE
+        LAUNCH_CHECK();
+      }
+    }
     hipLaunchKernelGGL(absorbed::softmax_stats_kernel, dim3(dm.H_q, splits), dim3(256), 0, st, a, mt);
     LAUNCH_CHECK();
     hipLaunchKernelGGL(absorbed::pv_kernel, dim3(splits * pl.n_col_tiles, nhb), dim3(absorbed::kPvWaves * 64), 0, st, a, mt);
@@ -702,7 +787,7 @@ size_t echokv_workspace_bytes(const echokv_shape* shape, int32_t batch, int64_t 
   Dims dm;
   if (check_shape(shape, &dm) != ECHOKV_OK || batch <= 0 || total_tokens <= 0 || max_q < 0) return 0;
   size_t need = decode_ws_bytes(dm, batch, total_tokens, true);
-  if ((shape->flags & ECHOKV_FLAG_ABSORBED) && absorbed_supported(dm, shape->flags))
+  if ((shape->flags & kAbsModes) && absorbed_supported(dm, shape->flags))
     need = std::max(need, absorbed_ws_bytes(dm, batch, total_tokens));
   if (max_q > 1) need = std::max(need, prefill_ws_bytes(dm, total_tokens, max_q));
   return need;
@@ -768,7 +853,7 @@ int echokv_profile_stream_read(const void* buf, size_t bytes, int32_t repeats, d
       rc = ECHOKV_ERR_HIP;
     else if (r > 0 && (best == 0.f || ms < best)) best = ms;
   }
-  hipEventDestroy(e0); hipEventDestroy(e1);
+  (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
   if (rc) return rc;
   *gb_per_s = (double)n16 * 16 * blocks / (best * 1e-3) / 1e9;
   return ECHOKV_OK;
@@ -906,15 +991,18 @@ int echokv_decode_attn_ex(const echokv_shape* shape, const echokv_layer_cache* a
                           extras->n_sink + extras->n_recent < 1)) return ECHOKV_ERR_SHAPE;
     has_extras = extras->rope_cos || extras->win_k;
   }
-  if (shape->flags & ECHOKV_FLAG_ABSORBED) {
-    // a rotation between reconstruction and the dot product breaks the re-association of the keys
-    if (has_extras || !absorbed_supported(dm, shape->flags)) return ECHOKV_ERR_UNSUPPORTED;
+  if (shape->flags & kAbsModes) {
+    if (!absorbed_supported(dm, shape->flags)) return ECHOKV_ERR_UNSUPPORTED;
+    // a rotation between reconstruction and the dot product breaks the re-association of the
+    // keys: the extras need the value-only mode
+    const bool value_only = (shape->flags & ECHOKV_FLAG_ABSORB_V) != 0;
+    if (has_extras && !value_only) return ECHOKV_ERR_UNSUPPORTED;
     const size_t need = absorbed_need(dm, anchor);
     if (need == (size_t)-1) return ECHOKV_ERR_UNSUPPORTED;
     if (!workspace || workspace_bytes < need) return ECHOKV_ERR_WORKSPACE;
     if ((uintptr_t)workspace % 256) return ECHOKV_ERR_WORKSPACE;
-    return absorbed_impl(dm, anchor, target, w_k, w_v, q, out, lse_out, (char*)workspace,
-                         (hipStream_t)hip_stream);
+    return absorbed_impl(dm, value_only, anchor, target, w_k, w_v, q, has_extras ? extras : nullptr, out,
+                         lse_out, (char*)workspace, (hipStream_t)hip_stream);
   }
   if ((shape->flags & ECHOKV_FLAG_W_PACKED) &&
       (dm.r != 0 || (shape->flags & ECHOKV_FLAG_UNFUSED) || !dm.bf16 || !fused_decode_supported<bf16_t>(dm.d, dm.G)))

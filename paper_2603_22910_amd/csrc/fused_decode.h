@@ -52,6 +52,8 @@ struct Args {
   // keys by token position; tokens held by the uncompressed window are masked out here
   const float* rope_cos; const float* rope_sin;
   int32_t n_sink, n_recent;
+  float* s_out;          // score kernel only: S^T [H_q, s_ld], column = slot * 128 + token
+  int64_t s_ld;
 };
 
 // LDS tile: [rows][64 k] bf16, a row is 8 chunks of 16 bytes; chunk c of row r
@@ -525,9 +527,12 @@ __device__ __forceinline__ void score_tail(float (&s)[4], EpiSmem& e, int wave, 
   if (lane == 0) { e.ml[wave][pair][0] = mx; e.ml[wave][pair][1] = sum; }
 }
 
-template <int HD, bool ROPE>
-__device__ __forceinline__ void k_epilogue(floatx16_t (&acc)[4][4], EpiSmem& e, int G,
-                                           int wave, int lane, int jw0, int L, const KExtra& x) {
+// `tail(s, hw, g)` receives the lane-partial scores s[4] of head hw of the wave's tile and
+// query head g of its group (token ji * 32 + lane % 32; add the other lane half for the total).
+template <int HD, bool ROPE, class Tail>
+__device__ __forceinline__ void k_scores(floatx16_t (&acc)[4][4], EpiSmem& e, int G,
+                                         int wave, int lane, int jw0, int L, const KExtra& x,
+                                         Tail tail) {
   constexpr int HPW = WN / HD, CBH = HD / 32;
   const int wc = wave & 1, lr = lane & 31, lh = lane >> 5;
   if constexpr (!ROPE) {
@@ -553,7 +558,7 @@ __device__ __forceinline__ void k_epilogue(floatx16_t (&acc)[4][4], EpiSmem& e, 
             __builtin_amdgcn_sched_barrier(0);
           }
         }
-        score_tail(s, e, wave, lane, hw * G + g, jw0, x);
+        tail(s, hw, g);
       }
     }
   } else {
@@ -620,9 +625,17 @@ __device__ __forceinline__ void k_epilogue(floatx16_t (&acc)[4][4], EpiSmem& e, 
       }
 #pragma unroll
       for (int g = 0; g < MAXPAIR; ++g)
-        if (g < G) score_tail(s[g], e, wave, lane, hw * G + g, jw0, x);
+        if (g < G) tail(s[g], hw, g);
     }
   }
+}
+
+// Scores -> this wave's softmax numerators in LDS (the fused kernel's score epilogue).
+template <int HD, bool ROPE>
+__device__ __forceinline__ void k_epilogue(floatx16_t (&acc)[4][4], EpiSmem& e, int G,
+                                           int wave, int lane, int jw0, int L, const KExtra& x) {
+  k_scores<HD, ROPE>(acc, e, G, wave, lane, jw0, L, x,
+                     [&](float (&s)[4], int hw, int g) { score_tail(s, e, wave, lane, hw * G + g, jw0, x); });
 }
 
 // After the V pass: acc[ji][ci] holds V_hat (rows = tokens, lanes = head dims).
@@ -715,6 +728,51 @@ __global__ __launch_bounds__(NTHREADS) void fused_decode_kernel(Args a, SeqMeta 
   if (jw0 >= L) return;                          // wave has no valid token: no partial
   v_epilogue<HD>(acc, sm.e, a.G, wave, lane, meta.sbase[b] + jw0 / kSlotTokens, a.H_q,
                  a.n_ret_heads + (n0 + wc * WN) / HD, a.part_o, a.part_ml);
+}
+
+// Key half of the fused kernel on its own: K_hat^T of the tile, then the scaled scores of
+// every (head, query head) of the tile written to S^T (base-2 logits: the caller folds log2 e
+// into the scale).  Used when the value side is evaluated in the other association order
+// (sum_j p_j x^V_j first, W_V afterwards), which stays valid under a rotary embedding.
+template <int HD, bool ROPE>
+__global__ __launch_bounds__(NTHREADS) void fused_kscores_kernel(Args a, SeqMeta meta) {
+  __shared__ Smem sm;
+  char* smem = reinterpret_cast<char*>(&sm);
+  int ttile, ctile;
+  if (!tile_of_block(a, ttile, ctile)) return;
+  const int b = find_seq(meta.tbase, meta.n, ttile);
+  const int L = meta.len[b];
+  const int j0 = (ttile - meta.tbase[b]) * BM;
+  const int n0 = ctile * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wt = wave >> 1, wc = wave & 1, lr = lane & 31, lh = lane >> 5;
+  const int last = min(BM, L - j0) - 1;
+  const int64_t row0 = meta.start[b] + j0;
+  const int nclamp = a.d_out - n0 - 8;
+  load_queries<HD>(sm.e, a.q, b, a.H_q, a.G, a.n_ret_heads + n0 / HD, a.scale, tid);
+  floatx16_t acc[4][4];
+  Stage sa, sb;
+  PassIo io;
+  make_io(io, a, a.xa[0] + row0 * a.D, a.xr[0] + row0 * a.m, a.w[0] + n0, last, nclamp, tid,
+          (ttile * 3) % ((a.D + a.m) / BK));
+  pass_prefetch<false>(sa, io, a);
+  gemm_pass<true, false>(acc, smem, a, io, sa, sb, tid);
+  const int jw0 = j0 + wt * WM;
+  if (jw0 >= L) return;
+  constexpr int HPW = WN / HD;
+  const int kvh0 = a.n_ret_heads + (n0 + wc * WN) / HD;       // first KV head of this wave's columns
+  const int H_kv = a.H_q / a.G;
+  float* srow = a.s_out + (int64_t)meta.sbase[b] * kSlotTokens + jw0 + lr;
+  KExtra x = make_kextra(a.rope_cos, a.rope_sin, 0, 0, L);
+  k_scores<HD, ROPE>(acc, sm.e, a.G, wave, lane, jw0, L, x, [&](float (&s)[4], int hw, int g) {
+    if (kvh0 + hw >= H_kv) return;
+    float* dst = srow + (int64_t)((kvh0 + hw) * a.G + g) * a.s_ld;
+#pragma unroll
+    for (int ji = 0; ji < 4; ++ji) {
+      const float v = s[ji] + __shfl_xor(s[ji], 32, 64);
+      if (lh == 0 && jw0 + ji * 32 + lr < L) dst[ji * 32] = v;
+    }
+  });
 }
 
 // Stand-alone predictor product (Eq. 3) with the same main loop: K_hat or V_hat
@@ -813,6 +871,7 @@ inline int launch_fused_decode(int H_q, int H_kv, int d, int m, int d_out, int n
   } else {
     fused::Args a;
     a.rope_cos = ex.rope_cos; a.rope_sin = ex.rope_sin; a.n_sink = ex.n_sink; a.n_recent = ex.n_recent;
+    a.s_out = nullptr; a.s_ld = 0;
     a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk; a.w[1] = wv;
     a.q = q; a.part_o = part_o; a.part_ml = part_ml;
     a.out[0] = a.out[1] = nullptr; a.ldo = 0; a.col0 = 0;
@@ -838,6 +897,37 @@ inline int launch_fused_decode(int H_q, int H_kv, int d, int m, int d_out, int n
   }
 }
 
+// Scores of the predicted heads -> s_out (see fused_kscores_kernel).  `scale` must already
+// include log2(e).
+template <typename T>
+inline int launch_fused_kscores(int H_q, int H_kv, int d, int m, int d_out, int n_ret_heads,
+                                float scale, const T* ka, const T* kr, const T* wk, const T* q,
+                                float* s_out, int64_t s_ld, SeqMeta& mt, hipStream_t st,
+                                const KvExtras& ex = KvExtras()) {
+  if constexpr (sizeof(T) != 2) {
+    return 6;
+  } else {
+    fused::Args a;
+    a.xa[0] = a.xa[1] = ka; a.xr[0] = a.xr[1] = kr; a.w[0] = a.w[1] = wk;
+    a.q = q; a.part_o = nullptr; a.part_ml = nullptr;
+    a.out[0] = a.out[1] = nullptr; a.ldo = 0; a.col0 = 0;
+    a.D = H_kv * d; a.m = m; a.d_out = d_out; a.H_q = H_q; a.G = H_q / H_kv;
+    a.n_ret_heads = n_ret_heads; a.scale = scale;
+    a.rope_cos = ex.rope_cos; a.rope_sin = ex.rope_sin; a.n_sink = 0; a.n_recent = 0;
+    a.s_out = s_out; a.s_ld = s_ld;
+    a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;
+    a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
+    const dim3 g(((a.n_tiles + 7) / 8) * 8), blk(fused::NTHREADS);
+    const bool rope = ex.rope_cos != nullptr;
+    if (d == 128 && rope) hipLaunchKernelGGL((fused::fused_kscores_kernel<128, true>), g, blk, 0, st, a, mt);
+    else if (d == 128) hipLaunchKernelGGL((fused::fused_kscores_kernel<128, false>), g, blk, 0, st, a, mt);
+    else if (rope) hipLaunchKernelGGL((fused::fused_kscores_kernel<64, true>), g, blk, 0, st, a, mt);
+    else hipLaunchKernelGGL((fused::fused_kscores_kernel<64, false>), g, blk, 0, st, a, mt);
+    if (hipGetLastError() != hipSuccess) return 7;
+    return 0;
+  }
+}
+
 // K_hat and V_hat of the sequences in `mt` -> out_k / out_v [rows, ldo] at
 // column col0, output row = sbase[b]*kSlotTokens + j.  d_out = width of W.
 template <typename T>
@@ -850,7 +940,7 @@ inline int launch_recon_mfma(int D, int m, int d_out, const T* ka, const T* va, 
     fused::Args a;
     a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk; a.w[1] = wv;
     a.q = nullptr; a.part_o = nullptr; a.part_ml = nullptr;
-    a.rope_cos = a.rope_sin = nullptr; a.n_sink = a.n_recent = 0;
+    a.rope_cos = a.rope_sin = nullptr; a.n_sink = a.n_recent = 0; a.s_out = nullptr; a.s_ld = 0;
     a.out[0] = out_k; a.out[1] = out_v; a.ldo = ldo; a.col0 = col0;
     a.D = D; a.m = m; a.d_out = d_out; a.H_q = 0; a.G = 1; a.n_ret_heads = 0; a.scale = 0.f;
     a.n_col_tiles = (a.d_out + fused::BN - 1) / fused::BN;

@@ -239,6 +239,7 @@ inline int launch_fused_decode_dma(int H_q, int H_kv, int d, int m, int d_out, i
                                    const KvExtras& ex = KvExtras()) {
   fused::Args a;
   a.rope_cos = ex.rope_cos; a.rope_sin = ex.rope_sin; a.n_sink = ex.n_sink; a.n_recent = ex.n_recent;
+  a.s_out = nullptr; a.s_ld = 0;
   a.xa[0] = ka; a.xa[1] = va; a.xr[0] = kr; a.xr[1] = vr; a.w[0] = wk_packed; a.w[1] = wv_packed;
   a.q = q; a.part_o = part_o; a.part_ml = part_ml;
   a.out[0] = a.out[1] = nullptr; a.ldo = 0; a.col0 = 0;

@@ -407,6 +407,78 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs<T> a, SeqMeta 
 }
 
 // ---------------------------------------------------------------------------
+// Scores only, over heads stored as rows (the target layer's retained heads):
+// S^T[h, slot * 128 + j] = scale * q_h . rot_j(k_j) for GT query heads of one KV
+// head over one chunk of tokens; base-2 logits if the caller folds log2(e) into
+// the scale.  Same row / lane layout and the same rotary handling as
+// attn_split_kernel.  grid.x = chunks (tbase), grid.y = kv heads * (G / GT).
+// ---------------------------------------------------------------------------
+template <typename T, int LPR, int GT>
+__global__ __launch_bounds__(256) void row_scores_kernel(AttnArgs<T> a, float* s_out, int64_t s_ld,
+                                                         SeqMeta meta) {
+  constexpr int VEC = Elem<T>::kVec;
+  constexpr int RPW = 64 / LPR, NRG = 4 * RPW;
+  const int b = find_seq(meta.tbase, meta.n, blockIdx.x);
+  const int chunk = blockIdx.x - meta.tbase[b];
+  const int L = meta.len[b];
+  const int gchunks = a.G / GT;
+  const int hl = blockIdx.y / gchunks;
+  const int qh0 = (a.head0 + hl) * a.G + (blockIdx.y % gchunks) * GT;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rg = wave * RPW + lane / LPR, li = lane % LPR;
+  const int64_t row0 = meta.start[b];
+  const int col = a.col0 + hl * a.d + li * VEC;
+  const int jbeg = chunk * a.split_tokens, jend = min(L, jbeg + a.split_tokens);
+  const bool rope = a.rope_cos != nullptr;
+  const int hc = (li % (LPR / 2)) * VEC;
+  float qv[GT][VEC];
+#pragma unroll
+  for (int g = 0; g < GT; ++g) {
+    load16<T>(a.q + ((int64_t)b * a.H_q + qh0 + g) * a.d + li * VEC, qv[g]);
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) qv[g][i] *= a.scale;
+  }
+  float* dst = s_out + (int64_t)qh0 * s_ld + (int64_t)meta.sbase[b] * kSlotTokens;
+  constexpr int UN = 4;
+  for (int j = jbeg + rg; j < jend; j += NRG * UN) {
+    float kv[UN][VEC];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int jj = min(j + u * NRG, jend - 1);
+      load16<T>(a.k + (row0 + jj) * a.ld + col, kv[u]);
+      if (rope) {
+        float cs[VEC], sn[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) {
+          const float4 c4 = *reinterpret_cast<const float4*>(a.rope_cos + (int64_t)jj * (a.d / 2) + hc + i);
+          const float4 s4 = *reinterpret_cast<const float4*>(a.rope_sin + (int64_t)jj * (a.d / 2) + hc + i);
+          cs[i] = c4.x; cs[i + 1] = c4.y; cs[i + 2] = c4.z; cs[i + 3] = c4.w;
+          sn[i] = s4.x; sn[i + 1] = s4.y; sn[i + 2] = s4.z; sn[i + 3] = s4.w;
+        }
+        const float sgn = (li < LPR / 2) ? -1.f : 1.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+          const float other = __shfl_xor(kv[u][i], LPR / 2, 64);
+          kv[u][i] = fmaf(kv[u][i], cs[i], sgn * other * sn[i]);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int jj = j + u * NRG;
+#pragma unroll
+      for (int g = 0; g < GT; ++g) {
+        float sc = 0.f;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) sc = fmaf(qv[g][i], kv[u][i], sc);
+        sc = wave_sum(sc, LPR);
+        if (li == 0 && jj < jend) dst[(int64_t)g * s_ld + jj] = sc;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Merge of the split partials of one (sequence, query head): exact
 // re-association of the softmax-weighted sum.  Heads below `n_stream_heads`
 // (in KV-head units) were written every `stream_step` slots, the others every

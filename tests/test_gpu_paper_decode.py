@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 TOL = {"bf16": (2e-2, 5e-3), "f32": (1e-5, 1e-5)}
 MODES = [pytest.param(0, id="fused"), pytest.param(ek.FLAG_UNFUSED, id="unfused"),
-         pytest.param(-1, id="packed")]
+         pytest.param(-1, id="packed"), pytest.param(ek.FLAG_ABSORB_V, id="absorb_v")]
 
 
 def host(t):
@@ -37,6 +37,8 @@ def run(w, flags, use_rope, use_window, n_sink=4, n_recent=128):
         dw.pack_weights()
         dw.W_K, dw.W_V = dw.W_K_packed, dw.W_V_packed
     else:
+        if flags & ek.FLAG_ABSORB_V and w.dtype != "bf16":
+            pytest.skip("value-absorbed decode: bf16 caches only")
         dw = DeviceWorkload(inp, flags=flags)
     rope = synth.rope_tables(w.head_dim, max(inp.seq_len[:inp.n_decode]) + 3) if use_rope else None
     window = (*synth.window_rows(inp, n_sink, n_recent), n_sink, n_recent) if use_window else None
@@ -69,18 +71,20 @@ def test_decode_extras_shapes(H_q, H_kv, d, m, dtype, flags, use_rope, use_windo
     run(w, flags, use_rope, use_window)
 
 
-@pytest.mark.parametrize("L", [1, 3, 4, 5, 131, 132, 133, 134, 259, 260, 261, 400])
-def test_window_boundaries(L):
+@pytest.mark.parametrize("flags", [pytest.param(0, id="fused"), pytest.param(ek.FLAG_ABSORB_V, id="absorb_v")])
+@pytest.mark.parametrize("L", [1, 3, 4, 5, 131, 132, 133, 134, 259, 260, 261, 400, 1030])
+def test_window_boundaries(L, flags):
     """Lengths around n_sink, n_sink + n_recent and the tile size: everything in the
     window, exactly one compressed token, ring wrap-around."""
     w = synth.Workload(f"pw_L{L}", "bf16", 8, 4, 128, 256, seed=500 + L, seq_lens=(L, max(1, L - 1)))
-    run(w, 0, True, True)
+    run(w, flags, True, True)
 
 
+@pytest.mark.parametrize("flags", [pytest.param(0, id="fused"), pytest.param(ek.FLAG_ABSORB_V, id="absorb_v")])
 @pytest.mark.parametrize("n_sink,n_recent", [(0, 64), (4, 0), (1, 1), (16, 200)])
-def test_window_sizes(n_sink, n_recent):
+def test_window_sizes(n_sink, n_recent, flags):
     w = synth.Workload(f"pw_{n_sink}_{n_recent}", "bf16", 8, 4, 128, 256, seed=41, seq_lens=(500, 17, 230))
-    run(w, 0, False, True, n_sink, n_recent)
+    run(w, flags, False, True, n_sink, n_recent)
 
 
 def test_extras_null_equals_plain_decode():
@@ -138,10 +142,11 @@ def test_window_append_keeps_the_ring_current():
                 assert torch.equal(wv[b, r], full_v[b][p]), (b, p)
 
 
-def test_decode_extras_batch_above_one_launch():
+@pytest.mark.parametrize("flags", [pytest.param(0, id="fused"), pytest.param(ek.FLAG_ABSORB_V, id="absorb_v")])
+def test_decode_extras_batch_above_one_launch(flags):
     lens = tuple(1 + (53 * i) % 400 for i in range(140))
     w = synth.Workload("px_b140", "bf16", 4, 2, 128, 128, seed=78, seq_lens=lens)
-    run(w, 0, True, True)
+    run(w, flags, True, True)
 
 
 def test_decode_extras_full_size_sampled():
@@ -152,10 +157,12 @@ def test_decode_extras_full_size_sampled():
     inp = synth.generate(w)
     rope = synth.rope_tables(w.head_dim, 32768)
     window = (*synth.window_rows(inp, 4, 128), 4, 128)
-    dw = DeviceWorkload(inp)
-    out, lse = dw.decode_ex(rope, window); torch.cuda.synchronize()
-    got = host(out)
-    assert np.isfinite(got).all()
+    dw = DeviceWorkload(inp, flags=ek.FLAG_ABSORB_V)       # workspace sized for both paths
     o_ref, l_ref = ref.decode_paper_ref(inp, rope, window)
-    check(got, o_ref, "bf16", "cfg3-shaped 32K rope+window")
-    assert np.abs(host(lse) - l_ref).max() <= 2e-2
+    for name, fl in (("fused", 0), ("absorb_v", ek.FLAG_ABSORB_V)):
+        dw.set_flags(fl)
+        out, lse = dw.decode_ex(rope, window); torch.cuda.synchronize()
+        got = host(out)
+        assert np.isfinite(got).all()
+        check(got, o_ref, "bf16", f"cfg3-shaped 32K rope+window, {name}")
+        assert np.abs(host(lse) - l_ref).max() <= 2e-2

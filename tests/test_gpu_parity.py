@@ -20,7 +20,8 @@ PACKED = 1 << 20       # test-only marker: weights re-laid out once by echokv_pa
 MODES = [pytest.param(0, id="fused"), pytest.param(ek.FLAG_UNFUSED, id="unfused"),
          pytest.param(PACKED, id="packed"),
          pytest.param(PACKED | ek.FLAG_STAGED, id="packed_staged"),
-         pytest.param(ek.FLAG_ABSORBED, id="absorbed")]
+         pytest.param(ek.FLAG_ABSORBED, id="absorbed"),
+         pytest.param(ek.FLAG_ABSORB_V, id="absorb_v")]
 
 
 def check(got, want, dtype, what=""):
@@ -44,7 +45,7 @@ def make_dw(inp, flags, **kw):
         dw.pack_weights()
         dw.shape.flags |= flags & ek.FLAG_STAGED
         return dw
-    if flags & ek.FLAG_ABSORBED and inp.w.dtype != "bf16":
+    if flags & (ek.FLAG_ABSORBED | ek.FLAG_ABSORB_V) and inp.w.dtype != "bf16":
         pytest.skip("weight-absorbed decode: bf16 caches only")
     return DeviceWorkload(inp, flags=flags, **kw)
 
