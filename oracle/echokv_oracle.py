@@ -468,3 +468,26 @@ def mlp_param_matched_hidden(D: int, m: int, multiple: int = 64) -> int:
     d_in, d_out = predictor_dims(D, m)
     h = d_in * d_out / (d_in + d_out)
     return max(multiple, int(round(h / multiple)) * multiple)
+
+
+# --------------------------------------------------------------------------
+# stage-1 fit of the linear predictor (Sec. "Training Details", the
+# reconstruction loss || C_hat_drop - C_drop ||^2): for a linear map the
+# minimiser has a closed form, the least-squares solution
+# --------------------------------------------------------------------------
+def fit_linear(C_anchor: np.ndarray, C_target_full: np.ndarray, m: int, ridge: float = 0.0) -> np.ndarray:
+    """W [D + m, D - m] = argmin || [C_anchor ; C_target[:, :m]] W - C_target[:, m:] ||_F^2
+    + ridge ||W||_F^2 over the given token rows."""
+    C_a = np.asarray(C_anchor, F64); C_t = np.asarray(C_target_full, F64)
+    X = predictor_input(C_a, C_t[:, :m])
+    Y = C_t[:, m:]
+    if ridge == 0.0:
+        return np.linalg.lstsq(X, Y, rcond=None)[0]
+    return np.linalg.solve(X.T @ X + ridge * np.eye(X.shape[1]), X.T @ Y)
+
+
+def reconstruction_loss(C_anchor, C_target_full, m: int, W) -> float:
+    """Mean squared error of the rebuilt dims (the stage-1 loss per element)."""
+    C_t = np.asarray(C_target_full, F64)
+    C_hat = predictor_input(C_anchor, C_t[:, :m]) @ np.asarray(W, F64)
+    return float(np.mean((C_hat - C_t[:, m:]) ** 2))

@@ -701,3 +701,35 @@ def test_mlp_param_matched_width():
     h = orc.mlp_param_matched_hidden(4096, 2048)
     d_in, d_out = 6144, 2048
     assert h % 64 == 0 and abs(h * (d_in + d_out) - d_in * d_out) <= 32 * (d_in + d_out)
+
+
+# ---- P16: closed-form stage-1 fit of the linear predictor -------------------------
+def test_fit_recovers_a_planted_predictor_and_is_the_library_least_squares():
+    r = np.random.default_rng(21)
+    T, D, m = 200, 12, 4
+    A = r.standard_normal((T, D)); T_m = r.standard_normal((T, m))
+    W0 = r.standard_normal((D + m, D - m))
+    C_t = np.concatenate([T_m, np.concatenate([A, T_m], axis=1) @ W0], axis=1)     # noise-free target
+    W = orc.fit_linear(A, C_t, m)
+    np.testing.assert_allclose(W, W0, rtol=1e-9, atol=1e-10)
+    assert orc.reconstruction_loss(A, C_t, m, W) < 1e-20
+    # with noise: the normal equations hold (residual orthogonal to every input column)
+    C_n = C_t + 0.3 * r.standard_normal(C_t.shape)
+    Wn = orc.fit_linear(A, C_n, m)
+    X = np.concatenate([A, C_n[:, :m]], axis=1)
+    assert np.abs(X.T @ (X @ Wn - C_n[:, m:])).max() < 1e-9
+    np.testing.assert_allclose(Wn, np.linalg.lstsq(X, C_n[:, m:], rcond=None)[0], rtol=1e-10, atol=1e-12)
+    # any other W has a larger loss
+    assert orc.reconstruction_loss(A, C_n, m, Wn) < orc.reconstruction_loss(A, C_n, m, Wn + 1e-3)
+
+
+def test_fit_ridge_closed_form_scalar_case():
+    # one input, one output: w = sum(x y) / (sum(x x) + ridge); take m = 0, D = 1 is impossible
+    # (nothing to predict), so D = 2, m = 1 with a zero anchor: inputs are [0, 0, t0] -> only t0 counts
+    t0 = np.array([1.0, 2.0, 3.0]); y = np.array([2.0, 3.9, 6.2])
+    C_t = np.stack([t0, y], axis=1)
+    A = np.zeros((3, 2))
+    for ridge in (0.5, 2.0):
+        W = orc.fit_linear(A, C_t, 1, ridge=ridge)
+        assert abs(W[2, 0] - (t0 @ y) / (t0 @ t0 + ridge)) < 1e-12
+        assert abs(W[0, 0]) < 1e-15 and abs(W[1, 0]) < 1e-15
