@@ -245,6 +245,29 @@ int echokv_decode_attn_mlp(const echokv_shape *shape, const echokv_layer_cache *
                            float *lse_out, void *workspace, size_t workspace_bytes,
                            void *hip_stream);
 
+/* Closed-form fit of a linear predictor to the stage-1 reconstruction loss
+ * (Sec. "Training Details": || C_hat_drop - C_drop ||^2).  For a linear map the
+ * minimiser is the least-squares solution
+ *   W = argmin || [C_global ; C_local] W - C_drop ||_F^2 + ridge ||W||_F^2
+ * over n_rows token rows.  The Gram matrices X^T X and X^T C_drop are formed on
+ * MFMA (bf16 inputs, fp32 accumulation) and the normal equations are solved by
+ * conjugate gradients in fp32 on the GPU (one step length for all columns).
+ *   anchor_rows : device [n_rows, D] bf16, the anchor layer's rows (K or V)
+ *   target_rows : device [n_rows, D] bf16, the target layer's FULL rows of the same
+ *                 tokens (first m dims = C_local, the rest = C_drop)
+ *   n_rows      : multiple of 64
+ *   w_out       : device [D + m, D - m] bf16
+ *   max_iters, tol : stop after max_iters steps or once ||residual||_F <= tol ||X^T C_drop||_F
+ *   iters_out, rel_residual_out : HOST, optional
+ * A training-side utility: synchronous (it reads two scalars back per step).
+ * bf16 only; workspace from echokv_fit_workspace_bytes. */
+size_t echokv_fit_workspace_bytes(const echokv_shape *shape, int64_t n_rows);
+int echokv_fit_linear(const echokv_shape *shape, const void *anchor_rows,
+                      const void *target_rows, int64_t n_rows, float ridge,
+                      int32_t max_iters, float tol, void *w_out, void *workspace,
+                      size_t workspace_bytes, int32_t *iters_out,
+                      float *rel_residual_out, void *hip_stream);
+
 /* Causal chunk of T_q queries of sequence `seq` (Eq. 7 with a causal mask):
  * query i sits at position q_pos0 + i and attends cached tokens
  * 0 .. q_pos0 + i inclusive, all read from the compressed cache (predicted

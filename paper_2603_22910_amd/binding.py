@@ -27,7 +27,7 @@ EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn",
            "echokv_profile_enable", "echokv_profile_read", "echokv_pack_weights",
            "echokv_cache_compress", "echokv_decode_attn_ex", "echokv_window_append",
-           "echokv_mlp_workspace_bytes", "echokv_decode_attn_mlp", "echokv_profile_stream_read")
+           "echokv_mlp_workspace_bytes", "echokv_decode_attn_mlp", "echokv_profile_stream_read", "echokv_fit_workspace_bytes", "echokv_fit_linear")
 ACT_RELU, ACT_SILU = 1, 2
 
 
@@ -97,6 +97,12 @@ def load() -> C.CDLL:
                                            C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                            C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.echokv_fit_workspace_bytes.restype = C.c_size_t
+    lib.echokv_fit_workspace_bytes.argtypes = [C.POINTER(Shape), C.c_int64]
+    lib.echokv_fit_linear.restype = C.c_int
+    lib.echokv_fit_linear.argtypes = [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int64, C.c_float,
+                                      C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,
+                                      C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_void_p]
     lib.echokv_window_append.restype = C.c_int
     lib.echokv_window_append.argtypes = [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_void_p,
@@ -263,6 +269,21 @@ def decode_attn_mlp(shape: Shape, anchor: LayerCache, target: LayerCache, w1_k, 
                                          _stream(stream)), "echokv_decode_attn_mlp")
 
 
+def fit_workspace_bytes(shape: Shape, n_rows: int) -> int:
+    return int(load().echokv_fit_workspace_bytes(C.byref(shape), int(n_rows)))
+
+
+def fit_linear(shape: Shape, anchor_rows, target_rows, n_rows: int, w_out, workspace, ridge: float = 0.0,
+               max_iters: int = 200, tol: float = 1e-5, stream=None):
+    """Returns (iterations, relative residual of the normal equations)."""
+    it, res = C.c_int32(0), C.c_float(0.0)
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load().echokv_fit_linear(C.byref(shape), _ptr(anchor_rows), _ptr(target_rows), int(n_rows),
+                                    float(ridge), int(max_iters), float(tol), _ptr(w_out), _ptr(workspace),
+                                    nbytes, C.byref(it), C.byref(res), _stream(stream)), "echokv_fit_linear")
+    return int(it.value), float(res.value)
+
+
 def window_append(shape: Shape, win_k, win_v, n_sink: int, n_recent: int, seq_len_before, k_new,
                   v_new, n_new, stream=None):
     before = np.ascontiguousarray(seq_len_before, dtype=np.int32)
@@ -293,7 +314,7 @@ def profile_stream_read(buf, repeats: int = 5) -> float:
     """GB/s a plain streaming-read kernel reaches over the tensor `buf`."""
     out = C.c_double(0.0)
     _check(load().echokv_profile_stream_read(_ptr(buf), buf.numel() * buf.element_size(), int(repeats),
-                                             C.byref(out)), "echokv_profile_stream_read")
+                                             C.byref(out)), "echokv_profile_stream_read", "echokv_fit_workspace_bytes", "echokv_fit_linear")
     return float(out.value)
 
 

@@ -16,6 +16,7 @@
 #include "fused_decode_dma.h"
 #include "prefill_kernels.h"
 #include "absorbed_decode.h"
+#include "fit_kernels.h"
 
 using namespace echokv;
 
@@ -803,8 +804,8 @@ int echokv_pack_weights(const echokv_shape* shape, const void* w, void* w_packed
   if (w == w_packed) return ECHOKV_ERR_SHAPE;
   hipStream_t st = (hipStream_t)hip_stream;
   dim3 grid((dm.d_out + 63) / 64, (dm.d_in + 63) / 64);
-  if (dm.bf16) hipLaunchKernelGGL((transpose_kernel<bf16_t>), grid, dim3(256), 0, st, (const bf16_t*)w, (bf16_t*)w_packed, dm.d_in, dm.d_out);
-  else hipLaunchKernelGGL((transpose_kernel<float>), grid, dim3(256), 0, st, (const float*)w, (float*)w_packed, dm.d_in, dm.d_out);
+  if (dm.bf16) hipLaunchKernelGGL((transpose_kernel<bf16_t>), grid, dim3(256), 0, st, (const bf16_t*)w, (bf16_t*)w_packed, dm.d_in, dm.d_out, (int64_t)dm.d_out);
+  else hipLaunchKernelGGL((transpose_kernel<float>), grid, dim3(256), 0, st, (const float*)w, (float*)w_packed, dm.d_in, dm.d_out, (int64_t)dm.d_out);
   LAUNCH_CHECK();
   return ECHOKV_OK;
 }
@@ -1104,6 +1105,156 @@ int echokv_decode_attn_mlp(const echokv_shape* shape, const echokv_layer_cache* 
   return mlp_impl(dm, anchor, target, (const bf16_t*)w1_k, (const bf16_t*)w2_k, (const bf16_t*)w1_v,
                   (const bf16_t*)w2_v, hidden, activation, (const bf16_t*)q, out, lse_out,
                   (char*)workspace, (hipStream_t)hip_stream);
+}
+
+// ---- closed-form fit of the linear predictor (stage-1 reconstruction loss) -----------------
+struct FitPlan { size_t off_xt, off_ga, off_gt, off_g, off_b, off_w, off_r, off_p, off_ap, off_part, total; };
+static FitPlan plan_fit(const Dims& dm, int64_t n_rows) {
+  FitPlan p;
+  size_t o = 0;
+  const size_t wn = (size_t)dm.d_in * dm.d_out * 4;
+  p.off_xt = o; o += align_up((size_t)dm.d_in * n_rows * 2);
+  p.off_ga = o; o += align_up((size_t)dm.d_in * dm.D * 4);
+  p.off_gt = o; o += align_up((size_t)dm.d_in * dm.D * 4);
+  p.off_g = o;  o += align_up((size_t)dm.d_in * dm.d_in * 4);
+  p.off_b = o;  o += align_up(wn);
+  p.off_w = o;  o += align_up(wn);
+  p.off_r = o;  o += align_up(wn);
+  p.off_p = o;  o += align_up(wn);
+  p.off_ap = o; o += align_up(wn);
+  p.off_part = o; o += align_up((size_t)fit::kDotBlocks * 4);
+  p.total = o;
+  return p;
+}
+static int check_fit(const Dims& dm, int64_t n_rows) {
+  if (!dm.bf16) return ECHOKV_ERR_UNSUPPORTED;
+  if (dm.d_out == 0) return ECHOKV_ERR_SHAPE;
+  if (n_rows < 64 || n_rows % 64) return ECHOKV_ERR_SHAPE;
+  // the Gram product addresses each [n_rows, D] matrix through one 2 GB buffer window
+  if (n_rows * (int64_t)dm.D * 2 >= ((int64_t)1 << 31)) return ECHOKV_ERR_UNSUPPORTED;
+  return ECHOKV_OK;
+}
+
+size_t echokv_fit_workspace_bytes(const echokv_shape* shape, int64_t n_rows) {
+  Dims dm;
+  if (check_shape(shape, &dm) != ECHOKV_OK || check_fit(dm, n_rows) != ECHOKV_OK) return 0;
+  return plan_fit(dm, n_rows).total;
+}
+
+int echokv_fit_linear(const echokv_shape* shape, const void* anchor_rows, const void* target_rows,
+                      int64_t n_rows, float ridge, int32_t max_iters, float tol, void* w_out,
+                      void* workspace, size_t workspace_bytes, int32_t* iters_out,
+                      float* rel_residual_out, void* hip_stream) {
+  Dims dm;
+  int rc = check_shape(shape, &dm);
+  if (rc) return rc;
+  rc = check_fit(dm, n_rows);
+  if (rc) return rc;
+  if (!anchor_rows || !target_rows || !w_out) return ECHOKV_ERR_NULL;
+  if (!(ridge >= 0.f) || max_iters < 1 || !(tol > 0.f)) return ECHOKV_ERR_SHAPE;
+  const FitPlan pl = plan_fit(dm, n_rows);
+  if (!workspace || workspace_bytes < pl.total || (uintptr_t)workspace % 256) return ECHOKV_ERR_WORKSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  char* ws = (char*)workspace;
+  typedef bf16_t T;
+  const T* A = (const T*)anchor_rows; const T* Tt = (const T*)target_rows;
+  T* xt = (T*)(ws + pl.off_xt);
+  float* ga = (float*)(ws + pl.off_ga); float* gt = (float*)(ws + pl.off_gt);
+  float* G = (float*)(ws + pl.off_g); float* B = (float*)(ws + pl.off_b);
+  float* W = (float*)(ws + pl.off_w); float* R = (float*)(ws + pl.off_r);
+  float* P = (float*)(ws + pl.off_p); float* AP = (float*)(ws + pl.off_ap);
+  float* part = (float*)(ws + pl.off_part);
+  const int T_rows = (int)n_rows;
+  const int64_t wn = (int64_t)dm.d_in * dm.d_out;
+
+  // 1. X^T [d_in, n_rows]: the anchor columns, then the target's first m columns (Eq. 3 order)
+  hipLaunchKernelGGL((transpose_kernel<T>), dim3((dm.D + 63) / 64, (T_rows + 63) / 64), dim3(256), 0, st,
+                     A, xt, T_rows, dm.D, (int64_t)dm.D);
+  LAUNCH_CHECK();
+  if (dm.m > 0) {
+    hipLaunchKernelGGL((transpose_kernel<T>), dim3((dm.m + 63) / 64, (T_rows + 63) / 64), dim3(256), 0, st,
+                       Tt, xt + (int64_t)dm.D * T_rows, T_rows, dm.m, (int64_t)dm.D);
+    LAUNCH_CHECK();
+  }
+  // 2. Gram blocks on MFMA, fp32 out: ga = X^T A, gt = X^T T  (rows of "X" here = predictor inputs,
+  //    contraction over the token rows)
+  {
+    SeqMeta mt;
+    mt.n = 1; mt.start[0] = 0; mt.len[0] = dm.d_in;
+    fill_slots(mt);
+    rc = launch_recon_mfma<T>(T_rows, 0, dm.D, xt, xt, (const T*)nullptr, (const T*)nullptr, A, Tt,
+                              (T*)ga, (T*)gt, dm.D, 0, mt, st, 0, true);
+    if (rc) return rc;
+  }
+  // 3. G = [ga | gt[:, :m]] (+ ridge on the diagonal via the operator below), B = gt[:, m:]
+  hipLaunchKernelGGL(fit::copy_cols_kernel, dim3(1024), dim3(256), 0, st, G, (int64_t)dm.d_in, 0, ga,
+                     (int64_t)dm.D, 0, dm.d_in, dm.D);
+  LAUNCH_CHECK();
+  if (dm.m > 0) {
+    hipLaunchKernelGGL(fit::copy_cols_kernel, dim3(1024), dim3(256), 0, st, G, (int64_t)dm.d_in, dm.D, gt,
+                       (int64_t)dm.D, 0, dm.d_in, dm.m);
+    LAUNCH_CHECK();
+  }
+  hipLaunchKernelGGL(fit::copy_cols_kernel, dim3(1024), dim3(256), 0, st, B, (int64_t)dm.d_out, 0, gt,
+                     (int64_t)dm.D, dm.m, dm.d_in, dm.d_out);
+  LAUNCH_CHECK();
+  // 4. conjugate gradients on (G + ridge I) W = B, W0 = 0, all columns sharing one step length
+  auto dot = [&](const float* x, const float* y, double* out) -> int {
+    hipLaunchKernelGGL(fit::dot_kernel, dim3(fit::kDotBlocks), dim3(256), 0, st, x, y, wn, part);
+    if (hipGetLastError() != hipSuccess) return ECHOKV_ERR_HIP;
+    std::vector<float> h(fit::kDotBlocks);
+    if (hipMemcpyAsync(h.data(), part, fit::kDotBlocks * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) return ECHOKV_ERR_HIP;
+    double s = 0.0;
+    for (float v : h) s += v;
+    *out = s;
+    return ECHOKV_OK;
+  };
+  hipLaunchKernelGGL(fit::fill_kernel, dim3(1024), dim3(256), 0, st, W, 0.f, wn);
+  LAUNCH_CHECK();
+  HIP_TRY(hipMemcpyAsync(R, B, wn * 4, hipMemcpyDeviceToDevice, st));
+  HIP_TRY(hipMemcpyAsync(P, B, wn * 4, hipMemcpyDeviceToDevice, st));
+  double rr = 0.0, bb = 0.0;
+  rc = dot(R, R, &rr);
+  if (rc) return rc;
+  bb = rr;
+  int it = 0;
+  for (; it < max_iters && rr > (double)tol * tol * bb && bb > 0.0; ++it) {
+    {   // AP = G P (fp32 tile GEMM), + ridge P
+      SeqMeta mt;
+      mt.n = 1; mt.start[0] = 0; mt.len[0] = dm.d_in;
+      fill_slots(mt);
+      GemmArgs<float> g;
+      g.xa[0] = g.xa[1] = G; g.xr[0] = g.xr[1] = nullptr; g.w[0] = g.w[1] = P; g.out[0] = g.out[1] = AP;
+      g.D = dm.d_in; g.m = 0; g.d_out = dm.d_out; g.ldo = dm.d_out; g.col0 = 0; g.rows_from_slots = 0;
+      const int tiles = fill_tiles(mt, 64);
+      hipLaunchKernelGGL((recon_fma_kernel<float>), dim3(tiles, (dm.d_out + 63) / 64, 1), dim3(256), 0, st, g, mt);
+      LAUNCH_CHECK();
+      if (ridge > 0.f) {
+        hipLaunchKernelGGL(fit::axpy_kernel, dim3(1024), dim3(256), 0, st, AP, P, ridge, wn);
+        LAUNCH_CHECK();
+      }
+    }
+    double pap = 0.0;
+    rc = dot(P, AP, &pap);
+    if (rc) return rc;
+    if (!(pap > 0.0)) break;
+    const float alpha = (float)(rr / pap);
+    hipLaunchKernelGGL(fit::step_kernel, dim3(1024), dim3(256), 0, st, W, R, P, AP, alpha, wn);
+    LAUNCH_CHECK();
+    double rr_new = 0.0;
+    rc = dot(R, R, &rr_new);
+    if (rc) return rc;
+    hipLaunchKernelGGL(fit::direction_kernel, dim3(1024), dim3(256), 0, st, P, R, (float)(rr_new / rr), wn);
+    LAUNCH_CHECK();
+    rr = rr_new;
+  }
+  hipLaunchKernelGGL(fit::to_bf16_kernel, dim3(1024), dim3(256), 0, st, (bf16_t*)w_out, W, wn);
+  LAUNCH_CHECK();
+  HIP_TRY(hipStreamSynchronize(st));
+  if (iters_out) *iters_out = it;
+  if (rel_residual_out) *rel_residual_out = bb > 0.0 ? (float)std::sqrt(rr / bb) : 0.f;
+  return ECHOKV_OK;
 }
 
 int echokv_prefill_attn(const echokv_shape* shape, const echokv_layer_cache* anchor,

@@ -780,7 +780,7 @@ __global__ __launch_bounds__(NTHREADS) void fused_kscores_kernel(Args a, SeqMeta
 // out[row, col0 + column].  Output row = sbase[b]*kSlotTokens + j.  With an
 // activation it is the first layer of the one-hidden-layer predictor
 // (Appendix "Prediction Network Architecture").
-template <int ACT>      // activation before rounding: 0 none, 1 ReLU, 2 SiLU
+template <int ACT, bool OUT32 = false>   // activation before rounding: 0 none, 1 ReLU, 2 SiLU; OUT32: fp32 output
 __global__ __launch_bounds__(NTHREADS) void recon_mfma_kernel(Args a, SeqMeta meta) {
   __shared__ Smem sm;
   char* smem = reinterpret_cast<char*>(&sm);
@@ -832,7 +832,10 @@ __global__ __launch_bounds__(NTHREADS) void recon_mfma_kernel(Args a, SeqMeta me
 #pragma unroll
       for (int ci = 0; ci < 4; ++ci) {
         const int c = n0 + wc * WN + ci * 32 + lr;
-        if (c < a.d_out) out[(orow0 + j) * a.ldo + a.col0 + c] = f32_to_bf16(acc[ji][ci][r]);
+        if (c < a.d_out) {
+          if constexpr (OUT32) reinterpret_cast<float*>(out)[(orow0 + j) * a.ldo + a.col0 + c] = acc[ji][ci][r];
+          else out[(orow0 + j) * a.ldo + a.col0 + c] = f32_to_bf16(acc[ji][ci][r]);
+        }
       }
     }
   }
@@ -933,7 +936,7 @@ inline int launch_fused_kscores(int H_q, int H_kv, int d, int m, int d_out, int 
 template <typename T>
 inline int launch_recon_mfma(int D, int m, int d_out, const T* ka, const T* va, const T* kr, const T* vr,
                              const T* wk, const T* wv, T* out_k, T* out_v, int64_t ldo, int col0,
-                             SeqMeta& mt, hipStream_t st, int act = 0) {
+                             SeqMeta& mt, hipStream_t st, int act = 0, bool out_f32 = false) {
   if constexpr (sizeof(T) != 2) {
     return 6;
   } else {
@@ -947,7 +950,8 @@ inline int launch_recon_mfma(int D, int m, int d_out, const T* ka, const T* va, 
     a.n_tiles = fused_fill_tiles(mt) * a.n_col_tiles;
     const int grid = ((a.n_tiles + 7) / 8) * 8;
     const dim3 g(grid, 2), blk(fused::NTHREADS);
-    if (act == 1) hipLaunchKernelGGL(fused::recon_mfma_kernel<1>, g, blk, 0, st, a, mt);
+    if (out_f32) hipLaunchKernelGGL((fused::recon_mfma_kernel<0, true>), g, blk, 0, st, a, mt);
+    else if (act == 1) hipLaunchKernelGGL(fused::recon_mfma_kernel<1>, g, blk, 0, st, a, mt);
     else if (act == 2) hipLaunchKernelGGL(fused::recon_mfma_kernel<2>, g, blk, 0, st, a, mt);
     else hipLaunchKernelGGL(fused::recon_mfma_kernel<0>, g, blk, 0, st, a, mt);
     if (hipGetLastError() != hipSuccess) return 7;

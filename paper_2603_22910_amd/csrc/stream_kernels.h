@@ -124,17 +124,18 @@ __global__ __launch_bounds__(256) void copy2d_kernel(Copy2dArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// dst[c, r] = src[r, c] for a row-major [R, C] matrix: 64x64 tiles through LDS.
+// dst[c, r] = src[r, c] for a row-major [R, C] matrix (row pitch ld_src): 64x64 tiles through LDS.
 // Used once per weight matrix to lay W out as [d_out, d_in] (k-contiguous rows),
 // the layout an MFMA operand wants.  grid = (ceil(C/64), ceil(R/64)).
 // ---------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void transpose_kernel(const T* src, T* dst, int R, int C) {
+__global__ __launch_bounds__(256) void transpose_kernel(const T* src, T* dst, int R, int C,
+                                                        int64_t ld_src) {
   __shared__ T tile[64][65];
   const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   for (int i = ty; i < 64; i += 4)
-    if (r0 + i < R && c0 + tx < C) tile[i][tx] = src[(int64_t)(r0 + i) * C + c0 + tx];
+    if (r0 + i < R && c0 + tx < C) tile[i][tx] = src[(int64_t)(r0 + i) * ld_src + c0 + tx];
   __syncthreads();
   for (int i = ty; i < 64; i += 4)
     if (c0 + i < C && r0 + tx < R) dst[(int64_t)(c0 + i) * R + r0 + tx] = tile[tx][i];

@@ -232,3 +232,18 @@ def test_mlp_argument_errors(lib):
     assert ek.mlp_workspace_bytes(f32, 1, 100, 128) == 0
     assert ek.mlp_workspace_bytes(sh, 1, 100, 128) > 0
     assert ek.mlp_workspace_bytes(sh, 1, 100, 96) == 0
+
+
+def test_fit_argument_errors(lib):
+    sh = ek.make_shape(8, 8, 64, 256, "bf16")
+    big = _Ws(1 << 34)
+    assert ek.fit_workspace_bytes(sh, 4096) > 0
+    assert ek.fit_workspace_bytes(sh, 100) == 0                       # rows not a multiple of 64
+    assert ek.fit_workspace_bytes(ek.make_shape(8, 8, 64, 256, "f32"), 4096) == 0
+    assert ek.fit_workspace_bytes(ek.make_shape(8, 8, 64, 512, "bf16"), 4096) == 0   # nothing to predict
+    assert code(ek.fit_linear, sh, None, FAKE, 4096, FAKE, big, stream=0) == ek.ERR_NULL
+    assert code(ek.fit_linear, sh, FAKE, FAKE, 100, FAKE, big, stream=0) == ek.ERR_SHAPE
+    assert code(ek.fit_linear, sh, FAKE, FAKE, 4096, FAKE, big, ridge=-1.0, stream=0) == ek.ERR_SHAPE
+    assert code(ek.fit_linear, sh, FAKE, FAKE, 4096, FAKE, big, max_iters=0, stream=0) == ek.ERR_SHAPE
+    assert code(ek.fit_linear, sh, FAKE, FAKE, 4096, FAKE, _Ws(1024), stream=0) == ek.ERR_WORKSPACE
+    assert code(ek.fit_linear, sh, FAKE, FAKE, 1 << 22, FAKE, big, stream=0) == ek.ERR_UNSUPPORTED   # > 2 GB per matrix
