@@ -170,6 +170,34 @@ int launch_attn_split(const Dims& dm, AttnArgs<T> a, SeqMeta& mt, int n_kv_heads
   return ECHOKV_OK;
 }
 
+// The uncompressed window's tokens: plain attention over its full-width rows, all KV heads,
+// one partial per sequence at slot win_slot0 + b of (po, pml).
+template <typename T>
+int launch_window_attn(const Dims& dm, const echokv_decode_extras* ex, const KvExtras& kx, const T* qq,
+                       float* po, float* pml, int b0, int win_slot0, const SeqMeta& mt, hipStream_t st) {
+  AttnArgs<T> a;
+  a.k = (const T*)ex->win_k; a.v = (const T*)ex->win_v; a.ld = dm.D; a.col0 = 0; a.head0 = 0;
+  a.row_mode = 3; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
+  a.split_tokens = kSlotTokens;
+  a.part_o = po; a.part_ml = pml;
+  a.rope_cos = kx.rope_cos; a.rope_sin = kx.rope_sin; a.win = Window{kx.n_sink, kx.n_recent};
+  a.seq0 = b0; a.win_slot0 = win_slot0;
+  SeqMeta wm = mt;                         // one chunk per sequence
+  for (int b = 0; b <= wm.n; ++b) wm.tbase[b] = b;
+  const int GT = (dm.G % 4 == 0) ? 4 : (dm.G % 2 == 0) ? 2 : 1;
+  dim3 grid(wm.n, dm.H_kv * (dm.G / GT));
+  constexpr int LPR64 = 64 * (int)sizeof(T) / 16, LPR128 = 128 * (int)sizeof(T) / 16;
+#define WIN_CASE(LPR_, GT_) hipLaunchKernelGGL((attn_split_kernel<T, LPR_, GT_>), grid, dim3(256), 0, st, a, wm)
+  if (dm.d == 64) {
+    if (GT == 4) WIN_CASE(LPR64, 4); else if (GT == 2) WIN_CASE(LPR64, 2); else WIN_CASE(LPR64, 1);
+  } else {
+    if (GT == 4) WIN_CASE(LPR128, 4); else if (GT == 2) WIN_CASE(LPR128, 2); else WIN_CASE(LPR128, 1);
+  }
+#undef WIN_CASE
+  LAUNCH_CHECK();
+  return ECHOKV_OK;
+}
+
 template <typename T>
 int launch_recon_fma(const Dims& dm, GemmArgs<T> g, SeqMeta& mt, hipStream_t st) {
   const int tiles = fill_tiles(mt, 64);
@@ -305,29 +333,9 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
     }
     int win_slot0 = -1;
     if (win.on()) {
-      // the window's tokens: plain attention over its full-width rows, all KV heads, one
-      // partial per sequence placed after the regular slots
-      win_slot0 = slots;
-      AttnArgs<T> a;
-      a.k = (const T*)ex->win_k; a.v = (const T*)ex->win_v; a.ld = dm.D; a.col0 = 0; a.head0 = 0;
-      a.row_mode = 3; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
-      a.split_tokens = kSlotTokens;
-      a.part_o = po; a.part_ml = pml;
-      a.rope_cos = kx.rope_cos; a.rope_sin = kx.rope_sin; a.win = win;
-      a.seq0 = b0; a.win_slot0 = win_slot0;
-      SeqMeta wm = mt;                         // one chunk per sequence
-      for (int b = 0; b <= wm.n; ++b) wm.tbase[b] = b;
-      const int GT = (dm.G % 4 == 0) ? 4 : (dm.G % 2 == 0) ? 2 : 1;
-      dim3 grid(wm.n, dm.H_kv * (dm.G / GT));
-      constexpr int LPR64 = 64 * (int)sizeof(T) / 16, LPR128 = 128 * (int)sizeof(T) / 16;
-#define WIN_CASE(LPR_, GT_) hipLaunchKernelGGL((attn_split_kernel<T, LPR_, GT_>), grid, dim3(256), 0, st, a, wm)
-      if (dm.d == 64) {
-        if (GT == 4) WIN_CASE(LPR64, 4); else if (GT == 2) WIN_CASE(LPR64, 2); else WIN_CASE(LPR64, 1);
-      } else {
-        if (GT == 4) WIN_CASE(LPR128, 4); else if (GT == 2) WIN_CASE(LPR128, 2); else WIN_CASE(LPR128, 1);
-      }
-#undef WIN_CASE
-      LAUNCH_CHECK();
+      win_slot0 = slots;                    // placed after the regular slots
+      int rcw = launch_window_attn<T>(dm, ex, kx, qq, po, pml, b0, win_slot0, mt, st);
+      if (rcw) return rcw;
     }
     int rc = dm.out_bf16
         ? merge_launch<T, bf16_t>(dm, po, pml, out, lse, b0, n_ret_heads, stream_step, fused_step, win_slot0, mt, st)
@@ -710,26 +718,8 @@ int absorbed_impl(const Dims& dm, bool value_only, const echokv_layer_cache* an,
         if (rc) return rc;
       }
       if (win.on()) {       // the window's tokens: one o-space partial per sequence
-        AttnArgs<T> wa;
-        wa.k = (const T*)ex->win_k; wa.v = (const T*)ex->win_v; wa.ld = dm.D; wa.col0 = 0; wa.head0 = 0;
-        wa.row_mode = 3; wa.q = a.q; wa.H_q = dm.H_q; wa.G = dm.G; wa.d = dm.d; wa.scale = dm.scale;
-        wa.split_tokens = kSlotTokens;
-        wa.part_o = win_po; wa.part_ml = win_pml;
-        wa.rope_cos = kx.rope_cos; wa.rope_sin = kx.rope_sin; wa.win = win;
-        wa.seq0 = b0; wa.win_slot0 = 0;
-        SeqMeta wm = mt;
-        for (int b = 0; b <= wm.n; ++b) wm.tbase[b] = b;
-        const int GT = (dm.G % 4 == 0) ? 4 : (dm.G % 2 == 0) ? 2 : 1;
-        dim3 grid(wm.n, dm.H_kv * (dm.G / GT));
-        constexpr int LPR64 = 8, LPR128 = 16;
-#define WIN_CASE(LPR_, GT_) hipLaunchKernelGGL((attn_split_kernel<T, LPR_, GT_>), grid, dim3(256), 0, st, wa, wm)
-        if (dm.d == 64) {
-          if (GT == 4) WIN_CASE(LPR64, 4); else if (GT == 2) WIN_CASE(LPR64, 2); else WIN_CASE(LPR64, 1);
-        } else {
-          if (GT == 4) WIN_CASE(LPR128, 4); else if (GT == 2) WIN_CASE(LPR128, 2); else WIN_CASE(LPR128, 1);
-        }
-#undef WIN_CASE
-        LAUNCH_CHECK();
+        rc = launch_window_attn<T>(dm, ex, kx, a.q, win_po, win_pml, b0, 0, mt, st);
+        if (rc) return rc;
       }
     }
     hipLaunchKernelGGL(absorbed::softmax_stats_kernel, dim3(dm.H_q, splits), dim3(256), 0, st, a, mt);

@@ -1,0 +1,43 @@
+"""The decode entry points allocate nothing, synchronise nothing and clear nothing with
+memsets, so a caller may capture them in a HIP graph.  Each replay is checked against an
+eager call on the same inputs, with eager work and synchronisations between the replays."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_22910_amd import binding as ek
+from paper_2603_22910_amd import synth
+from paper_2603_22910_amd.harness import DeviceWorkload
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("flags", [pytest.param(0, id="fused"), pytest.param(ek.FLAG_ABSORBED, id="absorbed"),
+                                   pytest.param(ek.FLAG_ABSORB_V, id="absorb_v"),
+                                   pytest.param(ek.FLAG_UNFUSED, id="unfused")])
+def test_decode_in_a_captured_graph_matches_eager_on_every_replay(flags):
+    w = synth.Workload("graph", "bf16", 8, 4, 128, 256, seed=61, seq_lens=(700, 129, 300))
+    inp = synth.generate(w)
+    dw = DeviceWorkload(inp, flags=flags)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        dw.decode(stream=side.cuda_stream)          # warm-up on the capture stream
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        dw.decode(stream=torch.cuda.current_stream().cuda_stream)
+    gen = torch.Generator().manual_seed(3)
+    for rep in range(4):
+        q_new = torch.randn(dw.q.shape, generator=gen).to(dw.q.dtype)
+        dw.q.copy_(q_new.to(dw.dev))                # same buffer the graph reads
+        torch.cuda.synchronize()
+        dw.out.zero_(); dw.lse.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        got, got_lse = dw.out.clone(), dw.lse.clone()
+        dw.out.zero_(); dw.lse.zero_()
+        dw.decode()                                  # eager, default stream
+        torch.cuda.synchronize()
+        assert torch.equal(got, dw.out), (flags, rep)
+        assert torch.equal(got_lse, dw.lse), (flags, rep)
+        assert float(got.float().abs().sum()) > 0
