@@ -314,7 +314,7 @@ def profile_stream_read(buf, repeats: int = 5) -> float:
     """GB/s a plain streaming-read kernel reaches over the tensor `buf`."""
     out = C.c_double(0.0)
     _check(load().echokv_profile_stream_read(_ptr(buf), buf.numel() * buf.element_size(), int(repeats),
-                                             C.byref(out)), "echokv_profile_stream_read", "echokv_fit_workspace_bytes", "echokv_fit_linear")
+                                             C.byref(out)), "echokv_profile_stream_read")
     return float(out.value)
 
 

@@ -247,3 +247,15 @@ def test_fit_argument_errors(lib):
     assert code(ek.fit_linear, sh, FAKE, FAKE, 4096, FAKE, big, max_iters=0, stream=0) == ek.ERR_SHAPE
     assert code(ek.fit_linear, sh, FAKE, FAKE, 4096, FAKE, _Ws(1024), stream=0) == ek.ERR_WORKSPACE
     assert code(ek.fit_linear, sh, FAKE, FAKE, 1 << 22, FAKE, big, stream=0) == ek.ERR_UNSUPPORTED   # > 2 GB per matrix
+
+
+def test_every_status_check_in_the_binding_is_well_formed():
+    """_check(status, label): a slip in an edit once gave one of these calls extra labels, which
+    only shows when that wrapper runs on a GPU."""
+    import ast
+    tree = ast.parse(open(os.path.join(ROOT, "paper_2603_22910_amd", "binding.py")).read())
+    calls = [n for n in ast.walk(tree) if isinstance(n, ast.Call) and getattr(n.func, "id", "") == "_check"]
+    assert len(calls) >= 12
+    for c in calls:
+        assert len(c.args) == 2 and not c.keywords, ast.dump(c)[:200]
+        assert isinstance(c.args[1], ast.Constant) and c.args[1].value in ek.EXPORTS

@@ -41,3 +41,11 @@ def test_decode_in_a_captured_graph_matches_eager_on_every_replay(flags):
         assert torch.equal(got, dw.out), (flags, rep)
         assert torch.equal(got_lse, dw.lse), (flags, rep)
         assert float(got.float().abs().sum()) > 0
+
+
+def test_stream_read_yardstick_runs_and_is_plausible():
+    buf = torch.ones(1 << 29, dtype=torch.uint8, device="cuda:0")
+    rate = ek.profile_stream_read(buf, 3)
+    assert 1000.0 < rate < 8000.0        # GB/s: above any PCIe-like figure, below the nominal HBM peak
+    with pytest.raises(ek.EchoKVError):
+        ek.profile_stream_read(torch.ones(1 << 20, dtype=torch.uint8, device="cuda:0"), 3)   # too small
