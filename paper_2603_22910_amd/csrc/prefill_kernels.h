@@ -232,6 +232,341 @@ __global__ __launch_bounds__(NTHREADS, 2) void prefill_attn_kernel(Args a) {
   }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Long chunks: 256 queries x one head per workgroup of eight waves (32 queries each), K and
+// V tiles of 64 keys copied global -> LDS by the buffer-load-to-LDS path into a ring of four
+// stages (three tiles in flight, no staging registers, no address arithmetic per element),
+// both stored row-major [key][dim].  The V^T fragments the second product needs are read with
+// the LDS transpose read: in a group of 16 lanes, lane 4j + a supplies dims 4a .. 4a+3 of key
+// j, and lane i receives dim i of keys 0 .. 3 -- so the 16 lanes read a 4-key x 16-dim patch
+// and end up holding one dim each, in order.  16-byte chunks of a row are XOR-swizzled by the
+// key so that neither the K row reads nor the V patch reads collide on LDS banks; the
+// swizzle is applied on the global side of the copy (the LDS side of it is linear).
+namespace dma {
+
+#ifndef ECHOKV_LDS
+#define ECHOKV_LDS __attribute__((address_space(3)))
+#endif
+using fused::rsrc_t;
+typedef short short4_t __attribute__((ext_vector_type(4)));
+
+constexpr int NST = 4, NTHREADS = 512, BQ = 256;
+constexpr int kMinQueries = 1024;      // shorter chunks keep the four-wave kernel (more workgroups)
+
+template <int HD> struct Cfg {
+  static constexpr int ROWB = HD * 2;                   // bytes per key row
+  static constexpr int CH = HD / 8;                     // 16-byte chunks per row
+  static constexpr int TILE = BKV * ROWB;               // bytes of one K (or V) tile
+  static constexpr int STAGE = 2 * TILE;                // K tile then V tile
+  static constexpr int NL = TILE / 1024 / 8;            // 1 KB copies per wave per tile and operand
+  static constexpr int ROWS_PER_COPY = 1024 / ROWB;     // 4 (HD = 128) or 8 (HD = 64)
+  static constexpr int KSTEPS = HD / 16, CB = HD / 32, KG = KSTEPS / 4;
+  // chunk c of key row r is stored at chunk c ^ kswz(r) (K tile) / c ^ vswz(r) (V tile)
+  __device__ static __forceinline__ int kswz(int r) { return CH == 16 ? (r & 15) : ((r ^ (r >> 3)) & 7); }
+  __device__ static __forceinline__ int vswz(int r) { return CH == 16 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2); }
+};
+
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));   // vmcnt(N)
+  __builtin_amdgcn_s_waitcnt(0xC07F);                                   // lgkmcnt(0): own LDS reads done
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+
+// What a lane needs to issue its share of a tile's global -> LDS copies.
+template <int HD> struct CopyPlan {
+  rsrc_t rk, rv;
+  int row[Cfg<HD>::NL];                 // tile row this lane copies a chunk of, per copy
+  uint32_t kcol[Cfg<HD>::NL], vcol[Cfg<HD>::NL];   // byte offset of the (swizzled) source chunk in the row
+  uint32_t ld2; int last, wave_u;
+};
+// Issue this wave's copies of key tile t into ring stage t % NST.  Rows past the last key
+// repeat it: finite values, masked by causality.  (A device function of its own: the copy
+// builtin is not accepted inside a kernel body by the host pass.)
+template <int HD>
+__device__ __forceinline__ void dma_tile(char* smem, const CopyPlan<HD>& cp, int t) {
+  using C = Cfg<HD>;
+  char* st = smem + (t & (NST - 1)) * C::STAGE;
+  const int kv0 = t * BKV;
+#pragma unroll
+  for (int i = 0; i < C::NL; ++i) {
+    const uint32_t ro = __umul24((uint32_t)min(kv0 + cp.row[i], cp.last), cp.ld2);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(cp.rk, (ECHOKV_LDS void*)(st + (C::NL * cp.wave_u + i) * 1024), 16,
+                                             ro + cp.kcol[i], 0, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(cp.rv, (ECHOKV_LDS void*)(st + C::TILE + (C::NL * cp.wave_u + i) * 1024), 16,
+                                             ro + cp.vcol[i], 0, 0, 0);
+  }
+}
+
+// max of a value over the two lanes (l, l + 32) that share a query, on the vector ALU
+__device__ __forceinline__ float max_over_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+typedef short short8_t __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(ECHOKV_LDS const char*)p;
+}
+// One k-step's V^T fragments: per 32-dim block, keys k0 .. k0+3 (lo) and k0+8 .. k0+11 (hi).
+struct VFrag { short4_t lo[4], hi[4]; };
+// LDS transpose reads written as instructions: the compiler orders the builtin form behind
+// every outstanding global -> LDS copy, which would drain the ring once per tile.
+template <int OFF>
+__device__ __forceinline__ short4_t tr_read(uint32_t addr) {
+  short4_t v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+// voff[cb]: this lane's byte offset inside a V tile for k-step 0, 32-dim block cb
+template <int HD, int TS>
+__device__ __forceinline__ void read_v(VFrag& f, uint32_t sv, const uint32_t (&voff)[Cfg<HD>::CB]) {
+#pragma unroll
+  for (int cb = 0; cb < Cfg<HD>::CB; ++cb) {
+    f.lo[cb] = tr_read<16 * TS * Cfg<HD>::ROWB>(sv + voff[cb]);
+    f.hi[cb] = tr_read<(16 * TS + 8) * Cfg<HD>::ROWB>(sv + voff[cb]);
+  }
+}
+// wait until at most N LDS reads issued after these are outstanding; the operands tie the
+// wait to the registers it guards
+template <int N, int CB>
+__device__ __forceinline__ void wait_v(VFrag& f) {
+  if constexpr (CB == 4)
+    asm volatile("s_waitcnt lgkmcnt(%8)"
+                 : "+v"(f.lo[0]), "+v"(f.lo[1]), "+v"(f.lo[2]), "+v"(f.lo[3]),
+                   "+v"(f.hi[0]), "+v"(f.hi[1]), "+v"(f.hi[2]), "+v"(f.hi[3])
+                 : "n"(N));
+  else
+    asm volatile("s_waitcnt lgkmcnt(%4)"
+                 : "+v"(f.lo[0]), "+v"(f.lo[1]), "+v"(f.hi[0]), "+v"(f.hi[1])
+                 : "n"(N));
+}
+
+
+// Four k-steps of K fragments (rows mb*32 + lane%32, 8 dims each).
+struct KFrag { fused::u32x4_t f[4][2]; };
+// koff[kk]: this lane's byte offset inside a K tile for k-step kk, rows 0..31 (rows 32..63: + 32 rows;
+// for d = 64 the swizzle of those rows differs in one bit, folded into koff1)
+template <int OFF>
+__device__ __forceinline__ fused::u32x4_t k_read(uint32_t addr) {
+  fused::u32x4_t v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+template <int HD>
+__device__ __forceinline__ void read_k(KFrag& f, uint32_t sk, const uint32_t (&koff)[2][Cfg<HD>::KSTEPS], int g) {
+#pragma unroll
+  for (int k4 = 0; k4 < 4; ++k4) {
+    f.f[k4][0] = k_read<0>(sk + koff[0][g * 4 + k4]);
+    f.f[k4][1] = k_read<32 * Cfg<HD>::ROWB>(sk + koff[1][g * 4 + k4]);
+  }
+}
+template <int N>
+__device__ __forceinline__ void wait_k(KFrag& f) {
+  asm volatile("s_waitcnt lgkmcnt(%8)"
+               : "+v"(f.f[0][0]), "+v"(f.f[0][1]), "+v"(f.f[1][0]), "+v"(f.f[1][1]),
+                 "+v"(f.f[2][0]), "+v"(f.f[2][1]), "+v"(f.f[3][0]), "+v"(f.f[3][1])
+               : "n"(N));
+}
+
+template <int HD>
+__global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
+  using C = Cfg<HD>;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];      // NST stages of [K tile | V tile]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  const int lr = lane & 31, lh = lane >> 5;
+  const int h = blockIdx.y;
+  const int nqb = (a.T_q + BQ - 1) / BQ;
+  const int i0 = (nqb - 1 - blockIdx.x) * BQ;     // longest (latest) query blocks first
+  const int Ltot = a.q_pos0 + a.T_q;
+  const int kvh = h / a.G;
+  const bf16_t* kbase; const bf16_t* vbase; uint32_t ld2;
+  if (kvh < a.n_ret_heads) { kbase = a.k_ret + kvh * HD; vbase = a.v_ret + kvh * HD; ld2 = (uint32_t)a.m * 2; }
+  else { const int c = (kvh - a.n_ret_heads) * HD; kbase = a.k_hat + c; vbase = a.v_hat + c; ld2 = (uint32_t)a.d_out * 2; }
+
+  // ---- copy plan: copy i of this wave fills tile rows (NL wave + i) * ROWS_PER_COPY + lane / CH;
+  //      LDS chunk slot lane % CH of that row receives global chunk slot ^ swizzle(row)
+  CopyPlan<HD> cp;
+#pragma unroll
+  for (int i = 0; i < C::NL; ++i) {
+    cp.row[i] = (C::NL * wave + i) * C::ROWS_PER_COPY + lane / C::CH;
+    cp.kcol[i] = (uint32_t)(((lane % C::CH) ^ C::kswz(cp.row[i])) * 16);
+    cp.vcol[i] = (uint32_t)(((lane % C::CH) ^ C::vswz(cp.row[i])) * 16);
+  }
+  cp.rk = fused::make_rsrc(kbase); cp.rv = fused::make_rsrc(vbase);
+  cp.ld2 = ld2; cp.last = Ltot - 1; cp.wave_u = wave_u;
+
+  // ---- this lane's query (clamped; clamped duplicates are not written back)
+  const int qi = i0 + wave * 32 + lr;
+  const int qic = min(qi, a.T_q - 1);
+  const int qpos = a.q_pos0 + qic;
+  bf16x8_t qf[C::KSTEPS];
+  {
+    const bf16_t* qp = a.q + ((int64_t)qic * a.H_q + h) * HD + lh * 8;
+#pragma unroll
+    for (int kk = 0; kk < C::KSTEPS; ++kk) qf[kk] = *reinterpret_cast<const bf16x8_t*>(qp + kk * 16);
+  }
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0x0F70);                // vmcnt(0): the ring's load counting starts from zero
+  asm volatile("" ::: "memory");
+  floatx16_t oacc[C::CB];
+#pragma unroll
+  for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float scale2 = a.scale * 1.44269504088896340736f;    // softmax in base 2
+  const int qpos_min = a.q_pos0 + min(i0 + wave * 32, a.T_q - 1);
+  const int qpos_max = a.q_pos0 + min(i0 + wave * 32 + 31, a.T_q - 1);
+  const int kv_end = min(Ltot, a.q_pos0 + min(i0 + BQ, a.T_q));   // keys any query of the block sees
+  const int ntiles = (kv_end + BKV - 1) / BKV;
+
+  // ---- fragment addresses inside a stage
+  // K: row mb*32 + lr, chunk (2 kk + lh) ^ kswz(row)
+  // V: transpose read of the patch keys k0 + s/4, dims cb*32 + 16*(blk%2) + 4*(s%4) .. +3, with
+  //    s = lane % 16, blk = lane / 16 (blk / 2 = lh): this lane then holds dim cb*32 + lane % 32
+  const int s16 = lane & 15, blk2 = (lane >> 4) & 1;
+  const int vkey = 4 * lh + (s16 >> 2);                        // + 16 ts (+ 8 for the second half)
+  const int vch = 2 * blk2 + ((s16 & 3) >> 1);                 // + 4 cb, before the swizzle
+  const uint32_t vbyte = (uint32_t)((s16 & 1) * 8);
+  uint32_t koff[2][C::KSTEPS];
+#pragma unroll
+  for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+    for (int kk = 0; kk < C::KSTEPS; ++kk)     // the + 32 rows of mb = 1 ride in the instruction offset
+      koff[mb][kk] = (uint32_t)(lr * C::ROWB + (((kk * 2 + lh) ^ C::kswz(mb * 32 + lr)) << 4));
+  uint32_t voff[C::CB];
+#pragma unroll
+  for (int cb = 0; cb < C::CB; ++cb)      // the swizzle of key vkey + 16 ts (+ 8) does not depend on ts
+    voff[cb] = (uint32_t)(vkey * C::ROWB + (((4 * cb + vch) ^ C::vswz(vkey)) << 4)) + vbyte;
+
+  dma_tile<HD>(smem, cp, 0); dma_tile<HD>(smem, cp, 1); dma_tile<HD>(smem, cp, 2);
+  for (int t = 0; t < ntiles; ++t) {
+    wait_loads_and_barrier<2 * 2 * C::NL>();     // tile t has landed for every wave; stage (t-1)%NST is free
+    dma_tile<HD>(smem, cp, t + 3);
+    const int kv0 = t * BKV;
+    if (kv0 > qpos_max) continue;      // wholly past this wave's queries (wave-uniform)
+    const char* sk = smem + (t & (NST - 1)) * C::STAGE;
+    const char* sv = sk + C::TILE;
+    // ---- S^T = K Q^T : all K fragments of the tile are requested up front, four k-steps per group
+    const uint32_t sku = lds_addr(sk), svu = lds_addr(sv);
+    KFrag kb[C::KG];
+#pragma unroll
+    for (int g = 0; g < C::KG; ++g) read_k<HD>(kb[g], sku, koff, g);
+    floatx16_t sacc[2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[mb][r] = 0.f;
+#pragma unroll
+    for (int g = 0; g < C::KG; ++g) {
+      if (g == 0) wait_k<(C::KG - 1) * 8>(kb[0]); else wait_k<0>(kb[C::KG - 1]);
+#pragma unroll
+      for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+          sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kb[g].f[k4][mb]),
+                                                             qf[g * 4 + k4], sacc[mb], 0, 0, 0);
+    }
+    // the first two k-steps of V^T arrive while the softmax runs
+    VFrag vb[2];
+    read_v<HD, 0>(vb[0], svu, voff);
+    read_v<HD, 1>(vb[1], svu, voff);
+    // ---- online softmax, lane-local (keys: mb*32 + 8*(r/4) + 4*lh + r%4), base 2, scale folded in
+    if (kv0 + BKV - 1 > qpos_min) {
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kv0 + mb * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
+          if (key > qpos) sacc[mb][r] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mb][r]);
+    mx = max_over_halves(mx);
+    const float m_new = fmaxf(m_run, mx);      // finite from the first tile on (key 0 is visible)
+    const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
+    const float mneg = -m_new * scale2;
+    float lsum = 0.f;
+    bf16x8_t pf[4];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[mb][r], scale2, mneg));
+        lsum += p;
+        pf[mb * 2 + (r >> 3)][r & 7] = (__bf16)p;
+      }
+    l_run = l_run * corr + lsum;
+    m_run = m_new;
+    if (__any(corr != 1.0f)) {          // the running maxima settle quickly: usually nothing to rescale
+#pragma unroll
+      for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[cb][r] *= corr;
+    }
+    // ---- O^T += V^T P^T : k-step ts, element e of lane half lh <-> key 16 ts + 4 lh + (e < 4 ? e : e + 4).
+    //      The transpose reads are issued by hand one k-step ahead of the MFMAs that use them.
+#pragma unroll
+    for (int ts = 0; ts < 4; ++ts) {
+      if (ts == 0) wait_v<2 * C::CB, C::CB>(vb[0]);
+      if (ts == 1) { read_v<HD, 2>(vb[0], svu, voff); wait_v<2 * C::CB, C::CB>(vb[1]); }
+      if (ts == 2) { read_v<HD, 3>(vb[1], svu, voff); wait_v<2 * C::CB, C::CB>(vb[0]); }
+      if (ts == 3) wait_v<0, C::CB>(vb[1]);
+#pragma unroll
+      for (int cb = 0; cb < C::CB; ++cb) {
+        const short8_t vv = __builtin_shufflevector(vb[ts & 1].lo[cb], vb[ts & 1].hi[cb], 0, 1, 2, 3, 4, 5, 6, 7);
+        oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv), pf[ts], oacc[cb], 0, 0, 0);
+      }
+    }
+  }
+  wait_loads_and_barrier<0>();         // the ring's last copies have landed before the workgroup ends
+  // ---- finish: this lane holds query qi, head dims cb*32 + 8*(r/4) + 4*lh + r%4
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (qi >= a.T_q) return;
+  const float inv = 1.0f / l_tot;
+  const int64_t ob = ((int64_t)qi * a.H_q + h) * HD;
+#pragma unroll
+  for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+      const int c = cb * 32 + r4 * 8 + lh * 4;
+      const float x0 = oacc[cb][r4 * 4] * inv, x1 = oacc[cb][r4 * 4 + 1] * inv;
+      const float x2 = oacc[cb][r4 * 4 + 2] * inv, x3 = oacc[cb][r4 * 4 + 3] * inv;
+      if (a.out_bf16) {
+        uint2 w;
+        w.x = (uint32_t)f32_to_bf16(x0) | ((uint32_t)f32_to_bf16(x1) << 16);
+        w.y = (uint32_t)f32_to_bf16(x2) | ((uint32_t)f32_to_bf16(x3) << 16);
+        *reinterpret_cast<uint2*>(reinterpret_cast<bf16_t*>(a.out) + ob + c) = w;
+      } else {
+        *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + ob + c) = make_float4(x0, x1, x2, x3);
+      }
+    }
+  if (a.lse && lh == 0)
+    a.lse[(int64_t)qi * a.H_q + h] = (m_run * scale2 + __log2f(l_tot)) * 0.69314718055994530942f;
+}
+
+template <int HD>
+inline int launch(dim3 grid, dim3 blk, hipStream_t st, const Args& a) {
+  constexpr int lds = NST * Cfg<HD>::STAGE;          // 128 KB (d = 128) or 64 KB of dynamic LDS
+  void (*fn)(Args) = prefill_attn_dma_kernel<HD>;
+  if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+    return 7;
+  hipLaunchKernelGGL(fn, grid, blk, lds, st, a);
+  return hipGetLastError() != hipSuccess ? 7 : 0;
+}
+
+}  // namespace dma
+
 }  // namespace prefill
 
 template <typename T> inline bool prefill_mfma_supported(int d) {
@@ -254,6 +589,12 @@ inline int launch_prefill_mfma(int H_q, int H_kv, int d, int m, int d_out, int n
     a.out = out; a.lse = lse;
     a.H_q = H_q; a.G = H_q / H_kv; a.m = m; a.d_out = d_out; a.n_ret_heads = n_ret_heads;
     a.T_q = T_q; a.q_pos0 = q_pos0; a.out_bf16 = out_bf16 ? 1 : 0; a.scale = scale;
+    // long chunks take the eight-wave kernel with the LDS ring (its 32-bit row offsets must fit)
+    const int64_t span = (int64_t)(q_pos0 + T_q) * (m > d_out ? m : d_out) * 2;
+    if (T_q >= prefill::dma::kMinQueries && span < (int64_t)1 << 31) {
+      const dim3 grid((T_q + prefill::dma::BQ - 1) / prefill::dma::BQ, H_q), blk(prefill::dma::NTHREADS);
+      return d == 128 ? prefill::dma::launch<128>(grid, blk, st, a) : prefill::dma::launch<64>(grid, blk, st, a);
+    }
     dim3 grid((T_q + prefill::BQ - 1) / prefill::BQ, H_q);
     if (d == 128) hipLaunchKernelGGL((prefill::prefill_attn_kernel<128>), grid, dim3(prefill::NTHREADS), 0, st, a);
     else hipLaunchKernelGGL((prefill::prefill_attn_kernel<64>), grid, dim3(prefill::NTHREADS), 0, st, a);

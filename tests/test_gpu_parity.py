@@ -241,7 +241,9 @@ def run_prefill_case(w, flags=0):
     return inp, dw
 
 
-@pytest.mark.parametrize("plen,pq", [(400, 400), (400, 150), (130, 1), (257, 256), (64, 64)])
+# chunks of 1024 queries and more take the kernel variant with 64 queries per wave
+@pytest.mark.parametrize("plen,pq", [(400, 400), (400, 150), (130, 1), (257, 256), (64, 64),
+                                     (1300, 1100), (1024, 1024), (1500, 1025)])
 def test_prefill_small(plen, pq):
     run_prefill_case(SMALL[4].scaled(prefill_len=plen, prefill_q=pq))
 
@@ -255,6 +257,10 @@ def test_prefill_gqa_and_f32():
                                     prefill_len=200, prefill_q=100))
     run_prefill_case(synth.Workload("pf_none", "bf16", 4, 4, 128, 0, seed=34, seq_lens=(5,),
                                     prefill_len=200, prefill_q=100))
+    run_prefill_case(synth.Workload("pf_gqa_long", "bf16", 8, 2, 128, 128, seed=35, seq_lens=(5,),
+                                    prefill_len=1400, prefill_q=1090))
+    run_prefill_case(synth.Workload("pf_d64_long", "bf16", 4, 4, 64, 128, seed=36, seq_lens=(5,),
+                                    prefill_len=1200, prefill_q=1200))
 
 
 def test_prefill_last_row_equals_decode():
