@@ -234,15 +234,16 @@ __global__ __launch_bounds__(NTHREADS, 2) void prefill_attn_kernel(Args a) {
 
 
 // ---------------------------------------------------------------------------------------
-// Long chunks: 256 queries x one head per workgroup of eight waves (32 queries each), K and
-// V tiles of 64 keys copied global -> LDS by the buffer-load-to-LDS path into a ring of four
-// stages (three tiles in flight, no staging registers, no address arithmetic per element),
-// both stored row-major [key][dim].  The V^T fragments the second product needs are read with
-// the LDS transpose read: in a group of 16 lanes, lane 4j + a supplies dims 4a .. 4a+3 of key
-// j, and lane i receives dim i of keys 0 .. 3 -- so the 16 lanes read a 4-key x 16-dim patch
-// and end up holding one dim each, in order.  16-byte chunks of a row are XOR-swizzled by the
-// key so that neither the K row reads nor the V patch reads collide on LDS banks; the
-// swizzle is applied on the global side of the copy (the LDS side of it is linear).
+// Long chunks: 384 queries x one head per workgroup of twelve waves (32 queries each, three
+// waves per SIMD: what hides the latencies here is other waves), K and V tiles of 64 keys
+// copied global -> LDS by the buffer-load-to-LDS path into a ring of four stages (three tiles in
+// flight, no staging registers, no address arithmetic per element), both stored row-major
+// [key][dim].  The V^T fragments the second product needs are read with the LDS transpose
+// read: in a group of 16 lanes, lane 4j + a supplies dims 4a .. 4a+3 of key j, and lane i
+// receives dim i of keys 0 .. 3 -- so the 16 lanes read a 4-key x 16-dim patch and end up
+// holding one dim each, in order.  16-byte chunks of a row are XOR-swizzled by the key so
+// that neither the K row reads nor the V patch reads collide on LDS banks; the swizzle is
+// applied on the global side of the copy (the LDS side of it is linear).
 namespace dma {
 
 #ifndef ECHOKV_LDS
@@ -251,7 +252,8 @@ namespace dma {
 using fused::rsrc_t;
 typedef short short4_t __attribute__((ext_vector_type(4)));
 
-constexpr int NST = 4, NTHREADS = 512, BQ = 256;
+// the first NCOPY waves issue the copies (a tile is 16 or 32 one-KB copies per operand)
+constexpr int NST = 4, NCOPY = 8, NWAVES = 12, NTHREADS = 64 * NWAVES, BQ = 32 * NWAVES;
 constexpr int kMinQueries = 1024;      // shorter chunks keep the four-wave kernel (more workgroups)
 
 template <int HD> struct Cfg {
@@ -259,9 +261,9 @@ template <int HD> struct Cfg {
   static constexpr int CH = HD / 8;                     // 16-byte chunks per row
   static constexpr int TILE = BKV * ROWB;               // bytes of one K (or V) tile
   static constexpr int STAGE = 2 * TILE;                // K tile then V tile
-  static constexpr int NL = TILE / 1024 / 8;            // 1 KB copies per wave per tile and operand
+  static constexpr int NL = TILE / 1024 / NCOPY;        // 1 KB copies per copying wave, tile and operand
   static constexpr int ROWS_PER_COPY = 1024 / ROWB;     // 4 (HD = 128) or 8 (HD = 64)
-  static constexpr int KSTEPS = HD / 16, CB = HD / 32, KG = KSTEPS / 4;
+  static constexpr int KSTEPS = HD / 16, CB = HD / 32;
   // chunk c of key row r is stored at chunk c ^ kswz(r) (K tile) / c ^ vswz(r) (V tile)
   __device__ static __forceinline__ int kswz(int r) { return CH == 16 ? (r & 15) : ((r ^ (r >> 3)) & 7); }
   __device__ static __forceinline__ int vswz(int r) { return CH == 16 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2); }
@@ -276,7 +278,6 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
   asm volatile("" ::: "memory");
 }
 
-
 // What a lane needs to issue its share of a tile's global -> LDS copies.
 template <int HD> struct CopyPlan {
   rsrc_t rk, rv;
@@ -290,6 +291,7 @@ template <int HD> struct CopyPlan {
 template <int HD>
 __device__ __forceinline__ void dma_tile(char* smem, const CopyPlan<HD>& cp, int t) {
   using C = Cfg<HD>;
+  if (cp.wave_u >= NCOPY) return;
   char* st = smem + (t & (NST - 1)) * C::STAGE;
   const int kv0 = t * BKV;
 #pragma unroll
@@ -347,32 +349,6 @@ __device__ __forceinline__ void wait_v(VFrag& f) {
 }
 
 
-// Four k-steps of K fragments (rows mb*32 + lane%32, 8 dims each).
-struct KFrag { fused::u32x4_t f[4][2]; };
-// koff[kk]: this lane's byte offset inside a K tile for k-step kk, rows 0..31 (rows 32..63: + 32 rows;
-// for d = 64 the swizzle of those rows differs in one bit, folded into koff1)
-template <int OFF>
-__device__ __forceinline__ fused::u32x4_t k_read(uint32_t addr) {
-  fused::u32x4_t v;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
-  return v;
-}
-template <int HD>
-__device__ __forceinline__ void read_k(KFrag& f, uint32_t sk, const uint32_t (&koff)[2][Cfg<HD>::KSTEPS], int g) {
-#pragma unroll
-  for (int k4 = 0; k4 < 4; ++k4) {
-    f.f[k4][0] = k_read<0>(sk + koff[0][g * 4 + k4]);
-    f.f[k4][1] = k_read<32 * Cfg<HD>::ROWB>(sk + koff[1][g * 4 + k4]);
-  }
-}
-template <int N>
-__device__ __forceinline__ void wait_k(KFrag& f) {
-  asm volatile("s_waitcnt lgkmcnt(%8)"
-               : "+v"(f.f[0][0]), "+v"(f.f[0][1]), "+v"(f.f[1][0]), "+v"(f.f[1][1]),
-                 "+v"(f.f[2][0]), "+v"(f.f[2][1]), "+v"(f.f[3][0]), "+v"(f.f[3][1])
-               : "n"(N));
-}
-
 template <int HD>
 __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
   using C = Cfg<HD>;
@@ -421,8 +397,8 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
     for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
   const float scale2 = a.scale * 1.44269504088896340736f;    // softmax in base 2
-  const int qpos_min = a.q_pos0 + min(i0 + wave * 32, a.T_q - 1);
-  const int qpos_max = a.q_pos0 + min(i0 + wave * 32 + 31, a.T_q - 1);
+  const int qpos_min = a.q_pos0 + min(i0 + wave_u * 32, a.T_q - 1);
+  const int qpos_max = a.q_pos0 + min(i0 + wave_u * 32 + 31, a.T_q - 1);
   const int kv_end = min(Ltot, a.q_pos0 + min(i0 + BQ, a.T_q));   // keys any query of the block sees
   const int ntiles = (kv_end + BKV - 1) / BKV;
 
@@ -434,12 +410,6 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
   const int vkey = 4 * lh + (s16 >> 2);                        // + 16 ts (+ 8 for the second half)
   const int vch = 2 * blk2 + ((s16 & 3) >> 1);                 // + 4 cb, before the swizzle
   const uint32_t vbyte = (uint32_t)((s16 & 1) * 8);
-  uint32_t koff[2][C::KSTEPS];
-#pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-    for (int kk = 0; kk < C::KSTEPS; ++kk)     // the + 32 rows of mb = 1 ride in the instruction offset
-      koff[mb][kk] = (uint32_t)(lr * C::ROWB + (((kk * 2 + lh) ^ C::kswz(mb * 32 + lr)) << 4));
   uint32_t voff[C::CB];
 #pragma unroll
   for (int cb = 0; cb < C::CB; ++cb)      // the swizzle of key vkey + 16 ts (+ 8) does not depend on ts
@@ -453,30 +423,21 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
     if (kv0 > qpos_max) continue;      // wholly past this wave's queries (wave-uniform)
     const char* sk = smem + (t & (NST - 1)) * C::STAGE;
     const char* sv = sk + C::TILE;
-    // ---- S^T = K Q^T : all K fragments of the tile are requested up front, four k-steps per group
-    const uint32_t sku = lds_addr(sk), svu = lds_addr(sv);
-    KFrag kb[C::KG];
-#pragma unroll
-    for (int g = 0; g < C::KG; ++g) read_k<HD>(kb[g], sku, koff, g);
+    // ---- S^T = K Q^T
+    const uint32_t svu = lds_addr(sv);
     floatx16_t sacc[2];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[mb][r] = 0.f;
 #pragma unroll
-    for (int g = 0; g < C::KG; ++g) {
-      if (g == 0) wait_k<(C::KG - 1) * 8>(kb[0]); else wait_k<0>(kb[C::KG - 1]);
+    for (int kk = 0; kk < C::KSTEPS; ++kk)
 #pragma unroll
-      for (int k4 = 0; k4 < 4; ++k4)
-#pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-          sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kb[g].f[k4][mb]),
-                                                             qf[g * 4 + k4], sacc[mb], 0, 0, 0);
-    }
-    // the first two k-steps of V^T arrive while the softmax runs
-    VFrag vb[2];
-    read_v<HD, 0>(vb[0], svu, voff);
-    read_v<HD, 1>(vb[1], svu, voff);
+      for (int mb = 0; mb < 2; ++mb) {
+        const int row = mb * 32 + lr, c = kk * 2 + lh;
+        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sk + row * C::ROWB + ((c ^ C::kswz(row)) << 4));
+        sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[mb], 0, 0, 0);
+      }
     // ---- online softmax, lane-local (keys: mb*32 + 8*(r/4) + 4*lh + r%4), base 2, scale folded in
     if (kv0 + BKV - 1 > qpos_min) {
 #pragma unroll
@@ -516,18 +477,20 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
     }
     // ---- O^T += V^T P^T : k-step ts, element e of lane half lh <-> key 16 ts + 4 lh + (e < 4 ? e : e + 4).
     //      The transpose reads are issued by hand one k-step ahead of the MFMAs that use them.
-#pragma unroll
-    for (int ts = 0; ts < 4; ++ts) {
-      if (ts == 0) wait_v<2 * C::CB, C::CB>(vb[0]);
-      if (ts == 1) { read_v<HD, 2>(vb[0], svu, voff); wait_v<2 * C::CB, C::CB>(vb[1]); }
-      if (ts == 2) { read_v<HD, 3>(vb[1], svu, voff); wait_v<2 * C::CB, C::CB>(vb[0]); }
-      if (ts == 3) wait_v<0, C::CB>(vb[1]);
+    VFrag vb;
+    auto pv = [&](int ts) {
+      wait_v<0, C::CB>(vb);
 #pragma unroll
       for (int cb = 0; cb < C::CB; ++cb) {
-        const short8_t vv = __builtin_shufflevector(vb[ts & 1].lo[cb], vb[ts & 1].hi[cb], 0, 1, 2, 3, 4, 5, 6, 7);
+        const short8_t vv = __builtin_shufflevector(vb.lo[cb], vb.hi[cb], 0, 1, 2, 3, 4, 5, 6, 7);
         oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv), pf[ts], oacc[cb], 0, 0, 0);
       }
-    }
+    };
+    // (one k-step of fragments at a time: the other waves of the SIMD cover the LDS latency)
+    read_v<HD, 0>(vb, svu, voff); pv(0);
+    read_v<HD, 1>(vb, svu, voff); pv(1);
+    read_v<HD, 2>(vb, svu, voff); pv(2);
+    read_v<HD, 3>(vb, svu, voff); pv(3);
   }
   wait_loads_and_barrier<0>();         // the ring's last copies have landed before the workgroup ends
   // ---- finish: this lane holds query qi, head dims cb*32 + 8*(r/4) + 4*lh + r%4
@@ -589,7 +552,7 @@ inline int launch_prefill_mfma(int H_q, int H_kv, int d, int m, int d_out, int n
     a.out = out; a.lse = lse;
     a.H_q = H_q; a.G = H_q / H_kv; a.m = m; a.d_out = d_out; a.n_ret_heads = n_ret_heads;
     a.T_q = T_q; a.q_pos0 = q_pos0; a.out_bf16 = out_bf16 ? 1 : 0; a.scale = scale;
-    // long chunks take the eight-wave kernel with the LDS ring (its 32-bit row offsets must fit)
+    // long chunks take the twelve-wave kernel with the LDS ring (its 32-bit row offsets must fit)
     const int64_t span = (int64_t)(q_pos0 + T_q) * (m > d_out ? m : d_out) * 2;
     if (T_q >= prefill::dma::kMinQueries && span < (int64_t)1 << 31) {
       const dim3 grid((T_q + prefill::dma::BQ - 1) / prefill::dma::BQ, H_q), blk(prefill::dma::NTHREADS);
