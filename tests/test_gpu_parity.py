@@ -263,6 +263,23 @@ def test_prefill_gqa_and_f32():
                                     prefill_len=1200, prefill_q=1200))
 
 
+def test_prefill_growing_scores():
+    """Keys whose norm grows along the sequence: the running maxima keep moving, so the
+    long-chunk kernel has to raise its reference maxima and rescale several times."""
+    w = synth.Workload("pf_grow", "bf16", 4, 4, 128, 512, seed=37, seq_lens=(5,),
+                       prefill_len=1300, prefill_q=1200)
+    inp = synth.generate(w)
+    r = inp.rows(inp.n_decode)
+    L = inp.seq_len[inp.n_decode]
+    ramp = (1.0 + 10.0 * torch.arange(L, dtype=torch.float32) / L)[:, None]
+    inp.K_r[r] = (inp.K_r[r].float() * ramp).to(inp.K_r.dtype)
+    dw = DeviceWorkload(inp)
+    out, lse = dw.prefill(); torch.cuda.synchronize()
+    o_ref, l_ref = ref.prefill_ref(inp)
+    check(host(out), o_ref, w.dtype, "prefill, growing scores")
+    assert np.abs(host(lse) - l_ref).max() <= 2e-2
+
+
 def test_prefill_last_row_equals_decode():
     w = SMALL[4].scaled(prefill_len=300, prefill_q=40)
     inp = synth.generate(w)
