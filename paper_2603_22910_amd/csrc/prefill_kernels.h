@@ -529,8 +529,14 @@ template <int HD>
 inline int launch(dim3 grid, dim3 blk, hipStream_t st, const Args& a) {
   constexpr int lds = NST * Cfg<HD>::STAGE;          // 128 KB (d = 128) or 64 KB of dynamic LDS
   void (*fn)(Args) = prefill_attn_dma_kernel<HD>;
-  if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
-    return 7;
+  static bool allowed[64] = {};                      // per device: the attribute is set once
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 7;
+  if (!allowed[dev]) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+      return 7;
+    allowed[dev] = true;
+  }
   hipLaunchKernelGGL(fn, grid, blk, lds, st, a);
   return hipGetLastError() != hipSuccess ? 7 : 0;
 }

@@ -280,6 +280,19 @@ def test_prefill_growing_scores():
     assert np.abs(host(lse) - l_ref).max() <= 2e-2
 
 
+def test_prefill_long_chunk_f32_out():
+    """fp32 outputs of the long-chunk kernel (no output rounding: what is left is the bf16
+    rounding of P and of the predicted K, V)."""
+    w = synth.Workload("pf_f32out", "bf16", 8, 4, 128, 256, seed=38, seq_lens=(5,),
+                       prefill_len=1411, prefill_q=1100)
+    inp = synth.generate(w)
+    dw = DeviceWorkload(inp, out_dtype="f32")
+    out, lse = dw.prefill(); torch.cuda.synchronize()
+    o_ref, l_ref = ref.prefill_ref(inp)
+    check(host(out), o_ref, "bf16", "prefill long chunk, f32 out")
+    assert np.abs(host(lse) - l_ref).max() <= 2e-2
+
+
 def test_prefill_last_row_equals_decode():
     w = SMALL[4].scaled(prefill_len=300, prefill_q=40)
     inp = synth.generate(w)
