@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import shutil
 import subprocess
 import sys
@@ -14,7 +15,13 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    "-Rpass-analysis=kernel-resource-usage",
 ]
+
+# Kernels that count their own outstanding global loads (manual s_waitcnt vmcnt(N) around
+# global -> LDS copies).  Register spills go through the same counter, so a spill in one of
+# them would make those waits meaningless: the build refuses it.
+NO_SPILL_KERNELS = ("fused_decode_dma_kernel", "prefill_attn_dma_kernel", "absorbed13scores_kernel")
 
 
 def hipcc_path() -> str:
@@ -35,8 +42,27 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
         raise RuntimeError("hipcc failed building libechokv.so")
+    spilled = check_spills(res.stdout + res.stderr)
+    if spilled:
+        raise RuntimeError("register spills in kernels that count their own loads: "
+                           + ", ".join(f"{k} ({n})" for k, n in spilled))
     os.replace(LIB_PATH + ".tmp", LIB_PATH)
     return LIB_PATH
+
+
+def check_spills(remarks: str):
+    """(kernel, spilled registers) for every NO_SPILL_KERNELS instance that spills, from the
+    compiler's resource-usage remarks."""
+    bad, cur = [], None
+    for line in remarks.splitlines():
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            cur = m.group(1)
+            continue
+        m = re.search(r"VGPRs Spill: (\d+)", line)
+        if m and cur and int(m.group(1)) > 0 and any(k in cur for k in NO_SPILL_KERNELS):
+            bad.append((cur, int(m.group(1))))
+    return bad
 
 
 if __name__ == "__main__":

@@ -764,8 +764,9 @@ __global__ __launch_bounds__(NTHREADS) void fused_kscores_kernel(Args a, SeqMeta
   const int H_kv = a.H_q / a.G;
   float* srow = a.s_out + (int64_t)meta.sbase[b] * kSlotTokens + jw0 + lr;
   KExtra x = make_kextra(a.rope_cos, a.rope_sin, 0, 0, L);
+  if (HPW == 1 && kvh0 >= H_kv) return;      // columns past the last head (an exit, not a branch to rejoin)
   k_scores<HD, ROPE>(acc, sm.e, a.G, wave, lane, jw0, L, x, [&](float (&s)[4], int hw, int g) {
-    if (kvh0 + hw >= H_kv) return;
+    if (HPW > 1 && kvh0 + hw >= H_kv) return;
     float* dst = srow + (int64_t)((kvh0 + hw) * a.G + g) * a.s_ld;
 #pragma unroll
     for (int ji = 0; ji < 4; ++ji) {
