@@ -367,6 +367,26 @@ def echokv_decode_paper(q, K_a, V_a, K_r, V_r, W_K, W_V, n_kv_heads: int,
     return o[0], lse[0]
 
 
+def echokv_prefill_paper(Q, K_a, V_a, K_r, V_r, W_K, W_V, n_kv_heads: int, q_pos0: int,
+                         scale: Optional[float] = None,
+                         rope: Optional[Tuple[np.ndarray, np.ndarray]] = None):
+    """echokv_prefill with the rotary embedding of the paper's inference: cached
+    keys are pre-rotation, token j's rebuilt key is rotated to position j before
+    the dot products; Q [T_q, H_q, d] must come in already rotated (query i to
+    position q_pos0 + i).  Returns (out [T_q, H_q, d], lse [T_q, H_q])."""
+    T_q = Q.shape[0]
+    L = K_a.shape[0]
+    if q_pos0 < 0 or q_pos0 + T_q > L:
+        raise ValueError("cache must already hold the chunk: need q_pos0 + T_q <= L")
+    K_t = reconstruct(K_a, K_r, W_K)
+    V_t = reconstruct(V_a, V_r, W_V)
+    if rope is not None:
+        K_t = rope_rotate(K_t, range(L), rope[0], rope[1], n_kv_heads)
+    vis = [q_pos0 + i + 1 for i in range(T_q)]
+    o, lse, _ = attention_rows(Q, K_t, V_t, n_kv_heads, scale, visible=vis)
+    return o, lse
+
+
 def brute_force_decode_paper(q, K_a, V_a, K_r, V_r, W_K, W_V, n_kv_heads: int,
                              scale=None, rope=None, window=None):
     """echokv_decode_paper again as scalar loops (tiny shapes)."""

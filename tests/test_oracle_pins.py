@@ -527,6 +527,35 @@ def test_decode_paper_without_extras_is_plain_decode_and_rope_is_applied_after_r
     assert np.abs(o2 - o0).max() > 1e-3
 
 
+def test_prefill_paper_rows_are_library_causal_attention_over_rotated_keys_and_decodes_of_the_prefix():
+    c, Q = make_case(4, 2, 8, 8, 29, seed=6, T_q=7)
+    q_pos0 = 29 - 7
+    cos, sin = angle_tables(8, 40)
+    # no tables: the plain prefill
+    o0, l0 = orc.echokv_prefill(Q, **c, n_kv_heads=2, q_pos0=q_pos0)
+    o1, l1 = orc.echokv_prefill_paper(Q, **c, n_kv_heads=2, q_pos0=q_pos0)
+    np.testing.assert_array_equal(o0, o1); np.testing.assert_array_equal(l0, l1)
+    # with tables: library causal attention over keys rotated (scalar loops) after the rebuild
+    o2, l2 = orc.echokv_prefill_paper(Q, **c, n_kv_heads=2, q_pos0=q_pos0, rope=(cos, sin))
+    K_t = orc.reconstruct(c["K_a"], c["K_r"], c["W_K"]); V_t = orc.reconstruct(c["V_a"], c["V_r"], c["W_V"])
+    K_rot = K_t.reshape(29, 2, 8).copy()
+    for j in range(29):
+        for i in range(4):
+            a, b = K_t.reshape(29, 2, 8)[j, :, i], K_t.reshape(29, 2, 8)[j, :, i + 4]
+            K_rot[j, :, i] = a * cos[j, i] - b * sin[j, i]
+            K_rot[j, :, i + 4] = b * cos[j, i] + a * sin[j, i]
+    np.testing.assert_allclose(o2, sdpa(Q, K_rot.reshape(29, 16), V_t, 2, causal_from=q_pos0),
+                               rtol=1e-11, atol=1e-12)
+    assert np.abs(o2 - o0).max() > 1e-3
+    # row i is the paper-faithful decode over the first q_pos0 + i + 1 tokens
+    for i in (0, 3, 6):
+        n = q_pos0 + i + 1
+        pre = {k: (v[:n] if k in ("K_a", "V_a", "K_r", "V_r") else v) for k, v in c.items()}
+        od, ld = orc.echokv_decode_paper(Q[i], **pre, n_kv_heads=2, rope=(cos, sin))
+        np.testing.assert_allclose(o2[i], od, rtol=1e-11, atol=1e-12)
+        np.testing.assert_allclose(l2[i], ld, rtol=1e-11, atol=1e-12)
+
+
 # ---- P14: uncompressed sink + local window --------------------------------------
 def test_window_ring_holds_exactly_the_sink_and_latest_tokens():
     n_sink, n_recent, D = 4, 6, 3
