@@ -281,6 +281,23 @@ int echokv_prefill_attn(const echokv_shape *shape, const echokv_layer_cache *anc
                         int32_t q_pos0, void *out, float *lse_out, void *workspace,
                         size_t workspace_bytes, void *hip_stream);
 
+/* echokv_prefill_attn with the rotary embedding of the paper's inference (Sec.
+ * "Network Architecture": the caches hold pre-rotation keys): with
+ * extras->rope_cos / rope_sin set, the key of cached token j -- retained or
+ * predicted -- is rotated to position j before the dot products, with the
+ * pairing and table layout described above echokv_decode_extras; q must come in
+ * already rotated (query i to position q_pos0 + i); rope_positions >=
+ * q_pos0 + T_q.  A prefill chunk reads the compressed cache only: extras with
+ * window pointers are refused (ECHOKV_ERR_UNSUPPORTED).  extras == NULL or no
+ * tables: the same as echokv_prefill_attn.  Same workspace size.  (bf16: the
+ * rotated keys are rounded to bf16 once more before the attention products.) */
+int echokv_prefill_attn_ex(const echokv_shape *shape, const echokv_layer_cache *anchor,
+                           const echokv_layer_cache *target, const void *w_k,
+                           const void *w_v, int32_t seq, const void *q, int32_t T_q,
+                           int32_t q_pos0, const echokv_decode_extras *extras, void *out,
+                           float *lse_out, void *workspace, size_t workspace_bytes,
+                           void *hip_stream);
+
 /* Measurement aid (no paper passage: it exists so that a benchmark can report
  * the duration of the kernel that dominates echokv_decode_attn, the fused
  * predictor-product + attention kernel, separately from the whole call).

@@ -27,7 +27,8 @@ EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn",
            "echokv_profile_enable", "echokv_profile_read", "echokv_pack_weights",
            "echokv_cache_compress", "echokv_decode_attn_ex", "echokv_window_append",
-           "echokv_mlp_workspace_bytes", "echokv_decode_attn_mlp", "echokv_profile_stream_read", "echokv_fit_workspace_bytes", "echokv_fit_linear")
+           "echokv_mlp_workspace_bytes", "echokv_decode_attn_mlp", "echokv_profile_stream_read",
+           "echokv_fit_workspace_bytes", "echokv_fit_linear", "echokv_prefill_attn_ex")
 ACT_RELU, ACT_SILU = 1, 2
 
 
@@ -112,6 +113,11 @@ def load() -> C.CDLL:
                                         C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_int32,
                                         C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                         C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.echokv_prefill_attn_ex.restype = C.c_int
+    lib.echokv_prefill_attn_ex.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
+                                           C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_int32,
+                                           C.c_void_p, C.c_int32, C.c_int32, C.POINTER(DecodeExtras),
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.echokv_cache_compress.restype = C.c_int
     lib.echokv_cache_compress.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
                                           C.POINTER(LayerCacheC), C.c_void_p]
@@ -303,6 +309,22 @@ def prefill_attn(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v,
                                       seq, _ptr(q), T_q, q_pos0, _ptr(out), _ptr(lse_out),
                                       _ptr(workspace), nbytes, _stream(stream)),
            "echokv_prefill_attn")
+
+
+def prefill_attn_ex(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, seq: int, q,
+                    T_q: int, q_pos0: int, out, lse_out, workspace, rope=None, window=None, stream=None):
+    """rope = (cos, sin) device fp32 [positions, d/2]; window is refused by the library."""
+    a, t = anchor.as_c(), target.as_c()
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ex = DecodeExtras()
+    if rope is not None:
+        ex.rope_cos, ex.rope_sin, ex.rope_positions = _ptr(rope[0]), _ptr(rope[1]), int(rope[0].shape[0])
+    if window is not None:
+        ex.win_k, ex.win_v, ex.n_sink, ex.n_recent = _ptr(window[0]), _ptr(window[1]), int(window[2]), int(window[3])
+    _check(load().echokv_prefill_attn_ex(C.byref(shape), C.byref(a), C.byref(t), _ptr(w_k), _ptr(w_v),
+                                         seq, _ptr(q), T_q, q_pos0, C.byref(ex), _ptr(out),
+                                         _ptr(lse_out), _ptr(workspace), nbytes, _stream(stream)),
+           "echokv_prefill_attn_ex")
 
 
 def pack_weights(shape: Shape, w, w_packed, stream=None):

@@ -384,6 +384,11 @@ int reconstruct_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_
 // bf16: the MFMA attention kernel keeps its softmax state in registers, so only
 // the materialised predicted dims live in the workspace; the fp32 streaming
 // path also needs split-K partials for one launch of query rows.
+int64_t prefill_part_slots(const Dims& dm, int64_t Ltot, int max_q);
+// The MFMA prefill path keeps room for a rotated copy of the retained keys behind the plan.
+size_t prefill_krot_offset(const Dims& dm, int64_t Ltot, int max_q) {
+  return align_up(plan_ws(dm, prefill_part_slots(dm, Ltot, max_q), (int64_t)slots_for(Ltot) * kSlotTokens).total);
+}
 int64_t prefill_part_slots(const Dims& dm, int64_t Ltot, int max_q) {
   const bool mfma = dm.bf16 && prefill_mfma_supported<bf16_t>(dm.d);
   return mfma ? 0 : (int64_t)std::min(max_q, kPrefillQChunk) * slots_for(Ltot);
@@ -394,7 +399,8 @@ int64_t prefill_part_slots(const Dims& dm, int64_t Ltot, int max_q) {
 template <typename T>
 int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_layer_cache* tg,
                  const void* w_k, const void* w_v, int seq, const void* q, int T_q, int q_pos0,
-                 void* out, float* lse, char* ws, hipStream_t st) {
+                 const float* rope_cos, const float* rope_sin, void* out, float* lse, char* ws,
+                 hipStream_t st) {
   const int n_ret_heads = dm.g0, n_rec_heads = dm.H_kv - n_ret_heads;
   const int Ltot = q_pos0 + T_q;
   const int64_t row0 = an->seq_start[seq];
@@ -425,8 +431,21 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
     }
   }
   if (prefill_mfma_supported<T>(dm.d)) {
+    const T* k_ret = (const T*)tg->k + row0 * dm.m;
+    if constexpr (sizeof(T) == 2) {
+      if (rope_cos) {
+        // rotary embedding: the predicted keys are rotated in place in the workspace, the
+        // retained ones into a copy next to them; the attention kernels then run unchanged
+        T* krot = (T*)(ws + prefill_krot_offset(dm, Ltot, T_q));
+        int rc = launch_rope_rows(kh, dm.d_out_v, kh, dm.d_out_v, n_rec_heads, dm.d, Ltot, rope_cos, rope_sin, st);
+        if (rc) return rc;
+        rc = launch_rope_rows(k_ret, dm.m, krot, dm.m, n_ret_heads, dm.d, Ltot, rope_cos, rope_sin, st);
+        if (rc) return rc;
+        if (n_ret_heads > 0) k_ret = krot;
+      }
+    }
     return launch_prefill_mfma<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale, dm.out_bf16,
-                                  (const T*)tg->k + row0 * dm.m, (const T*)tg->v + row0 * dm.m,
+                                  k_ret, (const T*)tg->v + row0 * dm.m,
                                   kh, vh, (const T*)q, T_q, q_pos0, out, lse, st);
   }
   // streaming path: each query is a virtual sequence of length q_pos0 + i + 1
@@ -442,6 +461,7 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
       AttnArgs<T> a;
       a.k = (const T*)tg->k; a.v = (const T*)tg->v; a.ld = dm.m; a.col0 = 0; a.head0 = 0;
       a.row_mode = 0; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
+      a.rope_cos = rope_cos; a.rope_sin = rope_sin;
       a.split_tokens = pick_split_tokens(tokens, n_ret_heads);
       a.part_o = po; a.part_ml = pml;
       stream_step = a.split_tokens / kSlotTokens;
@@ -452,6 +472,7 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
       AttnArgs<T> a;
       a.k = kh; a.v = vh; a.ld = dm.d_out_v; a.col0 = 0; a.head0 = n_ret_heads;
       a.row_mode = 2; a.q = qq; a.H_q = dm.H_q; a.G = dm.G; a.d = dm.d; a.scale = dm.scale;
+      a.rope_cos = rope_cos; a.rope_sin = rope_sin;
       a.split_tokens = pick_split_tokens(tokens, n_rec_heads);
       a.part_o = po; a.part_ml = pml;
       fused_step = a.split_tokens / kSlotTokens;
@@ -752,7 +773,8 @@ size_t decode_ws_bytes(const Dims& dm, int batch, int64_t total_tokens, bool unf
   return plan_ws(dm, slots, unfused ? slots * kSlotTokens : 0).total;
 }
 size_t prefill_ws_bytes(const Dims& dm, int64_t Ltot, int max_q) {
-  return plan_ws(dm, prefill_part_slots(dm, Ltot, max_q), (int64_t)slots_for(Ltot) * kSlotTokens).total;
+  const bool mfma = dm.bf16 && prefill_mfma_supported<bf16_t>(dm.d);
+  return prefill_krot_offset(dm, Ltot, max_q) + (mfma ? align_up((size_t)Ltot * dm.m * dm.es) : 0);
 }
 
 }  // namespace
@@ -1247,10 +1269,11 @@ int echokv_fit_linear(const echokv_shape* shape, const void* anchor_rows, const 
   return ECHOKV_OK;
 }
 
-int echokv_prefill_attn(const echokv_shape* shape, const echokv_layer_cache* anchor,
-                        const echokv_layer_cache* target, const void* w_k, const void* w_v,
-                        int32_t seq, const void* q, int32_t T_q, int32_t q_pos0, void* out,
-                        float* lse_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+int echokv_prefill_attn_ex(const echokv_shape* shape, const echokv_layer_cache* anchor,
+                           const echokv_layer_cache* target, const void* w_k, const void* w_v,
+                           int32_t seq, const void* q, int32_t T_q, int32_t q_pos0,
+                           const echokv_decode_extras* extras, void* out, float* lse_out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
   Dims dm;
   int rc = check_shape(shape, &dm);
   if (rc) return rc;
@@ -1262,12 +1285,28 @@ int echokv_prefill_attn(const echokv_shape* shape, const echokv_layer_cache* anc
   if ((int64_t)q_pos0 + T_q > anchor->seq_len[seq]) return ECHOKV_ERR_SHAPE;
   if (dm.d_out > 0 && (!w_k || !w_v)) return ECHOKV_ERR_NULL;
   if (!q || !out) return ECHOKV_ERR_NULL;
+  const float* rope_cos = nullptr; const float* rope_sin = nullptr;
+  if (extras) {
+    if ((extras->rope_cos == nullptr) != (extras->rope_sin == nullptr)) return ECHOKV_ERR_NULL;
+    // the uncompressed window is a decode-side structure: a prefill chunk reads the compressed cache
+    if (extras->win_k || extras->win_v) return ECHOKV_ERR_UNSUPPORTED;
+    if (extras->rope_cos && extras->rope_positions < q_pos0 + T_q) return ECHOKV_ERR_SHAPE;
+    rope_cos = extras->rope_cos; rope_sin = extras->rope_sin;
+  }
   const size_t need = prefill_ws_bytes(dm, (int64_t)q_pos0 + T_q, T_q);
   if (!workspace || workspace_bytes < need) return ECHOKV_ERR_WORKSPACE;
   if ((uintptr_t)workspace % 256) return ECHOKV_ERR_WORKSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
-  return dm.bf16 ? prefill_impl<bf16_t>(dm, anchor, target, w_k, w_v, seq, q, T_q, q_pos0, out, lse_out, (char*)workspace, st)
-                 : prefill_impl<float>(dm, anchor, target, w_k, w_v, seq, q, T_q, q_pos0, out, lse_out, (char*)workspace, st);
+  return dm.bf16 ? prefill_impl<bf16_t>(dm, anchor, target, w_k, w_v, seq, q, T_q, q_pos0, rope_cos, rope_sin, out, lse_out, (char*)workspace, st)
+                 : prefill_impl<float>(dm, anchor, target, w_k, w_v, seq, q, T_q, q_pos0, rope_cos, rope_sin, out, lse_out, (char*)workspace, st);
+}
+
+int echokv_prefill_attn(const echokv_shape* shape, const echokv_layer_cache* anchor,
+                        const echokv_layer_cache* target, const void* w_k, const void* w_v,
+                        int32_t seq, const void* q, int32_t T_q, int32_t q_pos0, void* out,
+                        float* lse_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return echokv_prefill_attn_ex(shape, anchor, target, w_k, w_v, seq, q, T_q, q_pos0, nullptr, out,
+                                lse_out, workspace, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

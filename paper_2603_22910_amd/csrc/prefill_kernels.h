@@ -545,6 +545,58 @@ inline int launch(dim3 grid, dim3 blk, hipStream_t st, const Args& a) {
 
 }  // namespace prefill
 
+// Rotary embedding of key rows ahead of the prefill attention kernels (Sec. "Network
+// Architecture": caches hold pre-rotation keys): row j of src [rows, n_heads * d] (pitch
+// ld_src) is rotated to position j, feature i of a head pairing with i + d/2, and written
+// to dst (pitch ld_dst; dst may be src).  One thread per 8 + 8 paired features.
+struct RopeRowsArgs {
+  const bf16_t* src; bf16_t* dst;
+  int64_t ld_src, ld_dst;
+  int32_t n_heads, d, rows;
+  const float* cos; const float* sin;      // [>= rows, d / 2]
+};
+__global__ __launch_bounds__(256) void rope_rows_kernel(RopeRowsArgs a) {
+  const int cpr = a.d / 16;                               // threads per head
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t per_row = (int64_t)a.n_heads * cpr;
+  if (idx >= per_row * a.rows) return;
+  const int row = (int)(idx / per_row);
+  const int rem = (int)(idx % per_row), head = rem / cpr, c = rem % cpr;
+  const int half = a.d / 2;
+  const bf16_t* sp = a.src + (int64_t)row * a.ld_src + head * a.d + c * 8;
+  const fused::u32x4_t xa = *reinterpret_cast<const fused::u32x4_t*>(sp);
+  const fused::u32x4_t xb = *reinterpret_cast<const fused::u32x4_t*>(sp + half);
+  const float* cr = a.cos + (int64_t)row * half + c * 8;
+  const float* sr = a.sin + (int64_t)row * half + c * 8;
+  fused::u32x4_t ya, yb;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    uint32_t oa = 0, ob = 0;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const float fa = __uint_as_float(((xa[w] >> (16 * e)) & 0xffffu) << 16);
+      const float fb = __uint_as_float(((xb[w] >> (16 * e)) & 0xffffu) << 16);
+      const float cs = cr[2 * w + e], sn = sr[2 * w + e];
+      oa |= (uint32_t)f32_to_bf16(fa * cs - fb * sn) << (16 * e);
+      ob |= (uint32_t)f32_to_bf16(fb * cs + fa * sn) << (16 * e);
+    }
+    ya[w] = oa; yb[w] = ob;
+  }
+  bf16_t* dp = a.dst + (int64_t)row * a.ld_dst + head * a.d + c * 8;
+  *reinterpret_cast<fused::u32x4_t*>(dp) = ya;
+  *reinterpret_cast<fused::u32x4_t*>(dp + half) = yb;
+}
+inline int launch_rope_rows(const bf16_t* src, int64_t ld_src, bf16_t* dst, int64_t ld_dst, int n_heads,
+                            int d, int rows, const float* cos, const float* sin, hipStream_t st) {
+  if (n_heads <= 0 || rows <= 0) return 0;
+  RopeRowsArgs a;
+  a.src = src; a.dst = dst; a.ld_src = ld_src; a.ld_dst = ld_dst; a.n_heads = n_heads; a.d = d;
+  a.rows = rows; a.cos = cos; a.sin = sin;
+  const int64_t n = (int64_t)rows * n_heads * (d / 16);
+  hipLaunchKernelGGL(rope_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, a);
+  return hipGetLastError() != hipSuccess ? 7 : 0;
+}
+
 template <typename T> inline bool prefill_mfma_supported(int d) {
   return sizeof(T) == 2 && (d == 64 || d == 128);
 }

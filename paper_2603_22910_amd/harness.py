@@ -105,13 +105,29 @@ class DeviceWorkload:
         finally:
             self.shape.flags = saved
 
-    def _prefill(self, stream=None):
+    def _prefill(self, stream=None, rope=None):
         seq = self.inp.n_decode
         T_q = int(self.q_prefill.shape[0])
-        ek.prefill_attn(self.shape, self.anchor_all, self.target_all, self.W_K, self.W_V, seq,
-                        self.q_prefill, T_q, self.inp.q_pos0, self.out_prefill, self.lse_prefill,
-                        self.workspace, stream)
+        if rope is None:
+            ek.prefill_attn(self.shape, self.anchor_all, self.target_all, self.W_K, self.W_V, seq,
+                            self.q_prefill, T_q, self.inp.q_pos0, self.out_prefill, self.lse_prefill,
+                            self.workspace, stream)
+        else:
+            ek.prefill_attn_ex(self.shape, self.anchor_all, self.target_all, self.W_K, self.W_V, seq,
+                               self.q_prefill, T_q, self.inp.q_pos0, self.out_prefill,
+                               self.lse_prefill, self.workspace, rope=rope, stream=stream)
         return self.out_prefill, self.lse_prefill
+
+    def prefill_ex(self, rope, stream=None):
+        """rope = (cos, sin) host or device fp32 tables [positions, d/2]."""
+        rope = tuple(t.to(self.dev).contiguous() for t in rope)
+        self._keep = rope
+        saved = self.shape.flags
+        self.shape.flags = saved & ~ek.FLAG_W_PACKED
+        try:
+            return self._prefill(stream, rope)
+        finally:
+            self.shape.flags = saved
 
     def reconstruct(self, seq: int, tok_begin: int, tok_end: int, stream=None):
         w = self.w

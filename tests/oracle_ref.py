@@ -41,6 +41,16 @@ def prefill_ref(inp, scale=None):
                               inp.w.n_kv_heads, inp.q_pos0, scale)
 
 
+def prefill_paper_ref(inp, rope, scale=None):
+    """rope = (cos, sin) torch fp32 tables."""
+    b = inp.n_decode
+    K_a, V_a, K_r, V_r = seq_arrays(inp, b)
+    W_K, W_V = weights(inp)
+    return orc.echokv_prefill_paper(f64(inp.q_prefill), K_a, V_a, K_r, V_r, W_K, W_V,
+                                    inp.w.n_kv_heads, inp.q_pos0, scale,
+                                    rope=(f64(rope[0]), f64(rope[1])))
+
+
 def reconstruct_ref(inp, b, t0, t1):
     K_a, V_a, K_r, V_r = seq_arrays(inp, b)
     W_K, W_V = weights(inp)

@@ -207,6 +207,23 @@ def test_decode_extras_argument_errors(lib):
                 rope=(_Tbl(200), _Tbl(200)), stream=0) == ek.ERR_UNSUPPORTED
 
 
+def test_prefill_extras_argument_errors(lib):
+    sh = ek.make_shape(8, 8, 64, 256, "f32")
+    a, t = caches(lens=(100,))
+    big = _Ws(1 << 30)
+    base = (sh, a, t, FAKE, FAKE, 0, FAKE, 10, 90, FAKE, None, big)
+    # tables shorter than the chunk's last position
+    assert code(ek.prefill_attn_ex, *base, rope=(_Tbl(99), _Tbl(99)), stream=0) == ek.ERR_SHAPE
+    # a prefill chunk reads the compressed cache only
+    assert code(ek.prefill_attn_ex, *base, window=(_Tbl(1), _Tbl(1), 4, 128), stream=0) == ek.ERR_UNSUPPORTED
+    # one table missing
+    import ctypes as C
+    half = ek.DecodeExtras(); half.rope_cos = FAKE; half.rope_positions = 200
+    a_c, t_c = a.as_c(), t.as_c()
+    assert lib.echokv_prefill_attn_ex(C.byref(sh), C.byref(a_c), C.byref(t_c), FAKE, FAKE, 0, FAKE, 10, 90,
+                                      C.byref(half), FAKE, None, FAKE, 1 << 30, None) == ek.ERR_NULL
+
+
 def test_window_append_argument_errors(lib):
     sh = ek.make_shape(8, 8, 64, 256, "f32")
     assert code(ek.window_append, sh, None, FAKE, 4, 128, [5], FAKE, FAKE, [1], stream=0) == ek.ERR_NULL

@@ -166,3 +166,50 @@ def test_decode_extras_full_size_sampled():
         assert np.isfinite(got).all()
         check(got, o_ref, "bf16", f"cfg3-shaped 32K rope+window, {name}")
         assert np.abs(host(lse) - l_ref).max() <= 2e-2
+
+
+# ---- causal prefill with the rotary embedding ---------------------------------------
+@pytest.mark.parametrize("H_q,H_kv,d,m,dtype,plen,pq", [
+    (8, 8, 128, 512, "bf16", 400, 300),       # short-chunk kernel, MHA, half retained
+    (8, 2, 128, 128, "bf16", 1400, 1090),     # long-chunk kernel, GQA 4:1, ragged
+    (8, 4, 64, 128, "bf16", 1200, 1200),      # head_dim 64, whole sequence in one chunk
+    (32, 8, 128, 0, "bf16", 300, 64),         # nothing retained
+    (4, 4, 128, 512, "bf16", 260, 200),       # everything retained
+    (32, 8, 128, 64, "bf16", 330, 300),       # half a head retained (the paper's m = 64 preset)
+    (8, 8, 64, 256, "f32", 200, 150),         # fp32: the streaming path rotates in the kernel
+])
+def test_prefill_rope(H_q, H_kv, d, m, dtype, plen, pq):
+    w = synth.Workload(f"ppx_{H_q}_{H_kv}_{d}_{m}_{dtype}", dtype, H_q, H_kv, d, m, seed=700 + H_q + m,
+                       seq_lens=(5,), prefill_len=plen, prefill_q=pq)
+    inp = synth.generate(w)
+    dw = DeviceWorkload(inp)
+    rope = synth.rope_tables(d, plen + 2)
+    out, lse = dw.prefill_ex(rope)
+    torch.cuda.synchronize()
+    o_ref, l_ref = ref.prefill_paper_ref(inp, rope)
+    check(host(out), o_ref, dtype, f"{w.name} prefill rope")
+    assert np.abs(host(lse) - l_ref).max() <= (1e-5 if dtype == "f32" else 2e-2)
+    # without tables the _ex entry point is the plain prefill, bit for bit
+    got = host(out).copy()
+    o0, _ = dw.prefill(); torch.cuda.synchronize()
+    plain = host(o0).copy()
+    ek.prefill_attn_ex(dw.shape, dw.anchor_all, dw.target_all, dw.W_K, dw.W_V, inp.n_decode, dw.q_prefill,
+                       pq, inp.q_pos0, dw.out_prefill, dw.lse_prefill, dw.workspace)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(dw.out_prefill), plain)
+    assert np.abs(got - plain).max() > 1e-3          # and the rotation does change the result
+
+
+def test_prefill_rope_last_row_equals_decode_ex():
+    """The chunk's last query against the decode entry point with the same tables."""
+    w = synth.Workload("ppx_last", "bf16", 8, 4, 128, 256, seed=731, seq_lens=(5,), prefill_len=300, prefill_q=40)
+    inp = synth.generate(w)
+    rope = synth.rope_tables(128, 310)
+    dw = DeviceWorkload(inp, out_dtype="f32")
+    out, _ = dw.prefill_ex(rope); torch.cuda.synchronize()
+    b = inp.n_decode
+    single = synth.Inputs(w, [inp.seq_start[b]], [inp.seq_len[b]], [inp.seq_cap[b]], 1, inp.K_a, inp.V_a,
+                          inp.K_r, inp.V_r, inp.W_K, inp.W_V, inp.q_prefill[-1:].clone(), None, 0)
+    dd = DeviceWorkload(single, out_dtype="f32")
+    o_dec, _ = dd.decode_ex(rope, None); torch.cuda.synchronize()
+    np.testing.assert_allclose(host(out)[-1], host(o_dec)[0], rtol=2e-2, atol=6e-3)   # bf16 K_hat, rotated keys rounded
