@@ -163,7 +163,10 @@ def main():
         if has_prefill:            # the configuration's causal prefill chunk rides in the same step
             if timed:
                 ev[0].record()
-            dw.prefill()
+            if extras is None:
+                dw.prefill()
+            else:                  # the chunk with the rotary embedding (a chunk reads no window)
+                dw.prefill_ex(extras[0])
             if timed:
                 ev[1].record()
 
