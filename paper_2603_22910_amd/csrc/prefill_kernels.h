@@ -44,6 +44,17 @@ template <int HD> struct Cfg {
 };
 __device__ __forceinline__ int vswz(int r) { return (r ^ (r >> 3)) & 7; }
 
+// The softmax reference maximum of a query is raised only when the running maximum has moved
+// more than kSlack above it (in base-2 exponent units): the probabilities then stay below
+// 2^kSlack, harmless in fp32 / bf16, sums and outputs are exact either way, and the
+// accumulators are rescaled once in a while instead of on most tiles.
+constexpr float kSlack = 8.0f;
+// max of a value over the two lanes (l, l + 32) that share a query, on the vector ALU
+__device__ __forceinline__ float max_over_halves(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 template <int HD>
 __global__ __launch_bounds__(NTHREADS, 2) void prefill_attn_kernel(Args a) {
   using C = Cfg<HD>;
@@ -166,10 +177,18 @@ __global__ __launch_bounds__(NTHREADS, 2) void prefill_attn_kernel(Args a) {
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mb][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);          // finite from the first tile on (key 0 is visible)
-    const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
-    const float mneg = -m_new * scale2;
+    mx = max_over_halves(mx);
+    const float m_new = fmaxf(m_run, mx);      // finite from the first tile on (key 0 is visible)
+    if (__any((m_new - m_run) * scale2 > kSlack)) {      // see kSlack
+      const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
+      l_run *= corr;
+#pragma unroll
+      for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[cb][r] *= corr;
+      m_run = m_new;
+    }
+    const float mneg = -m_run * scale2;
     float lsum = 0.f;
     bf16x8_t pf[4];
 #pragma unroll
@@ -180,14 +199,7 @@ __global__ __launch_bounds__(NTHREADS, 2) void prefill_attn_kernel(Args a) {
         lsum += p;
         pf[mb * 2 + (r >> 3)][r & 7] = (__bf16)p;
       }
-    l_run = l_run * corr + lsum;
-    m_run = m_new;
-    if (__any(corr != 1.0f)) {            // the running maxima settle quickly: usually nothing to rescale
-#pragma unroll
-      for (int cb = 0; cb < C::CB; ++cb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[cb][r] *= corr;
-    }
+    l_run += lsum;
     // ---- O^T += V^T P^T : k-step ts covers keys 16 ts .. 16 ts + 15 in slot order
     //      (lane half lh, element e) <-> key 16 ts + 4 lh + (e < 4 ? e : e + 4)
 #pragma unroll
@@ -254,7 +266,6 @@ typedef short short4_t __attribute__((ext_vector_type(4)));
 
 // the first NCOPY waves issue the copies (a tile is 16 or 32 one-KB copies per operand)
 constexpr int NST = 4, NCOPY = 8, NWAVES = 12, NTHREADS = 64 * NWAVES, BQ = 32 * NWAVES;
-constexpr float kSlack = 8.0f;         // see the softmax step
 constexpr int kMinQueries = 1024;      // shorter chunks keep the four-wave kernel (more workgroups)
 
 template <int HD> struct Cfg {
@@ -303,12 +314,6 @@ __device__ __forceinline__ void dma_tile(char* smem, const CopyPlan<HD>& cp, int
     __builtin_amdgcn_raw_ptr_buffer_load_lds(cp.rv, (ECHOKV_LDS void*)(st + C::TILE + (C::NL * cp.wave_u + i) * 1024), 16,
                                              ro + cp.vcol[i], 0, 0, 0);
   }
-}
-
-// max of a value over the two lanes (l, l + 32) that share a query, on the vector ALU
-__device__ __forceinline__ float max_over_halves(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 typedef short short8_t __attribute__((ext_vector_type(8)));
@@ -455,13 +460,8 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mb][r]);
     mx = max_over_halves(mx);
-    // The reference maximum m_run is raised only when the running maximum has moved more than
-    // kSlack above it (in base-2 exponent units): the probabilities then stay below 2^kSlack,
-    // harmless in fp32 / bf16, sums and outputs are exact either way, and the accumulators are
-    // rescaled once in a while instead of on most tiles.  (Key 0 is visible to every query,
-    // so the maximum is finite from the first tile on.)
-    const float m_new = fmaxf(m_run, mx);
-    if (__any((m_new - m_run) * scale2 > kSlack)) {
+    const float m_new = fmaxf(m_run, mx);      // finite from the first tile on (key 0 is visible)
+    if (__any((m_new - m_run) * scale2 > kSlack)) {      // see kSlack
       const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
       l_run *= corr;
 #pragma unroll
