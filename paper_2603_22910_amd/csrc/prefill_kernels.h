@@ -322,38 +322,32 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 }
 // One k-step's V^T fragments: per 32-dim block, keys k0 .. k0+3 (lo) and k0+8 .. k0+11 (hi).
 struct VFrag { short4_t lo[4], hi[4]; };
-// LDS transpose reads written as instructions: the compiler orders the builtin form behind
-// every outstanding global -> LDS copy, which would drain the ring once per tile.
-template <int OFF>
-__device__ __forceinline__ short4_t tr_read(uint32_t addr) {
-  short4_t v;
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
-  return v;
-}
-// voff[cb]: this lane's byte offset inside a V tile for k-step 0, 32-dim block cb
+// The LDS transpose reads of a k-step and the wait for them, written as one block of
+// instructions: in builtin form the compiler orders the reads behind every outstanding
+// global -> LDS copy (s_waitcnt vmcnt(0)), which would drain the ring once per tile.  One block,
+// so that nothing can touch the destination registers between the reads and the wait.
+// voff[cb]: this lane's byte offset inside a V tile for k-step 0, 32-dim block cb.
+#define ECHOKV_TR(dst, adr, off) "ds_read_b64_tr_b16 " dst ", " adr " offset:" off "\n"
 template <int HD, int TS>
 __device__ __forceinline__ void read_v(VFrag& f, uint32_t sv, const uint32_t (&voff)[Cfg<HD>::CB]) {
-#pragma unroll
-  for (int cb = 0; cb < Cfg<HD>::CB; ++cb) {
-    f.lo[cb] = tr_read<16 * TS * Cfg<HD>::ROWB>(sv + voff[cb]);
-    f.hi[cb] = tr_read<(16 * TS + 8) * Cfg<HD>::ROWB>(sv + voff[cb]);
+  constexpr int LO = 16 * TS * Cfg<HD>::ROWB, HI = (16 * TS + 8) * Cfg<HD>::ROWB;
+  if constexpr (Cfg<HD>::CB == 4) {
+    asm volatile(ECHOKV_TR("%0", "%8", "%12") ECHOKV_TR("%4", "%8", "%13")
+                 ECHOKV_TR("%1", "%9", "%12") ECHOKV_TR("%5", "%9", "%13")
+                 ECHOKV_TR("%2", "%10", "%12") ECHOKV_TR("%6", "%10", "%13")
+                 ECHOKV_TR("%3", "%11", "%12") ECHOKV_TR("%7", "%11", "%13")
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(f.lo[0]), "=&v"(f.lo[1]), "=&v"(f.lo[2]), "=&v"(f.lo[3]),
+                   "=&v"(f.hi[0]), "=&v"(f.hi[1]), "=&v"(f.hi[2]), "=&v"(f.hi[3])
+                 : "v"(sv + voff[0]), "v"(sv + voff[1]), "v"(sv + voff[2]), "v"(sv + voff[3]), "n"(LO), "n"(HI));
+  } else {
+    asm volatile(ECHOKV_TR("%0", "%4", "%6") ECHOKV_TR("%2", "%4", "%7")
+                 ECHOKV_TR("%1", "%5", "%6") ECHOKV_TR("%3", "%5", "%7")
+                 "s_waitcnt lgkmcnt(0)"
+                 : "=&v"(f.lo[0]), "=&v"(f.lo[1]), "=&v"(f.hi[0]), "=&v"(f.hi[1])
+                 : "v"(sv + voff[0]), "v"(sv + voff[1]), "n"(LO), "n"(HI));
   }
 }
-// wait until at most N LDS reads issued after these are outstanding; the operands tie the
-// wait to the registers it guards
-template <int N, int CB>
-__device__ __forceinline__ void wait_v(VFrag& f) {
-  if constexpr (CB == 4)
-    asm volatile("s_waitcnt lgkmcnt(%8)"
-                 : "+v"(f.lo[0]), "+v"(f.lo[1]), "+v"(f.lo[2]), "+v"(f.lo[3]),
-                   "+v"(f.hi[0]), "+v"(f.hi[1]), "+v"(f.hi[2]), "+v"(f.hi[3])
-                 : "n"(N));
-  else
-    asm volatile("s_waitcnt lgkmcnt(%4)"
-                 : "+v"(f.lo[0]), "+v"(f.lo[1]), "+v"(f.hi[0]), "+v"(f.hi[1])
-                 : "n"(N));
-}
-
 
 template <int HD>
 __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
@@ -486,7 +480,6 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
     //      The transpose reads are issued by hand one k-step ahead of the MFMAs that use them.
     VFrag vb;
     auto pv = [&](int ts) {
-      wait_v<0, C::CB>(vb);
 #pragma unroll
       for (int cb = 0; cb < C::CB; ++cb) {
         const short8_t vv = __builtin_shufflevector(vb.lo[cb], vb.hi[cb], 0, 1, 2, 3, 4, 5, 6, 7);
