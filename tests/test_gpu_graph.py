@@ -1,4 +1,4 @@
-"""The decode entry points allocate nothing, synchronise nothing and clear nothing with
+"""The decode and prefill entry points allocate nothing, synchronise nothing and clear nothing with
 memsets, so a caller may capture them in a HIP graph.  Each replay is checked against an
 eager call on the same inputs, with eager work and synchronisations between the replays."""
 import numpy as np
@@ -40,6 +40,41 @@ def test_decode_in_a_captured_graph_matches_eager_on_every_replay(flags):
         torch.cuda.synchronize()
         assert torch.equal(got, dw.out), (flags, rep)
         assert torch.equal(got_lse, dw.lse), (flags, rep)
+        assert float(got.float().abs().sum()) > 0
+
+
+@pytest.mark.parametrize("pq,use_rope", [pytest.param(300, False, id="short"), pytest.param(1100, False, id="long"),
+                                         pytest.param(1100, True, id="long+rope")])
+def test_prefill_in_a_captured_graph_matches_eager_on_every_replay(pq, use_rope):
+    """Both prefill attention kernels (and the key rotation ahead of them).  The first call on
+    a device sets a function attribute of the long-chunk kernel: it runs before the capture."""
+    w = synth.Workload("graph_pf", "bf16", 8, 4, 128, 256, seed=62, seq_lens=(5,), prefill_len=pq + 211,
+                       prefill_q=pq)
+    inp = synth.generate(w)
+    dw = DeviceWorkload(inp)
+    rope = tuple(t.to(dw.dev) for t in synth.rope_tables(128, pq + 300)) if use_rope else None
+    run = (lambda st=None: dw.prefill_ex(rope, stream=st)) if use_rope else (lambda st=None: dw.prefill(stream=st))
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        run(side.cuda_stream)
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        run(torch.cuda.current_stream().cuda_stream)
+    gen = torch.Generator().manual_seed(4)
+    for rep in range(3):
+        q_new = torch.randn(dw.q_prefill.shape, generator=gen).to(dw.q_prefill.dtype)
+        dw.q_prefill.copy_(q_new.to(dw.dev))
+        torch.cuda.synchronize()
+        dw.out_prefill.zero_(); dw.lse_prefill.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        got, got_lse = dw.out_prefill.clone(), dw.lse_prefill.clone()
+        dw.out_prefill.zero_(); dw.lse_prefill.zero_()
+        run()
+        torch.cuda.synchronize()
+        assert torch.equal(got, dw.out_prefill), rep
+        assert torch.equal(got_lse, dw.lse_prefill), rep
         assert float(got.float().abs().sum()) > 0
 
 
