@@ -19,8 +19,8 @@ HIPCC_FLAGS = [
 ]
 
 # Kernels that count their own outstanding global loads (manual s_waitcnt vmcnt(N) around
-# global -> LDS copies).  Register spills go through the same counter, so a spill in one of
-# them would make those waits meaningless: the build refuses it.
+# global -> LDS copies).  Register spills and stack objects go through the same counter, so any
+# scratch memory in one of them would make those waits meaningless: the build refuses it.
 NO_SPILL_KERNELS = ("fused_decode_dma_kernel", "prefill_attn_dma_kernel", "absorbed13scores_kernel")
 
 
@@ -44,22 +44,22 @@ def build_library(verbose: bool = False, extra_flags=()) -> str:
         raise RuntimeError("hipcc failed building libechokv.so")
     spilled = check_spills(res.stdout + res.stderr)
     if spilled:
-        raise RuntimeError("register spills in kernels that count their own loads: "
+        raise RuntimeError("scratch memory (spills or stack objects) in kernels that count their own loads: "
                            + ", ".join(f"{k} ({n})" for k, n in spilled))
     os.replace(LIB_PATH + ".tmp", LIB_PATH)
     return LIB_PATH
 
 
 def check_spills(remarks: str):
-    """(kernel, spilled registers) for every NO_SPILL_KERNELS instance that spills, from the
-    compiler's resource-usage remarks."""
+    """(kernel, amount) for every NO_SPILL_KERNELS instance that spills registers or keeps objects
+    in scratch memory, from the compiler's resource-usage remarks."""
     bad, cur = [], None
     for line in remarks.splitlines():
         m = re.search(r"Function Name: (\S+)", line)
         if m:
             cur = m.group(1)
             continue
-        m = re.search(r"VGPRs Spill: (\d+)", line)
+        m = re.search(r"(?:VGPRs Spill|ScratchSize \[bytes/lane\]): (\d+)", line)
         if m and cur and int(m.group(1)) > 0 and any(k in cur for k in NO_SPILL_KERNELS):
             bad.append((cur, int(m.group(1))))
     return bad
