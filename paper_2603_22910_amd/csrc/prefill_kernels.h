@@ -290,11 +290,15 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
   asm volatile("" ::: "memory");
 }
 
-// What a lane needs to issue its share of a tile's global -> LDS copies.
+// What a lane needs to issue its share of a tile's global -> LDS copies: copy i of a copying
+// wave fills tile rows (NL wave + i) * ROWS_PER_COPY + lane / CH; LDS chunk slot lane % CH of
+// such a row receives global chunk slot ^ swizzle(row).  Copy i sits i * ROWS_PER_COPY rows
+// below copy 0: same V swizzle; the K swizzle of d = 128 (row & 15, copy 0 in rows 0..3 mod 16)
+// changes by 4 i mod 16 (d = 64 has one copy per wave and operand).
 template <int HD> struct CopyPlan {
   rsrc_t rk, rv;
-  int row[Cfg<HD>::NL];                 // tile row this lane copies a chunk of, per copy
-  uint32_t kcol[Cfg<HD>::NL], vcol[Cfg<HD>::NL];   // byte offset of the (swizzled) source chunk in the row
+  int row0;                             // tile row of copy 0
+  uint32_t kcol0, vcol0;                // byte offset of its (swizzled) source chunk in the row
   uint32_t ld2; int last, wave_u;
 };
 // Issue this wave's copies of key tile t into ring stage t % NST.  Rows past the last key
@@ -303,16 +307,17 @@ template <int HD> struct CopyPlan {
 template <int HD>
 __device__ __forceinline__ void dma_tile(char* smem, const CopyPlan<HD>& cp, int t) {
   using C = Cfg<HD>;
+  static_assert(C::NL == 1 || (C::CH == 16 && C::ROWS_PER_COPY == 4), "swizzle relation between a wave's copies");
   if (cp.wave_u >= NCOPY) return;
   char* st = smem + (t & (NST - 1)) * C::STAGE;
   const int kv0 = t * BKV;
 #pragma unroll
   for (int i = 0; i < C::NL; ++i) {
-    const uint32_t ro = __umul24((uint32_t)min(kv0 + cp.row[i], cp.last), cp.ld2);
+    const uint32_t ro = __umul24((uint32_t)min(kv0 + cp.row0 + i * C::ROWS_PER_COPY, cp.last), cp.ld2);
     __builtin_amdgcn_raw_ptr_buffer_load_lds(cp.rk, (ECHOKV_LDS void*)(st + (C::NL * cp.wave_u + i) * 1024), 16,
-                                             ro + cp.kcol[i], 0, 0, 0);
+                                             ro + (cp.kcol0 ^ (uint32_t)(((i * 4) & 15) << 4)), 0, 0, 0);
     __builtin_amdgcn_raw_ptr_buffer_load_lds(cp.rv, (ECHOKV_LDS void*)(st + C::TILE + (C::NL * cp.wave_u + i) * 1024), 16,
-                                             ro + cp.vcol[i], 0, 0, 0);
+                                             ro + cp.vcol0, 0, 0, 0);
   }
 }
 
@@ -322,31 +327,40 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 }
 // One k-step's V^T fragments: per 32-dim block, keys k0 .. k0+3 (lo) and k0+8 .. k0+11 (hi).
 struct VFrag { short4_t lo[4], hi[4]; };
-// The LDS transpose reads of a k-step and the wait for them, written as one block of
-// instructions: in builtin form the compiler orders the reads behind every outstanding
-// global -> LDS copy (s_waitcnt vmcnt(0)), which would drain the ring once per tile.  One block,
-// so that nothing can touch the destination registers between the reads and the wait.
-// voff[cb]: this lane's byte offset inside a V tile for k-step 0, 32-dim block cb.
+// The LDS transpose reads are written as instructions: in builtin form the compiler orders
+// them behind every outstanding global -> LDS copy (s_waitcnt vmcnt(0)), which would drain the
+// ring once per tile.  issue_v requests the fragments of k-step TS; wait_v<N> waits until at
+// most N reads requested after them are outstanding, its operands tie it to the registers it
+// guards.  voff0: this lane's byte offset inside a V tile for k-step 0 and 32-dim block 0; block
+// cb is at voff0 ^ (cb << 6) (the swizzle only touches the two chunk-index bits that cb occupies).
 #define ECHOKV_TR(dst, adr, off) "ds_read_b64_tr_b16 " dst ", " adr " offset:" off "\n"
 template <int HD, int TS>
-__device__ __forceinline__ void read_v(VFrag& f, uint32_t sv, const uint32_t (&voff)[Cfg<HD>::CB]) {
+__device__ __forceinline__ void issue_v(VFrag& f, uint32_t sv, uint32_t voff0) {
   constexpr int LO = 16 * TS * Cfg<HD>::ROWB, HI = (16 * TS + 8) * Cfg<HD>::ROWB;
   if constexpr (Cfg<HD>::CB == 4) {
     asm volatile(ECHOKV_TR("%0", "%8", "%12") ECHOKV_TR("%4", "%8", "%13")
                  ECHOKV_TR("%1", "%9", "%12") ECHOKV_TR("%5", "%9", "%13")
                  ECHOKV_TR("%2", "%10", "%12") ECHOKV_TR("%6", "%10", "%13")
                  ECHOKV_TR("%3", "%11", "%12") ECHOKV_TR("%7", "%11", "%13")
-                 "s_waitcnt lgkmcnt(0)"
                  : "=&v"(f.lo[0]), "=&v"(f.lo[1]), "=&v"(f.lo[2]), "=&v"(f.lo[3]),
                    "=&v"(f.hi[0]), "=&v"(f.hi[1]), "=&v"(f.hi[2]), "=&v"(f.hi[3])
-                 : "v"(sv + voff[0]), "v"(sv + voff[1]), "v"(sv + voff[2]), "v"(sv + voff[3]), "n"(LO), "n"(HI));
+                 : "v"(sv + voff0), "v"(sv + (voff0 ^ 64u)), "v"(sv + (voff0 ^ 128u)), "v"(sv + (voff0 ^ 192u)), "n"(LO), "n"(HI));
   } else {
     asm volatile(ECHOKV_TR("%0", "%4", "%6") ECHOKV_TR("%2", "%4", "%7")
                  ECHOKV_TR("%1", "%5", "%6") ECHOKV_TR("%3", "%5", "%7")
-                 "s_waitcnt lgkmcnt(0)"
                  : "=&v"(f.lo[0]), "=&v"(f.lo[1]), "=&v"(f.hi[0]), "=&v"(f.hi[1])
-                 : "v"(sv + voff[0]), "v"(sv + voff[1]), "n"(LO), "n"(HI));
+                 : "v"(sv + voff0), "v"(sv + (voff0 ^ 64u)), "n"(LO), "n"(HI));
   }
+}
+template <int N, int CB>
+__device__ __forceinline__ void wait_v(VFrag& f) {
+  if constexpr (CB == 4)
+    asm volatile("s_waitcnt lgkmcnt(%8)"
+                 : "+v"(f.lo[0]), "+v"(f.lo[1]), "+v"(f.lo[2]), "+v"(f.lo[3]),
+                   "+v"(f.hi[0]), "+v"(f.hi[1]), "+v"(f.hi[2]), "+v"(f.hi[3])
+                 : "n"(N));
+  else
+    asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f.lo[0]), "+v"(f.lo[1]), "+v"(f.hi[0]), "+v"(f.hi[1]) : "n"(N));
 }
 
 template <int HD>
@@ -365,20 +379,15 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
   if (kvh < a.n_ret_heads) { kbase = a.k_ret + kvh * HD; vbase = a.v_ret + kvh * HD; ld2 = (uint32_t)a.m * 2; }
   else { const int c = (kvh - a.n_ret_heads) * HD; kbase = a.k_hat + c; vbase = a.v_hat + c; ld2 = (uint32_t)a.d_out * 2; }
 
-  // ---- copy plan: copy i of this wave fills tile rows (NL wave + i) * ROWS_PER_COPY + lane / CH;
-  //      LDS chunk slot lane % CH of that row receives global chunk slot ^ swizzle(row)
   CopyPlan<HD> cp;
-#pragma unroll
-  for (int i = 0; i < C::NL; ++i) {
-    cp.row[i] = (C::NL * wave + i) * C::ROWS_PER_COPY + lane / C::CH;
-    cp.kcol[i] = (uint32_t)(((lane % C::CH) ^ C::kswz(cp.row[i])) * 16);
-    cp.vcol[i] = (uint32_t)(((lane % C::CH) ^ C::vswz(cp.row[i])) * 16);
-  }
+  cp.row0 = C::NL * wave_u * C::ROWS_PER_COPY + lane / C::CH;
+  cp.kcol0 = (uint32_t)(((lane % C::CH) ^ C::kswz(cp.row0)) * 16);
+  cp.vcol0 = (uint32_t)(((lane % C::CH) ^ C::vswz(cp.row0)) * 16);
   cp.rk = fused::make_rsrc(kbase); cp.rv = fused::make_rsrc(vbase);
   cp.ld2 = ld2; cp.last = Ltot - 1; cp.wave_u = wave_u;
 
   // ---- this lane's query (clamped; clamped duplicates are not written back)
-  const int qi = i0 + wave * 32 + lr;
+  const int qi = i0 + wave_u * 32 + lr;
   const int qic = min(qi, a.T_q - 1);
   const int qpos = a.q_pos0 + qic;
   bf16x8_t qf[C::KSTEPS];
@@ -410,17 +419,21 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
   const int vkey = 4 * lh + (s16 >> 2);                        // + 16 ts (+ 8 for the second half)
   const int vch = 2 * blk2 + ((s16 & 3) >> 1);                 // + 4 cb, before the swizzle
   const uint32_t vbyte = (uint32_t)((s16 & 1) * 8);
-  uint32_t voff[C::CB];
+  const uint32_t voff = (uint32_t)(vkey * C::ROWB + ((vch ^ C::vswz(vkey)) << 4)) + vbyte;   // see issue_v
+  uint32_t koff[2];                      // K fragment of k-step 0: row mb*32 + lr, chunk lh ^ swizzle(row)
 #pragma unroll
-  for (int cb = 0; cb < C::CB; ++cb)      // the swizzle of key vkey + 16 ts (+ 8) does not depend on ts
-    voff[cb] = (uint32_t)(vkey * C::ROWB + (((4 * cb + vch) ^ C::vswz(vkey)) << 4)) + vbyte;
+  for (int mb = 0; mb < 2; ++mb) koff[mb] = (uint32_t)((mb * 32 + lr) * C::ROWB + ((lh ^ C::kswz(mb * 32 + lr)) << 4));
 
+  // Two loops (tiles that reach a query of this wave, then tiles wholly past them where the
+  // wave only keeps copying and meeting the others) instead of a skip inside one: no values
+  // to merge between the paths.
+  const int nact = min(ntiles, qpos_max / BKV + 1);
   dma_tile<HD>(smem, cp, 0); dma_tile<HD>(smem, cp, 1); dma_tile<HD>(smem, cp, 2);
-  for (int t = 0; t < ntiles; ++t) {
+  int t = 0;
+  for (; t < nact; ++t) {
     wait_loads_and_barrier<2 * 2 * C::NL>();     // tile t has landed for every wave; stage (t-1)%NST is free
     dma_tile<HD>(smem, cp, t + 3);
     const int kv0 = t * BKV;
-    if (kv0 > qpos_max) continue;      // wholly past this wave's queries (wave-uniform)
     const char* sk = smem + (t & (NST - 1)) * C::STAGE;
     const char* sv = sk + C::TILE;
     // ---- S^T = K Q^T
@@ -430,22 +443,25 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[mb][r] = 0.f;
+    // chunk (2 kk + lh) ^ swizzle of the lane's row is the chunk of k-step 0 with kk << 1 XOR-ed
+    // in: one address register per key block serves all k-steps
 #pragma unroll
     for (int kk = 0; kk < C::KSTEPS; ++kk)
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb) {
-        const int row = mb * 32 + lr, c = kk * 2 + lh;
-        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sk + row * C::ROWB + ((c ^ C::kswz(row)) << 4));
+        const bf16x8_t kf = *reinterpret_cast<const bf16x8_t*>(sk + (koff[mb] ^ (uint32_t)(kk << 5)));
         sacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[mb], 0, 0, 0);
       }
     // ---- online softmax, lane-local (keys: mb*32 + 8*(r/4) + 4*lh + r%4), base 2, scale folded in
-    if (kv0 + BKV - 1 > qpos_min) {
+    if (kv0 + BKV - 1 > qpos_min) {   // rare (diagonal tiles): the lane's query position is worked out afresh
+      const int ln = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+      const int qp = a.q_pos0 + min(i0 + wave_u * 32 + (ln & 31), a.T_q - 1);
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int key = kv0 + mb * 32 + (r >> 2) * 8 + lh * 4 + (r & 3);
-          if (key > qpos) sacc[mb][r] = -INFINITY;
+          const int key = kv0 + mb * 32 + (r >> 2) * 8 + (ln >> 5) * 4 + (r & 3);
+          if (key > qp) sacc[mb][r] = -INFINITY;
         }
     }
     float mx = -INFINITY;
@@ -478,31 +494,44 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
     l_run += lsum;
     // ---- O^T += V^T P^T : k-step ts, element e of lane half lh <-> key 16 ts + 4 lh + (e < 4 ? e : e + 4).
     //      The transpose reads are issued by hand one k-step ahead of the MFMAs that use them.
-    VFrag vb;
-    auto pv = [&](int ts) {
+    constexpr int V = 2 * C::CB;         // reads per k-step
+    VFrag va, vb;
+    auto pv = [&](int ts, const VFrag& v) {
 #pragma unroll
       for (int cb = 0; cb < C::CB; ++cb) {
-        const short8_t vv = __builtin_shufflevector(vb.lo[cb], vb.hi[cb], 0, 1, 2, 3, 4, 5, 6, 7);
+        const short8_t vv = __builtin_shufflevector(v.lo[cb], v.hi[cb], 0, 1, 2, 3, 4, 5, 6, 7);
         oacc[cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vv), pf[ts], oacc[cb], 0, 0, 0);
       }
     };
-    // (one k-step of fragments at a time: the other waves of the SIMD cover the LDS latency)
-    read_v<HD, 0>(vb, svu, voff); pv(0);
-    read_v<HD, 1>(vb, svu, voff); pv(1);
-    read_v<HD, 2>(vb, svu, voff); pv(2);
-    read_v<HD, 3>(vb, svu, voff); pv(3);
+    // two buffers: the fragments of a k-step are requested before the MFMAs of the one before it
+    issue_v<HD, 0>(va, svu, voff);
+    issue_v<HD, 1>(vb, svu, voff);
+    wait_v<V, C::CB>(va); pv(0, va);
+    issue_v<HD, 2>(va, svu, voff);
+    wait_v<V, C::CB>(vb); pv(1, vb);
+    issue_v<HD, 3>(vb, svu, voff);
+    wait_v<V, C::CB>(va); pv(2, va);
+    wait_v<0, C::CB>(vb); pv(3, vb);
+  }
+  for (; t < ntiles; ++t) {
+    wait_loads_and_barrier<2 * 2 * C::NL>();
+    dma_tile<HD>(smem, cp, t + 3);
   }
   wait_loads_and_barrier<0>();         // the ring's last copies have landed before the workgroup ends
   // ---- finish: this lane holds query qi, head dims cb*32 + 8*(r/4) + 4*lh + r%4
+  //      (The lane index is read afresh so that nothing of the set-up stays in registers over the loop.)
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  if (qi >= a.T_q) return;
+  const int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  const int lh_e = lane_e >> 5;
+  const int qi_e = i0 + wave_u * 32 + (lane_e & 31);
+  if (qi_e >= a.T_q) return;
   const float inv = 1.0f / l_tot;
-  const int64_t ob = ((int64_t)qi * a.H_q + h) * HD;
+  const int64_t ob = ((int64_t)qi_e * a.H_q + h) * HD;
 #pragma unroll
   for (int cb = 0; cb < C::CB; ++cb)
 #pragma unroll
     for (int r4 = 0; r4 < 4; ++r4) {
-      const int c = cb * 32 + r4 * 8 + lh * 4;
+      const int c = cb * 32 + r4 * 8 + lh_e * 4;
       const float x0 = oacc[cb][r4 * 4] * inv, x1 = oacc[cb][r4 * 4 + 1] * inv;
       const float x2 = oacc[cb][r4 * 4 + 2] * inv, x3 = oacc[cb][r4 * 4 + 3] * inv;
       if (a.out_bf16) {
@@ -514,8 +543,8 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
         *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.out) + ob + c) = make_float4(x0, x1, x2, x3);
       }
     }
-  if (a.lse && lh == 0)
-    a.lse[(int64_t)qi * a.H_q + h] = (m_run * scale2 + __log2f(l_tot)) * 0.69314718055994530942f;
+  if (a.lse && lh_e == 0)
+    a.lse[(int64_t)qi_e * a.H_q + h] = (m_run * scale2 + __log2f(l_tot)) * 0.69314718055994530942f;
 }
 
 template <int HD>
