@@ -230,6 +230,26 @@ def test_cache_append_then_decode_matches_bulk_layout():
     assert e.value.code == ek.ERR_CAPACITY
 
 
+@pytest.mark.parametrize("flags", MODES)
+def test_decode_growing_scores(flags):
+    """Key rows whose norm grows fourfold along the sequence: the score maxima of successive
+    tiles and splits differ by many powers of two, so every rescale and the split merge are
+    exercised with large exponents."""
+    w = synth.Workload("dec_grow", "bf16", 8, 4, 128, 256, seed=39, seq_lens=(1500, 700))
+    inp = synth.generate(w)
+    for b in range(inp.n_decode):
+        r = inp.rows(b)
+        L = inp.seq_len[b]
+        ramp = (1.0 + 3.0 * torch.arange(L, dtype=torch.float32) / L)[:, None]
+        inp.K_a[r] = (inp.K_a[r].float() * ramp).to(inp.K_a.dtype)
+        inp.K_r[r] = (inp.K_r[r].float() * ramp).to(inp.K_r.dtype)
+    dw = make_dw(inp, flags)
+    out, lse = dw.decode(); torch.cuda.synchronize()
+    o_ref, l_ref = ref.decode_ref(inp)
+    check(host(out), o_ref, w.dtype, f"decode, growing scores, flags={flags}")
+    assert np.abs(host(lse) - l_ref).max() <= 5e-2      # scores reach +-30: bf16 inputs, fp32 sums
+
+
 # ---- prefill -------------------------------------------------------------------
 def run_prefill_case(w, flags=0):
     inp = synth.generate(w)
