@@ -15,7 +15,9 @@
  *    pointers are ordinary host memory read (or, for seq_len in
  *    echokv_cache_append, written) during the call only.
  *  - The library allocates no device memory and frees none.  Cache, weights,
- *    queries, outputs and workspace are owned by the caller.
+ *    queries, outputs and workspace are owned by the caller (the one fixed
+ *    buffer inside the library's device image belongs to
+ *    echokv_decode_attn_static, see there).
  *  - All argument checks run before the first HIP call and leave every buffer
  *    and every host array untouched on failure.
  *  - Work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream);
@@ -43,7 +45,9 @@ typedef enum {
   ECHOKV_ERR_CAPACITY = 4,    /* append past a sequence's reserved rows */
   ECHOKV_ERR_WORKSPACE = 5,   /* workspace missing or too small */
   ECHOKV_ERR_UNSUPPORTED = 6, /* legal in the method, not built (e.g. m % 64 != 0) */
-  ECHOKV_ERR_HIP = 7          /* a HIP runtime call or launch failed */
+  ECHOKV_ERR_HIP = 7,         /* a HIP runtime call or launch failed */
+  ECHOKV_ERR_STATIC_LIMIT = 8 /* echokv_decode_attn_static: the request needs more than
+                                 ECHOKV_STATIC_SCRATCH_BYTES of scratch */
 } echokv_status;
 
 typedef enum { ECHOKV_BF16 = 0, ECHOKV_F32 = 1 } echokv_dtype;
@@ -166,6 +170,29 @@ int echokv_decode_attn(const echokv_shape *shape, const echokv_layer_cache *anch
                        const echokv_layer_cache *target, const void *w_k,
                        const void *w_v, const void *q, void *out, float *lse_out,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* echokv_decode_attn for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels, same result as
+ * echokv_decode_attn (shape->flags honoured alike), but the split partials (and
+ * whatever else the chosen path keeps in its workspace) live in a fixed buffer
+ * of ECHOKV_STATIC_SCRATCH_BYTES inside the library's device image instead of a
+ * caller-owned workspace.  The call allocates and frees nothing.
+ *  - Limit: a request whose echokv_workspace_bytes-style need exceeds
+ *    ECHOKV_STATIC_SCRATCH_BYTES returns ECHOKV_ERR_STATIC_LIMIT and touches
+ *    nothing.  On the fused path the need is about (tokens / 128 + 2 * batch) *
+ *    H_q * (d + 2) * 4 bytes: 32 MiB covers ~250 K cached tokens at H_q = 32,
+ *    d = 128.
+ *  - Every GPU the library runs on holds one such buffer until the process
+ *    ends; all calls on a GPU share it.  It keeps the previous call's contents;
+ *    nothing in it needs to start at zero (every partial that is read has been
+ *    written by the same call).  Two calls that overlap in time on one GPU
+ *    (different streams, different threads) race on it: order them. */
+#define ECHOKV_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int echokv_decode_attn_static(const echokv_shape *shape, const echokv_layer_cache *anchor,
+                              const echokv_layer_cache *target, const void *w_k,
+                              const void *w_v, const void *q, void *out, float *lse_out,
+                              void *hip_stream);
 
 /* What the paper's own inference adds around Eq. 7 (both optional, independent):
  *

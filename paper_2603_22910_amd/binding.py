@@ -15,7 +15,8 @@ import numpy as np
 _LIB = None
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libechokv.so")
 
-OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_CAPACITY, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP = range(8)
+OK, ERR_NULL, ERR_SHAPE, ERR_DTYPE, ERR_CAPACITY, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_HIP, ERR_STATIC_LIMIT = range(9)
+STATIC_SCRATCH_BYTES = 32 << 20
 BF16, F32 = 0, 1
 FLAG_UNFUSED = 1
 FLAG_W_PACKED = 2
@@ -28,7 +29,8 @@ EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_profile_enable", "echokv_profile_read", "echokv_pack_weights",
            "echokv_cache_compress", "echokv_decode_attn_ex", "echokv_window_append",
            "echokv_mlp_workspace_bytes", "echokv_decode_attn_mlp", "echokv_profile_stream_read",
-           "echokv_fit_workspace_bytes", "echokv_fit_linear", "echokv_prefill_attn_ex")
+           "echokv_fit_workspace_bytes", "echokv_fit_linear", "echokv_prefill_attn_ex",
+           "echokv_decode_attn_static")
 ACT_RELU, ACT_SILU = 1, 2
 
 
@@ -86,6 +88,10 @@ def load() -> C.CDLL:
     lib.echokv_decode_attn.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
                                        C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.echokv_decode_attn_static.restype = C.c_int
+    lib.echokv_decode_attn_static.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
+                                              C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.echokv_decode_attn_ex.restype = C.c_int
     lib.echokv_decode_attn_ex.argtypes = [C.POINTER(Shape), C.POINTER(LayerCacheC),
                                           C.POINTER(LayerCacheC), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -243,6 +249,15 @@ def decode_attn(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, 
     _check(load().echokv_decode_attn(C.byref(shape), C.byref(a), C.byref(t), _ptr(w_k), _ptr(w_v),
                                      _ptr(q), _ptr(out), _ptr(lse_out), _ptr(workspace), nbytes,
                                      _stream(stream)), "echokv_decode_attn")
+
+
+def decode_attn_static(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, q, out,
+                       lse_out, stream=None):
+    """echokv_decode_attn on the library's fixed scratch: no workspace, nothing allocated."""
+    a, t = anchor.as_c(), target.as_c()
+    _check(load().echokv_decode_attn_static(C.byref(shape), C.byref(a), C.byref(t), _ptr(w_k),
+                                            _ptr(w_v), _ptr(q), _ptr(out), _ptr(lse_out),
+                                            _stream(stream)), "echokv_decode_attn_static")
 
 
 def decode_attn_ex(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, q, out,

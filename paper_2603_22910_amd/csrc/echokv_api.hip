@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -103,6 +104,30 @@ WsPlan plan_ws(const Dims& dm, int64_t part_slots, int64_t recon_rows) {
 }
 
 constexpr int kPrefillQChunk = kMaxSeqPerLaunch;   // queries per launch, streaming prefill
+
+// Fixed scratch of echokv_decode_attn_static: takes the place of the caller's workspace for callers
+// that cannot allocate.  Every GPU the library runs on holds its own copy until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; kernels and the planning
+// code get the per-device address kept in g_scratch_ptr.
+constexpr size_t kStaticScratchBytes = ECHOKV_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+// Device address of this device's copy of `scratch` (looked up once per device).
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ECHOKV_ERR_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ECHOKV_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return ECHOKV_OK;
+}
 
 // Optional event pairs around the dominant decode kernel (echokv_profile_*).
 struct Profiler {
@@ -791,6 +816,7 @@ const char* echokv_status_string(int status) {
     case ECHOKV_ERR_WORKSPACE: return "workspace missing or too small";
     case ECHOKV_ERR_UNSUPPORTED: return "configuration not supported by this build";
     case ECHOKV_ERR_HIP: return "HIP runtime error";
+    case ECHOKV_ERR_STATIC_LIMIT: return "request needs more than the fixed scratch of echokv_decode_attn_static";
     default: return "unknown status";
   }
 }
@@ -1038,6 +1064,22 @@ int echokv_decode_attn(const echokv_shape* shape, const echokv_layer_cache* anch
                        size_t workspace_bytes, void* hip_stream) {
   return echokv_decode_attn_ex(shape, anchor, target, w_k, w_v, q, nullptr, out, lse_out, workspace,
                                workspace_bytes, hip_stream);
+}
+
+int echokv_decode_attn_static(const echokv_shape* shape, const echokv_layer_cache* anchor,
+                              const echokv_layer_cache* target, const void* w_k, const void* w_v,
+                              const void* q, void* out, float* lse_out, void* hip_stream) {
+  // argument checks first (a NULL workspace of zero bytes makes the shared path stop right after
+  // them, before any HIP call): only a request that is valid but lacks a workspace goes on
+  int rc = echokv_decode_attn_ex(shape, anchor, target, w_k, w_v, q, nullptr, out, lse_out, nullptr, 0,
+                                 hip_stream);
+  if (rc != ECHOKV_ERR_WORKSPACE) return rc;
+  void* ptr = nullptr;
+  rc = static_scratch(&ptr);
+  if (rc) return rc;
+  rc = echokv_decode_attn_ex(shape, anchor, target, w_k, w_v, q, nullptr, out, lse_out, ptr,
+                             kStaticScratchBytes, hip_stream);
+  return rc == ECHOKV_ERR_WORKSPACE ? ECHOKV_ERR_STATIC_LIMIT : rc;
 }
 
 int echokv_window_append(const echokv_shape* shape, void* win_k, void* win_v, int32_t n_sink,
