@@ -1,15 +1,22 @@
 #!/usr/bin/env python3
 """Benchmark of the EchoKV decode hot path on one MI355X.
 
-One step = one decode step of one target layer over the whole batch: append
-the step's new token to the anchor and target caches (echokv_cache_append x2),
-then echokv_decode_attn (retained-head streaming kernel, fused
-reconstruct+attend kernel, split-K merge).  Inputs are synthetic, seeded, and
-resident in HBM before the timed region.  Prints ONE JSON line.
+One step = one pass of the whole hot path of one target layer over one batch:
+append the step's new token to the anchor and target caches
+(echokv_cache_append x2), then echokv_decode_attn over every decode sequence
+(retained-head streaming kernel, fused reconstruct+attend kernel, split-K
+merge) and, where the configuration has one, the causal prefill chunk
+(echokv_prefill_attn).  Inputs are synthetic, seeded, and resident in HBM
+before the timed region.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N] [--unfused]
+The default workload is configuration 4, the largest one that fits one GPU:
+32 ragged decode sequences (log-uniform 1 K .. 64 K tokens) plus one
+8192-query causal prefill chunk in the same step.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N] [--unfused] ...
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -24,27 +31,45 @@ PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
 
+def kernel_source_sha():
+    """Identifies the kernel sources a counter summary under profiles/ was taken with."""
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2603_22910_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".h", ".hip")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def read_traffic(workload_name):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3
-    counter summary (profiles/traffic_<workload>.txt, `key = value` lines), or None."""
+    """L2-miss bytes (HBM or Infinity Cache) per launch of the dominant kernel from the committed
+    rocprofv3 counter summary (profiles/traffic_<workload>.txt, `key = value` lines).
+    Returns (bytes or None, note).  A summary taken with other kernel sources than the ones in
+    the tree is reported as stale: its figure is kept out of `traffic`."""
     path = os.path.join(ROOT, "profiles", f"traffic_{workload_name}.txt")
     if not os.path.exists(path):
-        return None
+        return None, "no counter summary committed for this workload"
     vals = {}
     for line in open(path):
         if "=" in line and not line.lstrip().startswith("#"):
             k, v = line.split("=", 1)
             vals[k.strip()] = v.strip()
     try:
-        return float(vals["hbm_bytes_per_launch"])
+        traffic = float(vals["hbm_bytes_per_launch"])
     except (KeyError, ValueError):
-        return None
+        return None, "counter summary has no hbm_bytes_per_launch"
+    sha = vals.get("kernel_source_sha")
+    if sha != kernel_source_sha():
+        return None, (f"stale: summary taken with kernel sources {sha}, tree has {kernel_source_sha()} "
+                      f"(stored figure {traffic:.4g} B)")
+    return traffic, f"profiles/{os.path.basename(path)} at commit {vals.get('commit', '?')}"
 
 
 def cpu_baseline(inp, min_s=12.0):
     """The fp64 oracle, as it stands, timed on this host over a bounded sample
-    (whole sequences of the same workload) -> context tokens/s."""
-    import numpy as np
+    (whole decode sequences of the same workload, shortest first so that the
+    sample holds several) -> context tokens/s."""
     from oracle import echokv_oracle as orc
     try:
         from threadpoolctl import threadpool_info
@@ -54,9 +79,10 @@ def cpu_baseline(inp, min_s=12.0):
     w = inp.w
     f64 = lambda t: t.double().numpy()
     W_K, W_V = f64(inp.W_K), f64(inp.W_V)
+    order = sorted(range(inp.n_decode), key=lambda b: inp.seq_len[b])
     tokens, seqs, t0 = 0, 0, time.perf_counter()
     while time.perf_counter() - t0 < min_s:       # whole sequences, wrapping round the batch
-        b = seqs % inp.n_decode
+        b = order[seqs % inp.n_decode]
         r = inp.rows(b)
         orc.echokv_decode(f64(inp.q[b]), f64(inp.K_a[r]), f64(inp.V_a[r]), f64(inp.K_r[r]),
                           f64(inp.V_r[r]), W_K, W_V, w.n_kv_heads)
@@ -64,16 +90,19 @@ def cpu_baseline(inp, min_s=12.0):
     dt = time.perf_counter() - t0
     return {"value": tokens / dt, "unit": "context tokens/s/layer", "cores": int(threads),
             "kind": "oracle",
-            "sample": f"{seqs} sequence passes ({tokens} context tokens) of {w.name}, "
-                      f"fp64 NumPy oracle, {dt:.1f} s"}
+            "sample": f"{seqs} whole decode sequences, shortest first ({tokens} context tokens) of "
+                      f"{w.name}, fp64 NumPy oracle, {dt:.1f} s"}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--config", type=int, default=1, help="benchmark configuration index (0-4)")
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration index (0-4)")
+    ap.add_argument("--ramp-seconds", type=float, default=3.0,
+                    help="untimed steps for this much wall time before the warm-up, so that the "
+                         "timed steps run at the clocks the chip settles at under this load")
     ap.add_argument("--unfused", action="store_true", help="time the unfused comparison path")
     ap.add_argument("--packed-weights", action="store_true",
                     help="lay W_K/W_V out once with echokv_pack_weights before the timed region")
@@ -106,8 +135,10 @@ def main():
     from paper_2603_22910_amd import synth
     from paper_2603_22910_amd.harness import DeviceWorkload
 
+    t_gen = time.perf_counter()
     w = synth.CONFIGS[args.config]
     inp = synth.generate(w)
+    t_gen = time.perf_counter() - t_gen
     flags = (ek.FLAG_UNFUSED if args.unfused else ek.FLAG_ABSORBED if args.absorbed
              else ek.FLAG_ABSORB_V if args.absorb_v else 0)
     # the default run also times the weight-absorbed mode afterwards (reported beside the
@@ -121,7 +152,7 @@ def main():
         dw.pack_weights()
     dev = dw.dev
     B = inp.n_decode
-    tokens = inp.total_decode_tokens
+    dec_tokens = inp.total_decode_tokens
 
     # the step's new token: the last cached row of every sequence, re-appended
     # each step (lengths are wound back by one on the host, so every step sees
@@ -147,9 +178,8 @@ def main():
         mlp = tuple(t.to(dev) for t in synth.mlp_weights(w, args.mlp_hidden))
 
     has_prefill = inp.q_prefill is not None
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
 
-    def step(timed=False):
+    def step():
         dw.anchor.seq_len[:] = full_len - 1
         ek.cache_append(dw.shape, dw.anchor, ka_new, va_new, ones)
         dw.target.seq_len[:] = full_len - 1
@@ -161,32 +191,42 @@ def main():
         else:
             dw.decode_ex(*extras)
         if has_prefill:            # the configuration's causal prefill chunk rides in the same step
-            if timed:
-                ev[0].record()
             if extras is None:
                 dw.prefill()
             else:                  # the chunk with the rotary embedding (a chunk reads no window)
                 dw.prefill_ex(extras[0])
-            if timed:
-                ev[1].record()
+
+    def clock_ramp():
+        # untimed: run the step until the wall time is up (a fresh chip runs its first tens of
+        # milliseconds of a heavy load at clocks it does not keep)
+        t0, n = time.perf_counter(), 0
+        while time.perf_counter() - t0 < args.ramp_seconds:
+            step(); n += 1
+            torch.cuda.synchronize()
+        return time.perf_counter() - t0, n
 
     def timed_run():
+        """Times exactly args.steps steps after args.warmup untimed ones.  Returns the wall time and,
+        per profiler channel, (summed kernel ms by HIP events on the launch stream, launches)."""
         for _ in range(args.warmup):
             step()
         torch.cuda.synchronize()
         ek.profile_enable(True)
-        ek.profile_read()
+        for ch in range(3):
+            ek.profile_read(ch)
         t0 = time.perf_counter()
-        for i in range(args.steps):
-            step(timed=(i == args.steps - 1))
+        for _ in range(args.steps):
+            step()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        kern_ms, launches = ek.profile_read()
+        prof = [ek.profile_read(ch) for ch in range(3)]
         ek.profile_enable(False)
-        return dt, kern_ms, launches
+        return dt, prof
 
-    dt, kern_ms, launches = timed_run()
-    prefill_ms = ev[0].elapsed_time(ev[1]) if has_prefill else None
+    ramp_s, ramp_steps = clock_ramp() if args.ramp_seconds > 0 else (0.0, 0)
+    dt, prof = timed_run()
+    kern_ms, launches = prof[0]
+    tokens = dec_tokens
     if has_prefill:
         tokens += inp.seq_len[inp.n_decode]      # the chunk's context counts as processed tokens
 
@@ -203,7 +243,6 @@ def main():
 
     # roofline of the dominant kernel (the fused predictor product + attention):
     # algorithmic work = 4 * d_in * d_out flop per cached token (K and V products)
-    dec_tokens = inp.total_decode_tokens
     flops = 4.0 * w.d_in * w.d_out * dec_tokens
     if args.mlp_hidden:      # two layers, for keys and for values
         flops = 4.0 * args.mlp_hidden * (w.d_in + w.d_out) * dec_tokens
@@ -224,9 +263,10 @@ def main():
         # the absorbed path's kernels together read every cache row and both weight matrices once
         k_s = kern_ms / launches * 1e-3
         ach = bytes_alg / k_s / 1e9
-        return {"bound": "hbm", "kernel": "absorbed decode (scores_kernel + pv_kernel and 5 small ones)",
+        traffic, note = read_traffic(w.name + "_absorbed")
+        return {"bound": "hbm", "kernel": "absorbed decode (all kernels of the call)",
                 "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": ach / PEAK_HBM_GBS,
-                "traffic": read_traffic(w.name + "_absorbed"), "kernel_ms": k_s * 1e3,
+                "traffic": traffic, "traffic_source": note, "kernel_ms": k_s * 1e3,
                 "algorithmic_bytes": bytes_alg, "measured_stream_read_GBs": measured_stream_read()}
 
     roofline = None
@@ -244,16 +284,41 @@ def main():
         k_s = kern_ms / launches * 1e-3
         ach = flops / k_s / 1e12
         peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
+        plain = not (args.mlp_hidden or args.rope_window or args.unfused or args.packed_weights)
+        traffic, note = read_traffic(w.name) if plain else (None, "counter summaries cover the plain fused kernel only")
         roofline = {"bound": "mfma",
                     "kernel": "recon_mfma_kernel + fused_decode_kernel" if args.mlp_hidden else "fused_decode_kernel",
                     "achieved": ach,
                     "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
-                    # the stored counter summary is of the plain fused kernel on this workload
-                    "traffic": None if (args.mlp_hidden or args.rope_window or args.unfused
-                                        or args.packed_weights) else read_traffic(w.name),
-                    "kernel_ms": k_s * 1e3,
+                    "traffic": traffic, "traffic_source": note,
+                    "kernel_ms": k_s * 1e3, "launches_timed": launches,
                     "algorithmic_flop": flops, "algorithmic_bytes": bytes_alg,
                     "hbm_frac_of_algorithmic_bytes": bytes_alg / k_s / 1e9 / PEAK_HBM_GBS}
+
+    # second roofline object: the prefill chunk (predictor product over the chunk's visible context
+    # + causal attention), both on the matrix cores
+    roofline_prefill = None
+    if has_prefill and w.dtype == "bf16" and prof[1][1] > 0 and prof[2][1] > 0:
+        Lp = inp.seq_len[inp.n_decode]
+        Tq, q0 = int(inp.q_prefill.shape[0]), inp.q_pos0
+        recon_flop = 4.0 * w.d_in * w.d_out * Lp
+        # causal scores + weighted sum: 4 * d flop per (query, visible key, query head)
+        pairs = sum(q0 + i + 1 for i in range(Tq))
+        attn_flop = 4.0 * w.head_dim * w.n_q_heads * pairs
+        r_ms = prof[1][0] / prof[1][1]
+        a_ms = prof[2][0] / prof[2][1]
+        ach = (recon_flop + attn_flop) / ((r_ms + a_ms) * 1e-3) / 1e12
+        traffic, note = read_traffic(w.name + "_prefill")
+        roofline_prefill = {
+            "bound": "mfma", "kernel": "recon_mfma_kernel + prefill_attn_dma_kernel (one chunk)",
+            "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+            "traffic": traffic, "traffic_source": note,
+            "kernel_ms": r_ms + a_ms, "algorithmic_flop": recon_flop + attn_flop,
+            "predictor_product": {"kernel_ms": r_ms, "algorithmic_flop": recon_flop,
+                                  "frac": recon_flop / (r_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+            "attention": {"kernel_ms": a_ms, "algorithmic_flop": attn_flop,
+                          "frac": attn_flop / (a_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+            "chunk": {"queries": Tq, "q_pos0": q0, "context": Lp}}
 
     out = {
         "metric": "context tokens/s/layer for fused reconstruct+decode-attn; % MFMA & HBM peak",
@@ -261,6 +326,8 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "batch": B, "context_tokens": tokens,
+                   "decode_tokens": dec_tokens,
+                   "prefill_chunk_tokens": inp.seq_len[inp.n_decode] if has_prefill else 0,
                    "H_q": w.n_q_heads, "H_kv": w.n_kv_heads, "head_dim": w.head_dim,
                    "n_retained": w.n_retained, "d_in": w.d_in, "d_out": w.d_out,
                    "path": ("unfused" if args.unfused else "absorbed" if args.absorbed
@@ -269,14 +336,18 @@ def main():
                    "predictor": f"one hidden layer of {args.mlp_hidden}, ReLU" if args.mlp_hidden else "linear",
                    "weights": "packed [d_out,d_in]" if args.packed_weights else "row-major [d_in,d_out]",
                    "step": "cache_append(anchor)+cache_append(target)+decode_attn"
-                           + ("+prefill_attn" if has_prefill else ""),
-                   "prefill_ms_last_step": prefill_ms},
+                           + ("+prefill_attn" if has_prefill else "")},
+        "clock_ramp": {"seconds": ramp_s, "untimed_steps": ramp_steps},
+        "input_generation_s": t_gen,
         "roofline": roofline,
     }
+    if roofline_prefill is not None:
+        out["roofline_prefill"] = roofline_prefill
     if also_absorbed:
         # same step, same inputs, decode in the other association order (Eq. 3 is linear)
         dw.set_flags(ek.FLAG_ABSORBED)
-        dt2, k2, l2 = timed_run()
+        dt2, prof2 = timed_run()
+        k2, l2 = prof2[0]
         out["absorbed_mode"] = {"value": tokens / (dt2 / args.steps), "unit": "context tokens/s/layer",
                                 "ms_per_step": dt2 * 1e3 / args.steps,
                                 "roofline": absorbed_roofline(k2, l2) if l2 > 0 and k2 > 0 else None}

@@ -334,6 +334,11 @@ int echokv_prefill_attn_ex(const echokv_shape *shape, const echokv_layer_cache *
  * launches, and forgets them.  Not thread safe; keep it off in production. */
 int echokv_profile_enable(int on);
 int echokv_profile_read(double *total_ms, int64_t *launches);
+/* The same for a prefill chunk: channel 1 = the chunk's predictor product (Eq. 3
+ * for every visible token), channel 2 = its causal attention kernel (Eq. 7);
+ * channel 0 is what echokv_profile_read returns.  The recorder is one
+ * process-wide list: do not call the library from two threads while it is on. */
+int echokv_profile_read_channel(int channel, double *total_ms, int64_t *launches);
 
 /* Measurement aid: the rate at which a plain kernel streams `bytes` of device
  * memory at `buf` (16-byte aligned, at least 403 MB to mean anything; the

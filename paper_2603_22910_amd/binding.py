@@ -30,7 +30,7 @@ EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_cache_compress", "echokv_decode_attn_ex", "echokv_window_append",
            "echokv_mlp_workspace_bytes", "echokv_decode_attn_mlp", "echokv_profile_stream_read",
            "echokv_fit_workspace_bytes", "echokv_fit_linear", "echokv_prefill_attn_ex",
-           "echokv_decode_attn_static")
+           "echokv_decode_attn_static", "echokv_profile_read_channel")
 ACT_RELU, ACT_SILU = 1, 2
 
 
@@ -133,6 +133,8 @@ def load() -> C.CDLL:
     lib.echokv_profile_enable.argtypes = [C.c_int]
     lib.echokv_profile_read.restype = C.c_int
     lib.echokv_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.echokv_profile_read_channel.restype = C.c_int
+    lib.echokv_profile_read_channel.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.echokv_profile_stream_read.restype = C.c_int
     lib.echokv_profile_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int32, C.POINTER(C.c_double)]
     _LIB = lib
@@ -359,8 +361,10 @@ def profile_enable(on: bool):
     _check(load().echokv_profile_enable(1 if on else 0), "echokv_profile_enable")
 
 
-def profile_read():
-    """(total milliseconds, launches) of the dominant decode kernel since the last read."""
+def profile_read(channel: int = 0):
+    """(total milliseconds, launches) since the last read.  Channel 0: the dominant decode
+    kernel(s); 1: a prefill chunk's predictor product; 2: its attention kernel."""
     ms, n = C.c_double(0.0), C.c_int64(0)
-    _check(load().echokv_profile_read(C.byref(ms), C.byref(n)), "echokv_profile_read")
+    _check(load().echokv_profile_read_channel(int(channel), C.byref(ms), C.byref(n)),
+           "echokv_profile_read_channel")
     return float(ms.value), int(n.value)

@@ -129,17 +129,47 @@ int static_scratch(void** out) {
   return ECHOKV_OK;
 }
 
-// Optional event pairs around the dominant decode kernel (echokv_profile_*).
+// Optional event pairs around the dominant kernels (echokv_profile_*).  Channel 0: the decode
+// call's dominant kernel(s); 1: a prefill chunk's predictor product; 2: its attention kernel.
+constexpr int kProfChannels = 3;
 struct Profiler {
   bool on = false;
-  std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs;   // recorded, not yet read
-  std::vector<hipEvent_t> pool;                           // created once, reused
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> pairs[kProfChannels];   // recorded, not yet read
+  std::vector<hipEvent_t> pool;                                          // created once, reused
   bool get(hipEvent_t* e) {
     if (!pool.empty()) { *e = pool.back(); pool.pop_back(); return true; }
     return hipEventCreate(e) == hipSuccess;
   }
 };
 Profiler g_prof;
+
+// One timed region on a stream.  Does nothing while profiling is off.  Events of a region that is
+// left early (an error return between begin and end) go back to the pool.
+struct ProfScope {
+  int ch = 0;
+  hipStream_t st = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  bool open = false;
+  int begin(int channel, hipStream_t stream) {
+    if (!g_prof.on) return ECHOKV_OK;
+    ch = channel; st = stream;
+    if (!g_prof.get(&e0)) return ECHOKV_ERR_HIP;
+    if (!g_prof.get(&e1)) { g_prof.pool.push_back(e0); return ECHOKV_ERR_HIP; }
+    open = true;
+    if (hipEventRecord(e0, st) != hipSuccess) return ECHOKV_ERR_HIP;
+    return ECHOKV_OK;
+  }
+  int end() {
+    if (!open) return ECHOKV_OK;
+    if (hipEventRecord(e1, st) != hipSuccess) return ECHOKV_ERR_HIP;
+    g_prof.pairs[ch].emplace_back(e0, e1);
+    open = false;
+    return ECHOKV_OK;
+  }
+  ~ProfScope() {
+    if (open) { g_prof.pool.push_back(e0); g_prof.pool.push_back(e1); }
+  }
+};
 
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) return ECHOKV_ERR_HIP; } while (0)
 #define LAUNCH_CHECK() do { if (hipGetLastError() != hipSuccess) return ECHOKV_ERR_HIP; } while (0)
@@ -299,12 +329,9 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
     }
     if (n_rec_heads > 0) {
       if (fused) {
-        hipEvent_t e0 = nullptr, e1 = nullptr;
-        if (g_prof.on) {
-          if (!g_prof.get(&e0) || !g_prof.get(&e1)) return ECHOKV_ERR_HIP;
-          HIP_TRY(hipEventRecord(e0, st));
-        }
-        int rc;
+        ProfScope prof;
+        int rc = prof.begin(0, st);
+        if (rc) return rc;
         if constexpr (sizeof(T) == 4)
           rc = launch_fused_decode_f32(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale,
                                        (const float*)an->k, (const float*)an->v, (const float*)tg->k,
@@ -321,10 +348,8 @@ int decode_impl(const Dims& dm, uint32_t flags, const echokv_layer_cache* an,
                                       (const T*)an->k, (const T*)an->v, (const T*)tg->k,
                                       (const T*)tg->v, wk, wv, qq, po,
                                       pml, mt, &fused_step, st, (flags & ECHOKV_FLAG_W_PACKED) != 0, kx);
-        if (g_prof.on) {
-          HIP_TRY(hipEventRecord(e1, st));
-          g_prof.pairs.emplace_back(e0, e1);
-        }
+        if (rc) return rc;
+        rc = prof.end();
         if (rc) return rc;
       } else {
         T* kh = (T*)(ws + wp.off_kh);
@@ -438,6 +463,9 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
     const T* wk; const T* wv;
     int rc = effective_weights<T>(dm, w_k, w_v, ws, wp, &wk, &wv, st);
     if (rc) return rc;
+    ProfScope prof;
+    rc = prof.begin(1, st);
+    if (rc) return rc;
     SeqMeta mt;
     mt.n = 1; mt.start[0] = row0; mt.len[0] = Ltot; mt.sbase[0] = 0; mt.sbase[1] = slots_for(Ltot);
     if (recon_mfma_supported<T>()) {
@@ -454,8 +482,13 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
       rc = launch_recon_fma<T>(dm, g, mt, st);
       if (rc) return rc;
     }
+    rc = prof.end();
+    if (rc) return rc;
   }
   if (prefill_mfma_supported<T>(dm.d)) {
+    ProfScope prof;
+    int rcp = prof.begin(2, st);
+    if (rcp) return rcp;
     const T* k_ret = (const T*)tg->k + row0 * dm.m;
     if constexpr (sizeof(T) == 2) {
       if (rope_cos) {
@@ -469,9 +502,11 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
         if (n_ret_heads > 0) k_ret = krot;
       }
     }
-    return launch_prefill_mfma<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale, dm.out_bf16,
-                                  k_ret, (const T*)tg->v + row0 * dm.m,
-                                  kh, vh, (const T*)q, T_q, q_pos0, out, lse, st);
+    rcp = launch_prefill_mfma<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale, dm.out_bf16,
+                                 k_ret, (const T*)tg->v + row0 * dm.m,
+                                 kh, vh, (const T*)q, T_q, q_pos0, out, lse, st);
+    if (rcp) return rcp;
+    return prof.end();
   }
   // streaming path: each query is a virtual sequence of length q_pos0 + i + 1
   for (int i0 = 0; i0 < T_q; i0 += kPrefillQChunk) {
@@ -564,14 +599,12 @@ int mlp_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_layer_ca
       if (rc) return rc;
     }
     if (n_rec_heads > 0) {
-      hipEvent_t e0 = nullptr, e1 = nullptr;
-      if (g_prof.on) {
-        if (!g_prof.get(&e0) || !g_prof.get(&e1)) return ECHOKV_ERR_HIP;
-        HIP_TRY(hipEventRecord(e0, st));
-      }
+      ProfScope prof;
+      int rc = prof.begin(0, st);
+      if (rc) return rc;
       T* hk = (T*)(ws + wp.off_hk);
       T* hv = (T*)(ws + wp.off_hv);
-      int rc = launch_recon_mfma<T>(dm.D, dm.m, hidden, (const T*)an->k, (const T*)an->v,
+      rc = launch_recon_mfma<T>(dm.D, dm.m, hidden, (const T*)an->k, (const T*)an->v,
                                     (const T*)tg->k, (const T*)tg->v, w1k, w1v, hk, hv, hidden, 0,
                                     mt, st, act);
       if (rc) return rc;
@@ -580,10 +613,8 @@ int mlp_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_layer_ca
       rc = launch_fused_decode<T>(dm.H_q, dm.H_kv, dm.d, 0, dm.d_out, dm.g0, dm.scale, hk, hv,
                                   (const T*)nullptr, (const T*)nullptr, w2k, w2v, qq, po, pml, hm,
                                   &fused_step, st, false, KvExtras(), hidden);
-      if (g_prof.on) {
-        HIP_TRY(hipEventRecord(e1, st));
-        g_prof.pairs.emplace_back(e0, e1);
-      }
+      if (rc) return rc;
+      rc = prof.end();
       if (rc) return rc;
     }
     int rc = dm.out_bf16
@@ -720,11 +751,9 @@ int absorbed_impl(const Dims& dm, bool value_only, const echokv_layer_cache* an,
     const int nhb = pl.H_pad / absorbed::kHB;
     const int n = mt.n;
 
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (g_prof.on) {
-      if (!g_prof.get(&e0) || !g_prof.get(&e1)) return ECHOKV_ERR_HIP;
-      HIP_TRY(hipEventRecord(e0, st));
-    }
+    ProfScope prof;
+    rc = prof.begin(0, st);
+    if (rc) return rc;
     if (!value_only) {
       const dim3 qg((dm.d_in + 127) / 128, dm.H_kv);
       if (dm.d == 128) hipLaunchKernelGGL((absorbed::absorb_q_kernel<128>), qg, dim3(256), 0, st, a, n);
@@ -785,10 +814,8 @@ int absorbed_impl(const Dims& dm, bool value_only, const echokv_layer_cache* an,
     if (dm.out_bf16) hipLaunchKernelGGL((absorbed::out_final_kernel<bf16_t>), dim3(fb), dim3(256), 0, st, a, n);
     else hipLaunchKernelGGL((absorbed::out_final_kernel<float>), dim3(fb), dim3(256), 0, st, a, n);
     LAUNCH_CHECK();
-    if (g_prof.on) {
-      HIP_TRY(hipEventRecord(e1, st));
-      g_prof.pairs.emplace_back(e0, e1);
-    }
+    rc = prof.end();
+    if (rc) return rc;
   }
   return ECHOKV_OK;
 }
@@ -853,21 +880,26 @@ int echokv_profile_enable(int on) {
   return ECHOKV_OK;
 }
 
-int echokv_profile_read(double* total_ms, int64_t* launches) {
+int echokv_profile_read_channel(int channel, double* total_ms, int64_t* launches) {
   if (!total_ms || !launches) return ECHOKV_ERR_NULL;
+  if (channel < 0 || channel >= kProfChannels) return ECHOKV_ERR_SHAPE;
   double tot = 0.0;
   int64_t n = 0;
   int rc = ECHOKV_OK;
-  for (auto& pr : g_prof.pairs) {
+  for (auto& pr : g_prof.pairs[channel]) {
     float ms = 0.f;
     if (hipEventSynchronize(pr.second) != hipSuccess ||
         hipEventElapsedTime(&ms, pr.first, pr.second) != hipSuccess) rc = ECHOKV_ERR_HIP;
     else { tot += ms; ++n; }
     g_prof.pool.push_back(pr.first); g_prof.pool.push_back(pr.second);
   }
-  g_prof.pairs.clear();
+  g_prof.pairs[channel].clear();
   *total_ms = tot; *launches = n;
   return rc;
+}
+
+int echokv_profile_read(double* total_ms, int64_t* launches) {
+  return echokv_profile_read_channel(0, total_ms, launches);
 }
 
 int echokv_profile_stream_read(const void* buf, size_t bytes, int32_t repeats, double* gb_per_s) {

@@ -201,9 +201,7 @@ def generate(w: Workload) -> Inputs:
     D, m = w.D, w.n_retained
     td = w.torch_dtype
 
-    valid = torch.zeros(pool, 1, dtype=torch.float32)
-    for s_, n_ in zip(starts, lens):
-        valid[s_:s_ + n_] = 1.0
+    gaps = [(s_ + n_, s_ + c_) for s_, n_, c_ in zip(starts, lens, caps) if c_ > n_]
 
     def layer_pair(tag):
         """Anchor rows A ~ N(0,1) and the target's retained prefix A @ M1 + 0.1 E1."""
@@ -214,11 +212,16 @@ def generate(w: Workload) -> Inputs:
         block = _CHUNK_ROWS * _DRAW_THREADS
         for r0 in range(0, pool, block):
             r1 = min(pool, r0 + block)
-            a = _draw_rows(r0, r1, D, w.seed, tag + "_a") * valid[r0:r1]
-            a_out[r0:r1] = a.to(td)
+            a = _draw_rows(r0, r1, D, w.seed, tag + "_a")
+            a_out[r0:r1].copy_(a)
             if m:
                 e = _draw_rows(r0, r1, m, w.seed, "E1_" + tag)
-                r_out[r0:r1] = ((a @ M1 + 0.1 * e) * valid[r0:r1]).to(td)
+                e.mul_(0.1)
+                e.addmm_(a, M1)                 # A @ M1 + 0.1 E1, in place
+                r_out[r0:r1].copy_(e)
+        for g0, g1 in gaps:                     # rows no sequence owns stay zero
+            a_out[g0:g1] = 0
+            r_out[g0:g1] = 0
         return a_out, r_out
 
     K_a, K_r = layer_pair("K")

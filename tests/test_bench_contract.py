@@ -24,13 +24,27 @@ def test_bench_refuses_a_multi_rank_launch():
     assert r.returncode != 0 and "ONE GPU" in r.stderr
 
 
-def test_traffic_files_parse():
+def test_traffic_files_parse_and_are_tied_to_the_kernel_sources(tmp_path, monkeypatch):
     sys.path.insert(0, ROOT)
     import bench
-    for name in ("cfg1_7b_mha_r50_b8_l4096", "cfg1_7b_mha_r50_b8_l4096_absorbed"):
-        v = bench.read_traffic(name)
-        assert v is not None and v > 5e8
-    assert bench.read_traffic("no_such_workload") is None
+    assert bench.read_traffic("no_such_workload")[0] is None
+    prof = os.path.join(ROOT, "profiles")
+    names = [f[len("traffic_"):-4] for f in os.listdir(prof) if f.startswith("traffic_") and f.endswith(".txt")]
+    assert names
+    for name in names:
+        v, note = bench.read_traffic(name)
+        # a summary is either current (a figure) or reported stale (no figure, the reason given)
+        assert (v is not None and v > 1e6) or "stale" in note, (name, note)
+    # a summary stamped with other kernel sources is not used
+    monkeypatch.setattr(bench, "kernel_source_sha", lambda: "0" * 16)
+    for name in names:
+        v, note = bench.read_traffic(name)
+        assert v is None and "stale" in note
+
+
+def test_bench_defaults_to_the_largest_single_gpu_configuration():
+    src = open(os.path.join(ROOT, "bench.py")).read()
+    assert '"--config", type=int, default=4' in src
 
 
 def test_entry_module_has_build_and_smoke():

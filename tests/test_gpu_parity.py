@@ -190,12 +190,14 @@ def test_reconstruct_small(cfg):
     for got, want, nm in ((k_out, k_ref, "K"), (v_out, v_ref, "V")):
         mx, rl = error_metrics(host(got), want)
         print(f"[parity] {w.name} reconstruct {nm}: max_abs={mx:.3e} rel_l2={rl:.3e}")
-        assert mx <= tol[0] * 2 and rl <= tol[1]
+        assert mx <= tol[0] and rl <= tol[1]
 
 
-def test_cache_append_then_decode_matches_bulk_layout():
-    """Tokens appended in pieces through the ABI give the same cache, bit for
-    bit, as the bulk layout; the dropped dims are never written."""
+def test_cache_append_matches_the_oracle_layout():
+    """Tokens appended in pieces through the ABI against the oracle's cache_append fed the same
+    full-width rows (Eq. 1 for the anchor, Eq. 2 for the target): bit for bit the same cache; the
+    dropped dims (marker values here) are never written anywhere."""
+    from oracle import echokv_oracle as orc
     w = synth.Workload("append", "bf16", 8, 8, 128, 512, seed=21, seq_lens=(200, 77, 300))
     inp = synth.generate(w)
     dev = torch.device("cuda:0")
@@ -206,7 +208,11 @@ def test_cache_append_then_decode_matches_bulk_layout():
     zero = [0] * 3
     anchor = ek.LayerCache(Ka, Va, w.D, pool, inp.seq_start, zero, inp.seq_cap)
     target = ek.LayerCache(Kr, Vr, w.n_retained, pool, inp.seq_start, zero, inp.seq_cap)
-    # the target layer's full K/V: retained dims as generated, dropped dims = a marker
+    # the oracle's caches (fp64 holds every bf16 value exactly) and its own sequence lengths
+    o_Ka = np.zeros((pool, w.D)); o_Va = np.zeros((pool, w.D))
+    o_Kr = np.zeros((pool, w.n_retained)); o_Vr = np.zeros((pool, w.n_retained))
+    o_len_a = [0, 0, 0]; o_len_t = [0, 0, 0]
+    # the target layer's full K/V rows: retained dims as generated, dropped dims = a marker
     done = [0, 0, 0]
     steps = [[150, 77, 1], [50, 0, 299]]
     for n_new in steps:
@@ -218,13 +224,20 @@ def test_cache_append_then_decode_matches_bulk_layout():
             full_v = torch.full((n, w.D), -77.0, dtype=torch.bfloat16); full_v[:, :w.n_retained] = inp.V_r[r]
             kt.append(full_k); vt.append(full_v)
             done[b] += n
+            orc.cache_append(o_Ka, inp.seq_start[b], o_len_a[b], ref.f64(ka[-1]))
+            o_len_a[b] = orc.cache_append(o_Va, inp.seq_start[b], o_len_a[b], ref.f64(va[-1]))
+            orc.cache_append(o_Kr, inp.seq_start[b], o_len_t[b], ref.f64(full_k))
+            o_len_t[b] = orc.cache_append(o_Vr, inp.seq_start[b], o_len_t[b], ref.f64(full_v))
         cat = lambda xs: torch.cat(xs).to(dev)
         ek.cache_append(shape, anchor, cat(ka), cat(va), n_new)
         ek.cache_append(shape, target, cat(kt), cat(vt), n_new)
     torch.cuda.synchronize()
-    assert list(anchor.seq_len) == inp.seq_len and list(target.seq_len) == inp.seq_len
-    assert torch.equal(Ka.cpu(), inp.K_a) and torch.equal(Va.cpu(), inp.V_a)
-    assert torch.equal(Kr.cpu(), inp.K_r) and torch.equal(Vr.cpu(), inp.V_r)
+    assert list(anchor.seq_len) == o_len_a and list(target.seq_len) == o_len_t == inp.seq_len
+    for got, want in ((Ka, o_Ka), (Va, o_Va), (Kr, o_Kr), (Vr, o_Vr)):
+        assert np.array_equal(host(got), want)
+    assert not (np.abs(host(Kr)) == 77.0).any() and not (np.abs(host(Vr)) == 77.0).any()
+    # and the generator's bulk layout is the same cache
+    assert torch.equal(Ka.cpu(), inp.K_a) and torch.equal(Kr.cpu(), inp.K_r)
     with pytest.raises(ek.EchoKVError) as e:
         ek.cache_append(shape, target, Ka, Va, [1000, 0, 0])
     assert e.value.code == ek.ERR_CAPACITY
@@ -327,70 +340,6 @@ def test_prefill_last_row_equals_decode():
     dd = DeviceWorkload(single, out_dtype="f32")
     o_dec, _ = dd.decode(); torch.cuda.synchronize()
     np.testing.assert_allclose(host(out)[-1], host(o_dec)[0], rtol=1e-2, atol=4e-3)  # bf16 K_hat in prefill
-
-
-# ---- full-size configurations: sampled outputs against the oracle ----------------
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
-def test_decode_full_size_sampled(cfg):
-    w = synth.CONFIGS[cfg]
-    if cfg == 4:
-        w = w.scaled(prefill_len=0, prefill_q=0)
-    print(f"[full] generating {w.name}", flush=True)
-    inp = synth.generate(w)
-    dw = DeviceWorkload(inp, flags=ek.FLAG_ABSORBED)      # workspace sized for both paths
-    results = {}
-    for name, fl in (("fused", 0), ("absorbed", ek.FLAG_ABSORBED)):
-        dw.set_flags(fl)
-        out, lse = dw.decode(); torch.cuda.synchronize()
-        results[name] = (host(out).copy(), host(lse).copy())
-        assert np.isfinite(results[name][0]).all() and np.isfinite(results[name][1]).all()
-    rng = np.random.default_rng(cfg)
-    n_ret = w.n_retained // w.head_dim * w.group
-    picks = []
-    if cfg == 4:   # shortest, longest and one more sequence
-        order = np.argsort(inp.seq_len[:inp.n_decode])
-        seqs = [int(order[0]), int(order[-1]), int(order[len(order) // 2])]
-    else:
-        seqs = sorted({0, inp.n_decode - 1})
-    for b in seqs:
-        picks.append((b, int(rng.integers(0, n_ret))))                       # a retained head
-        picks.append((b, int(rng.integers(n_ret, w.n_q_heads))))             # predicted heads
-        picks.append((b, w.n_q_heads - 1))
-    refs = []
-    for b, h in picks:
-        o, l = ref.decode_head_ref(inp, b, h)
-        refs.append(o)
-        for name, (got, got_lse) in results.items():
-            assert abs(got_lse[b, h] - l) <= 2e-2, (name, b, h)
-        print(f"[full] {w.name} seq {b} head {h} ok", flush=True)
-    for name, (got, _) in results.items():
-        check(np.stack([got[b, h] for b, h in picks]), np.stack(refs), "bf16",
-              f"{w.name} full-size sampled, {name}")
-
-
-@pytest.mark.parametrize("q_pos0", [0, 3000])
-def test_prefill_full_size_sampled(q_pos0):
-    """The benchmark's 8192-query causal chunk on the 7B-shaped layer (50% retention);
-    a sample of query rows is checked against the oracle, all heads."""
-    from oracle import echokv_oracle as orc
-    T_q = 8192
-    w = synth.CONFIGS[4].scaled(batch=0, seq_lens=(300,), prefill_len=q_pos0 + T_q, prefill_q=T_q)
-    inp = synth.generate(w)
-    dw = DeviceWorkload(inp)
-    out, lse = dw.prefill(); torch.cuda.synchronize()
-    got, got_lse = host(out), host(lse)
-    assert np.isfinite(got).all()
-    b = inp.n_decode
-    K_a, V_a, K_r, V_r = ref.seq_arrays(inp, b)
-    W_K, W_V = ref.weights(inp)
-    K_t = orc.reconstruct(K_a, K_r, W_K); V_t = orc.reconstruct(V_a, V_r, W_V)
-    rng = np.random.default_rng(5)
-    idx = sorted({0, 1, 63, 64, 127, 128, T_q - 1, *rng.integers(0, T_q, 40).tolist()})
-    Q = ref.f64(inp.q_prefill)[idx]
-    o_ref, l_ref, _ = orc.attention_rows(Q, K_t, V_t, w.n_kv_heads,
-                                         visible=[q_pos0 + i + 1 for i in idx])
-    check(got[idx], o_ref, "bf16", f"prefill full size q_pos0={q_pos0}")
-    assert np.abs(got_lse[idx] - l_ref).max() <= 2e-2
 
 
 @pytest.mark.parametrize("flags", MODES)
