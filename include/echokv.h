@@ -124,10 +124,19 @@ int echokv_cache_append(const echokv_shape *shape, echokv_layer_cache *dst,
  * transition of Sec. "Overview of EchoKV": when memory runs short, the dims
  * [m, D) of the layer are evicted and from then on predicted; Eq. 2 says what
  * stays).  Copies the first m dims of every valid row of `full` (width D) into
- * `dst` (width m) and sets dst->seq_len[b] = full->seq_len[b].  The two caches
- * describe the same sequences but may place them differently (seq_start,
- * seq_cap); dst must not overlap full.  The caller frees the full cache once
- * the stream has passed this call.  ERR_CAPACITY if a sequence does not fit. */
+ * `dst` (width m) and sets dst->seq_len[b] = full->seq_len[b].
+ *  - Two buffers: the two caches describe the same sequences but may place them
+ *    differently (seq_start, seq_cap); they must not overlap.  The caller frees
+ *    the full cache once the stream has passed this call.
+ *  - In place (no second buffer, for the moment memory is short): dst->k ==
+ *    full->k and dst->v == full->v, dst->seq_start[b] == full->seq_start[b].
+ *    The pool [pool_tokens, D] becomes the pool [pool_tokens, m] at the same
+ *    address: row r moves from byte offset r * D * es to r * m * es.  Rows
+ *    between the first and the last valid row are all moved (gap rows too).
+ *    Afterwards the bytes behind pool_tokens * m * es are the caller's to give
+ *    back; `full` no longer describes anything.  Any other overlap of the two
+ *    caches returns ECHOKV_ERR_UNSUPPORTED.
+ * ERR_CAPACITY if a sequence does not fit dst->seq_cap. */
 int echokv_cache_compress(const echokv_shape *shape, const echokv_layer_cache *full,
                           echokv_layer_cache *dst, void *hip_stream);
 
@@ -170,6 +179,24 @@ int echokv_decode_attn(const echokv_shape *shape, const echokv_layer_cache *anch
                        const echokv_layer_cache *target, const void *w_k,
                        const void *w_v, const void *q, void *out, float *lse_out,
                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Which kernels echokv_decode_attn will run for `shape` (its flags included),
+ * so that a caller can tell beforehand when a layer does not take the fused
+ * reconstruct-then-attend kernel.  The fused kernel keeps the softmax
+ * numerators of every (KV head in its 128-column wave tile, query head of the
+ * group) pair in LDS, at most 8 pairs: (128 / d) * G <= 8.  A layer beyond that
+ * (e.g. d = 128 with 16 query heads per KV head) is served by the materialising
+ * path -- predictor product into the workspace, then streaming attention --
+ * exactly as if ECHOKV_FLAG_UNFUSED were set, and echokv_workspace_bytes
+ * already accounts for it.  The same call reports the choice made for the
+ * other flags.  *path_out is one of ECHOKV_PATH_*. */
+#define ECHOKV_PATH_FUSED 0          /* fused predictor product + attention, row-major W */
+#define ECHOKV_PATH_FUSED_DIRECT 1   /* the same with packed W, operands straight into LDS */
+#define ECHOKV_PATH_UNFUSED 2        /* K-hat / V-hat materialised in the workspace, then attended */
+#define ECHOKV_PATH_ABSORBED 3       /* ECHOKV_FLAG_ABSORBED */
+#define ECHOKV_PATH_ABSORB_V 4       /* ECHOKV_FLAG_ABSORB_V */
+#define ECHOKV_PATH_RETAINED_ONLY 5  /* m == D: nothing to predict, plain streaming attention */
+int echokv_decode_path(const echokv_shape *shape, int32_t *path_out);
 
 /* echokv_decode_attn for callers that cannot allocate device memory and have no
  * workspace to hand over: code under HIP graph capture, tight serving loops,

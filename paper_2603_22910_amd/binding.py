@@ -30,8 +30,9 @@ EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_cache_compress", "echokv_decode_attn_ex", "echokv_window_append",
            "echokv_mlp_workspace_bytes", "echokv_decode_attn_mlp", "echokv_profile_stream_read",
            "echokv_fit_workspace_bytes", "echokv_fit_linear", "echokv_prefill_attn_ex",
-           "echokv_decode_attn_static", "echokv_profile_read_channel")
+           "echokv_decode_attn_static", "echokv_profile_read_channel", "echokv_decode_path")
 ACT_RELU, ACT_SILU = 1, 2
+PATH_FUSED, PATH_FUSED_DIRECT, PATH_UNFUSED, PATH_ABSORBED, PATH_ABSORB_V, PATH_RETAINED_ONLY = range(6)
 
 
 class EchoKVError(RuntimeError):
@@ -133,6 +134,8 @@ def load() -> C.CDLL:
     lib.echokv_profile_enable.argtypes = [C.c_int]
     lib.echokv_profile_read.restype = C.c_int
     lib.echokv_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+    lib.echokv_decode_path.restype = C.c_int
+    lib.echokv_decode_path.argtypes = [C.POINTER(Shape), C.POINTER(C.c_int32)]
     lib.echokv_profile_read_channel.restype = C.c_int
     lib.echokv_profile_read_channel.argtypes = [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     lib.echokv_profile_stream_read.restype = C.c_int
@@ -251,6 +254,13 @@ def decode_attn(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, 
     _check(load().echokv_decode_attn(C.byref(shape), C.byref(a), C.byref(t), _ptr(w_k), _ptr(w_v),
                                      _ptr(q), _ptr(out), _ptr(lse_out), _ptr(workspace), nbytes,
                                      _stream(stream)), "echokv_decode_attn")
+
+
+def decode_path(shape: Shape) -> int:
+    """One of PATH_*: the kernels echokv_decode_attn runs for this shape and its flags."""
+    out = C.c_int32(-1)
+    _check(load().echokv_decode_path(C.byref(shape), C.byref(out)), "echokv_decode_path")
+    return int(out.value)
 
 
 def decode_attn_static(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w_v, q, out,

@@ -977,6 +977,37 @@ int echokv_cache_append(const echokv_shape* shape, echokv_layer_cache* dst, cons
   return ECHOKV_OK;
 }
 
+// In-place form of echokv_cache_compress for one matrix pair: rows [row_begin, row_end) of the
+// pool at `base` narrow from D to m dims where they lie.
+static int compress_in_place(const Dims& dm, char* k, char* v, int64_t row_begin, int64_t row_end,
+                             hipStream_t st) {
+  const int64_t sb = (int64_t)dm.D * dm.es, db = (int64_t)dm.m * dm.es;
+  // rows [r0, r1) can move as one plain copy once their destination ends at or below the byte
+  // where their source begins: r1 * m <= r0 * D
+  auto chunk_end = [&](int64_t r0) { return std::min(row_end, r0 * dm.D / dm.m); };
+  int64_t r0 = row_begin;
+  int64_t r_seq = r0;
+  while (r_seq < row_end && chunk_end(r_seq) - r_seq < 64) ++r_seq;   // too early for plain copies
+  if (r_seq > r0) {
+    CompactArgs c;
+    c.base[0] = k; c.base[1] = v; c.src_row_bytes = sb; c.dst_row_bytes = db; c.r0 = r0; c.r1 = r_seq;
+    hipLaunchKernelGGL(compact_rows_seq_kernel, dim3(2), dim3(256), 0, st, c);
+    LAUNCH_CHECK();
+    r0 = r_seq;
+  }
+  while (r0 < row_end) {
+    const int64_t r1 = chunk_end(r0);
+    Copy2dArgs c;
+    c.src[0] = k + r0 * sb; c.src[1] = v + r0 * sb;
+    c.dst[0] = k + r0 * db; c.dst[1] = v + r0 * db;
+    c.src_row_bytes = sb; c.dst_row_bytes = db; c.copy_bytes = db; c.rows = r1 - r0;
+    hipLaunchKernelGGL(copy2d_kernel, dim3((unsigned)std::min<int64_t>(r1 - r0, 16384), 2), dim3(256), 0, st, c);
+    LAUNCH_CHECK();
+    r0 = r1;
+  }
+  return ECHOKV_OK;
+}
+
 int echokv_cache_compress(const echokv_shape* shape, const echokv_layer_cache* full,
                           echokv_layer_cache* dst, void* hip_stream) {
   Dims dm;
@@ -990,7 +1021,32 @@ int echokv_cache_compress(const echokv_shape* shape, const echokv_layer_cache* f
   for (int b = 0; b < full->batch; ++b)
     if (full->seq_len[b] > dst->seq_cap[b]) return ECHOKV_ERR_CAPACITY;
   hipStream_t st = (hipStream_t)hip_stream;
-  if (dm.m > 0) {
+  // in place: dst describes the same pool at the same addresses, rows narrowed to m dims
+  const bool in_place = dm.m > 0 && dst->k == full->k && dst->v == full->v;
+  if (dm.m > 0 && !in_place) {
+    // any other overlap of the two caches is refused
+    auto overlaps = [&](const void* a, int64_t an, const void* b2, int64_t bn) {
+      const char* x = (const char*)a; const char* y = (const char*)b2;
+      return x < y + bn && y < x + an;
+    };
+    const int64_t fb = full->pool_tokens * (int64_t)dm.D * dm.es, db = dst->pool_tokens * (int64_t)dm.m * dm.es;
+    if (overlaps(full->k, fb, dst->k, db) || overlaps(full->v, fb, dst->v, db) ||
+        overlaps(full->k, fb, dst->v, db) || overlaps(full->v, fb, dst->k, db))
+      return ECHOKV_ERR_UNSUPPORTED;
+  }
+  if (in_place) {
+    int64_t row_begin = INT64_MAX, row_end = 0;
+    for (int b = 0; b < full->batch; ++b) {
+      if (dst->seq_start[b] != full->seq_start[b]) return ECHOKV_ERR_UNSUPPORTED;   // same rows, narrower
+      if (full->seq_len[b] == 0) continue;
+      row_begin = std::min(row_begin, full->seq_start[b]);
+      row_end = std::max(row_end, full->seq_start[b] + (int64_t)full->seq_len[b]);
+    }
+    if (dm.m < dm.D && row_end > row_begin) {
+      rc = compress_in_place(dm, (char*)full->k, (char*)full->v, row_begin, row_end, st);
+      if (rc) return rc;
+    }
+  } else if (dm.m > 0) {
     for (int b = 0; b < full->batch; ++b) {
       const int64_t rows = full->seq_len[b];
       if (rows == 0) continue;
@@ -1096,6 +1152,28 @@ int echokv_decode_attn(const echokv_shape* shape, const echokv_layer_cache* anch
                        size_t workspace_bytes, void* hip_stream) {
   return echokv_decode_attn_ex(shape, anchor, target, w_k, w_v, q, nullptr, out, lse_out, workspace,
                                workspace_bytes, hip_stream);
+}
+
+int echokv_decode_path(const echokv_shape* shape, int32_t* path_out) {
+  Dims dm;
+  int rc = check_shape(shape, &dm);
+  if (rc) return rc;
+  if (!path_out) return ECHOKV_ERR_NULL;
+  const uint32_t f = shape->flags;
+  if (f & kAbsModes) {
+    if (!absorbed_supported(dm, f)) return ECHOKV_ERR_UNSUPPORTED;
+    *path_out = (f & ECHOKV_FLAG_ABSORB_V) ? ECHOKV_PATH_ABSORB_V : ECHOKV_PATH_ABSORBED;
+    return ECHOKV_OK;
+  }
+  const bool can_fuse = dm.bf16 ? fused_decode_supported<bf16_t>(dm.d, dm.G)
+                                : fused_decode_supported<float>(dm.d, dm.G);
+  if ((f & ECHOKV_FLAG_W_PACKED) && (dm.r != 0 || (f & ECHOKV_FLAG_UNFUSED) || !dm.bf16 || !can_fuse))
+    return ECHOKV_ERR_UNSUPPORTED;
+  if (dm.d_out == 0) *path_out = ECHOKV_PATH_RETAINED_ONLY;
+  else if ((f & ECHOKV_FLAG_UNFUSED) || !can_fuse) *path_out = ECHOKV_PATH_UNFUSED;
+  else if ((f & ECHOKV_FLAG_W_PACKED) && !(f & ECHOKV_FLAG_STAGED)) *path_out = ECHOKV_PATH_FUSED_DIRECT;
+  else *path_out = ECHOKV_PATH_FUSED;
+  return ECHOKV_OK;
 }
 
 int echokv_decode_attn_static(const echokv_shape* shape, const echokv_layer_cache* anchor,
@@ -1218,6 +1296,10 @@ static int check_fit(const Dims& dm, int64_t n_rows) {
   if (n_rows < 64 || n_rows % 64) return ECHOKV_ERR_SHAPE;
   // the Gram product addresses each [n_rows, D] matrix through one 2 GB buffer window
   if (n_rows * (int64_t)dm.D * 2 >= ((int64_t)1 << 31)) return ECHOKV_ERR_UNSUPPORTED;
+  // ... and reads X^T [d_in, n_rows] as the row operand of the predictor-product kernel: its row
+  // pitch n_rows * 2 bytes goes through a 24-bit multiply, and a tile of 256 rows (+ one k-tile)
+  // through the same 2 GB window
+  if (n_rows * 2 >= ((int64_t)1 << 24) || 257 * n_rows * 2 >= ((int64_t)1 << 31)) return ECHOKV_ERR_UNSUPPORTED;
   return ECHOKV_OK;
 }
 

@@ -123,6 +123,46 @@ __global__ __launch_bounds__(256) void copy2d_kernel(Copy2dArgs a) {
   }
 }
 
+// In-place narrowing of rows [r0, r1) of a row-major matrix from src_row_bytes to the first
+// dst_row_bytes of each row, both at `base` (the full -> compressed switch of a target layer done
+// where the full cache lies).  Every destination byte sits at or below the source byte it comes
+// from, so walking the 16-byte pieces in (row, piece) order never overwrites a piece that is still
+// to be read -- as long as the pieces of one round have all been read before any of them is
+// written.  One workgroup per matrix (blockIdx.x = K or V) takes rounds of 256 x 16 pieces: load
+// all into registers, wait for the data, barrier, store.  Used for the first rows only; further on
+// source and destination of whole row ranges no longer overlap and plain copies take over.
+struct CompactArgs {
+  char* base[2];
+  int64_t src_row_bytes, dst_row_bytes;
+  int64_t r0, r1;
+};
+__global__ __launch_bounds__(256) void compact_rows_seq_kernel(CompactArgs a) {
+  char* base = a.base[blockIdx.x];
+  const int64_t ppr = a.dst_row_bytes >> 4;               // pieces per row
+  const int64_t p_end = a.r1 * ppr;
+  for (int64_t p0 = a.r0 * ppr; p0 < p_end; p0 += 256 * 16) {
+    uint4 v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int64_t p = p0 + j * 256 + threadIdx.x;
+      if (p < p_end) {
+        const int64_t row = p / ppr, c = p - row * ppr;
+        v[j] = *reinterpret_cast<const uint4*>(base + row * a.src_row_bytes + c * 16);
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0): this round's pieces are in registers
+    __syncthreads();                          // ... for every wave, before any of them is overwritten
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int64_t p = p0 + j * 256 + threadIdx.x;
+      if (p < p_end) {
+        const int64_t row = p / ppr, c = p - row * ppr;
+        *reinterpret_cast<uint4*>(base + row * a.dst_row_bytes + c * 16) = v[j];
+      }
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------
 // dst[c, r] = src[r, c] for a row-major [R, C] matrix (row pitch ld_src): 64x64 tiles through LDS.
 // Used once per weight matrix to lay W out as [d_out, d_in] (k-contiguous rows),

@@ -31,8 +31,8 @@ def test_exports_match_header(lib):
 
 
 def test_status_strings(lib):
-    seen = {ek.status_string(c) for c in range(8)}
-    assert len(seen) == 8 and ek.status_string(0) == "ok"
+    seen = {ek.status_string(c) for c in range(9)}
+    assert len(seen) == 9 and ek.status_string(0) == "ok"
     assert ek.status_string(99) == "unknown status"
 
 
@@ -264,6 +264,50 @@ def test_fit_argument_errors(lib):
     assert code(ek.fit_linear, sh, FAKE, FAKE, 4096, FAKE, big, max_iters=0, stream=0) == ek.ERR_SHAPE
     assert code(ek.fit_linear, sh, FAKE, FAKE, 4096, FAKE, _Ws(1024), stream=0) == ek.ERR_WORKSPACE
     assert code(ek.fit_linear, sh, FAKE, FAKE, 1 << 22, FAKE, big, stream=0) == ek.ERR_UNSUPPORTED   # > 2 GB per matrix
+    # a narrow layer (D = 128) stays under 2 GB per matrix far longer, but the transposed input's row
+    # pitch (n_rows * 2 bytes) must fit the kernel's 24-bit multiply and its 2 GB window
+    narrow = ek.make_shape(2, 2, 64, 64, "bf16")
+    assert ek.fit_workspace_bytes(narrow, 1 << 21) > 0
+    assert ek.fit_workspace_bytes(narrow, 4177920) > 0                # 257 * n * 2 just under 2^31
+    assert ek.fit_workspace_bytes(narrow, 4177920 + 128) == 0
+    assert ek.fit_workspace_bytes(narrow, 1 << 23) == 0
+    assert code(ek.fit_linear, narrow, FAKE, FAKE, 1 << 23, FAKE, big, stream=0) == ek.ERR_UNSUPPORTED
+
+
+def test_decode_path_query(lib):
+    sh = lambda *a, **k: ek.make_shape(*a, **k)
+    assert ek.decode_path(sh(32, 32, 128, 2048, "bf16")) == ek.PATH_FUSED
+    assert ek.decode_path(sh(32, 8, 128, 512, "bf16")) == ek.PATH_FUSED             # G = 4
+    assert ek.decode_path(sh(64, 8, 128, 512, "bf16")) == ek.PATH_FUSED             # G = 8: the limit
+    assert ek.decode_path(sh(128, 8, 128, 512, "bf16")) == ek.PATH_UNFUSED          # G = 16: 16 pairs > 8
+    assert ek.decode_path(sh(64, 8, 64, 256, "bf16")) == ek.PATH_UNFUSED            # d = 64, G = 8: 16 pairs
+    assert ek.decode_path(sh(32, 8, 64, 256, "bf16")) == ek.PATH_FUSED              # d = 64, G = 4: 8 pairs
+    assert ek.decode_path(sh(8, 8, 64, 256, "f32")) == ek.PATH_FUSED
+    assert ek.decode_path(sh(8, 8, 64, 512, "f32")) == ek.PATH_RETAINED_ONLY
+    assert ek.decode_path(sh(32, 32, 128, 2048, "bf16", flags=ek.FLAG_UNFUSED)) == ek.PATH_UNFUSED
+    assert ek.decode_path(sh(32, 32, 128, 2048, "bf16", flags=ek.FLAG_W_PACKED)) == ek.PATH_FUSED_DIRECT
+    assert ek.decode_path(sh(32, 32, 128, 2048, "bf16", flags=ek.FLAG_W_PACKED | ek.FLAG_STAGED)) == ek.PATH_FUSED
+    assert ek.decode_path(sh(32, 32, 128, 2048, "bf16", flags=ek.FLAG_ABSORBED)) == ek.PATH_ABSORBED
+    assert ek.decode_path(sh(32, 32, 128, 2048, "bf16", flags=ek.FLAG_ABSORB_V)) == ek.PATH_ABSORB_V
+    assert code(ek.decode_path, sh(128, 8, 128, 512, "bf16", flags=ek.FLAG_W_PACKED)) == ek.ERR_UNSUPPORTED
+    assert code(ek.decode_path, sh(8, 8, 64, 256, "f32", flags=ek.FLAG_ABSORBED)) == ek.ERR_UNSUPPORTED
+    assert code(ek.decode_path, sh(8, 8, 96, 256, "bf16")) == ek.ERR_UNSUPPORTED
+    # the workspace query already covers the materialising path such a layer takes
+    big, small = sh(128, 8, 128, 512, "bf16"), sh(64, 8, 128, 512, "bf16", flags=ek.FLAG_UNFUSED)
+    assert ek.workspace_bytes(big, 2, 5000) >= ek.workspace_bytes(small, 2, 5000) > 5000 * 512 * 2 * 2
+
+
+def test_compress_in_place_argument_rules(lib):
+    sh = ek.make_shape(8, 8, 64, 256, "bf16")
+    full = ek.LayerCache(FAKE, FAKE, 512, 512, [0, 256], [0, 0], [256, 256])     # no valid rows: nothing launched
+    same = ek.LayerCache(FAKE, FAKE, 256, 512, [0, 256], [0, 0], [256, 256])
+    assert code(ek.cache_compress, sh, full, same, stream=0) == ek.OK
+    moved = ek.LayerCache(FAKE, FAKE, 256, 1024, [0, 512], [0, 0], [256, 256])
+    assert code(ek.cache_compress, sh, full, moved, stream=0) == ek.ERR_UNSUPPORTED   # in place keeps the row indices
+    inside = ek.LayerCache(FAKE + 4096, FAKE + 4096, 256, 512, [0, 256], [0, 0], [256, 256])
+    assert code(ek.cache_compress, sh, full, inside, stream=0) == ek.ERR_UNSUPPORTED  # partial overlap
+    crossed = ek.LayerCache(FAKE, FAKE + (1 << 30), 256, 512, [0, 256], [0, 0], [256, 256])
+    assert code(ek.cache_compress, sh, full, crossed, stream=0) == ek.ERR_UNSUPPORTED
 
 
 def test_every_status_check_in_the_binding_is_well_formed():

@@ -397,6 +397,85 @@ def test_switch_from_full_cache_to_compressed_cache():
     assert e.value.code == ek.ERR_CAPACITY
 
 
+@pytest.mark.parametrize("m,lens", [(512, (333, 70, 1)), (256, (2500,)), (960, (700, 129)), (64, (1200, 5)),
+                                    (0, (100,)), (1024, (100, 30))])
+def test_switch_in_place_then_decode(m, lens):
+    """The same transition with no second buffer (the moment it is needed there is no memory for
+    one): the pool [rows, D] is narrowed to [rows, m] where it lies.  The result must be the
+    oracle's compressed cache bit for bit, and decoding from it must match the oracle."""
+    from oracle import echokv_oracle as orc
+    w = synth.Workload(f"switch_inplace_m{m}", "bf16", 8, 8, 128, m, seed=43, seq_lens=lens)
+    inp = synth.generate(w)
+    dev = torch.device("cuda:0")
+    g = torch.Generator().manual_seed(2)
+    pool = inp.pool_tokens
+    full_k = torch.randn(pool, w.D, generator=g).to(torch.bfloat16)
+    full_v = torch.randn(pool, w.D, generator=g).to(torch.bfloat16)
+    full_k[:, :m] = inp.K_r; full_v[:, :m] = inp.V_r
+    fk, fv = full_k.to(dev), full_v.to(dev)
+    shape = ek.make_shape(w.n_q_heads, w.n_kv_heads, w.head_dim, m, "bf16")
+    full = ek.LayerCache(fk, fv, w.D, pool, inp.seq_start, inp.seq_len, inp.seq_cap)
+    # the same memory seen as [pool, m]
+    ck = fk.view(-1)[:pool * m].view(pool, m) if m else None
+    cv = fv.view(-1)[:pool * m].view(pool, m) if m else None
+    if m:
+        assert ck.data_ptr() == fk.data_ptr()
+    dst = ek.LayerCache(ck if m else None, cv if m else None, m, pool, inp.seq_start, [0] * len(lens), inp.seq_cap)
+    if m == 0:
+        dst.k = dst.v = None
+    ek.cache_compress(shape, full, dst); torch.cuda.synchronize()
+    assert list(dst.seq_len) == inp.seq_len
+    for b in range(inp.n_decode):
+        want_k = orc.cache_compress(ref.f64(full_k[inp.rows(b)]), m)
+        want_v = orc.cache_compress(ref.f64(full_v[inp.rows(b)]), m)
+        if m:
+            assert np.array_equal(host(ck[inp.rows(b)]), want_k)
+            assert np.array_equal(host(cv[inp.rows(b)]), want_v)
+    # decode from the narrowed pool
+    dw = DeviceWorkload(inp)
+    if m:
+        dw.target = ek.LayerCache(ck, cv, m, pool, inp.seq_start, inp.seq_len, inp.seq_cap)
+    out, _ = dw.decode(); torch.cuda.synchronize()
+    o_ref, _ = ref.decode_ref(inp)
+    check(host(out), o_ref, "bf16", f"decode after in-place switch, m={m}")
+
+
+def test_switch_in_place_long_pool():
+    """Enough rows for the plain-copy phase (row ranges whose destination ends below their source)
+    to take over from the ordered single-workgroup phase, at a ratio close to 1 and at 1/2."""
+    from oracle import echokv_oracle as orc
+    dev = torch.device("cuda:0")
+    for H, d, m, rows in ((8, 128, 960, 9000), (8, 128, 512, 70000), (4, 64, 64, 3000)):
+        D = H * d
+        g = torch.Generator().manual_seed(rows)
+        full_k = torch.randn(rows, D, generator=g).to(torch.bfloat16)
+        full_v = torch.randn(rows, D, generator=g).to(torch.bfloat16)
+        fk, fv = full_k.to(dev), full_v.to(dev)
+        shape = ek.make_shape(H, H, d, m, "bf16")
+        starts, lens, caps = [0, rows // 2], [rows // 2 - 7, rows - rows // 2], [rows // 2, rows - rows // 2]
+        full = ek.LayerCache(fk, fv, D, rows, starts, lens, caps)
+        ck = fk.view(-1)[:rows * m].view(rows, m); cv = fv.view(-1)[:rows * m].view(rows, m)
+        dst = ek.LayerCache(ck, cv, m, rows, starts, [0, 0], caps)
+        ek.cache_compress(shape, full, dst); torch.cuda.synchronize()
+        for b in range(2):
+            r = slice(starts[b], starts[b] + lens[b])
+            assert np.array_equal(host(ck[r]), orc.cache_compress(ref.f64(full_k[r]), m)), (m, rows, b)
+            assert np.array_equal(host(cv[r]), orc.cache_compress(ref.f64(full_v[r]), m)), (m, rows, b)
+
+
+@pytest.mark.parametrize("H_q,H_kv,d,m", [(64, 4, 128, 256), (32, 4, 64, 128)])
+def test_decode_more_query_heads_per_kv_head_than_the_fused_kernel_holds(H_q, H_kv, d, m):
+    """(128 / d) * G > 8: the library serves the layer on the materialising path and says so."""
+    w = synth.Workload(f"g{H_q // H_kv}_d{d}", "bf16", H_q, H_kv, d, m, seed=88, seq_lens=(700, 129))
+    inp = synth.generate(w)
+    dw = DeviceWorkload(inp)
+    assert ek.decode_path(dw.shape) == ek.PATH_UNFUSED
+    out, lse = dw.decode(); torch.cuda.synchronize()
+    o_ref, l_ref = ref.decode_ref(inp)
+    check(host(out), o_ref, "bf16", f"{w.name} decode on the materialising path")
+    assert np.abs(host(lse) - l_ref).max() <= 2e-2
+
+
 # ---- the paper's own (S, m) presets on its models' KV layout (8 KV heads x 128) ----------
 # Appendix "Compression-Ratio Configurations": m = 384 (ratio 0.7), m = 0 (0.5), m = 64 (0.3;
 # the retained prefix ends in the middle of head 0).  S only says how many target layers
