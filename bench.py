@@ -31,22 +31,23 @@ PEAK_FP32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
 
-def kernel_source_sha():
-    """Identifies the kernel sources a counter summary under profiles/ was taken with."""
+def kernel_source_sha(names=None):
+    """Identifies the kernel sources a counter summary under profiles/ was taken with: a hash over
+    the named files of csrc/ (all of them if none are named)."""
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2603_22910_amd", "csrc")
-    for name in sorted(os.listdir(csrc)):
-        if name.endswith((".h", ".hip")):
-            h.update(name.encode())
-            h.update(open(os.path.join(csrc, name), "rb").read())
+    for name in sorted(names or [n for n in os.listdir(csrc) if n.endswith((".h", ".hip"))]):
+        h.update(name.encode())
+        h.update(open(os.path.join(csrc, name), "rb").read())
     return h.hexdigest()[:16]
 
 
 def read_traffic(workload_name):
     """L2-miss bytes (HBM or Infinity Cache) per launch of the dominant kernel from the committed
     rocprofv3 counter summary (profiles/traffic_<workload>.txt, `key = value` lines).
-    Returns (bytes or None, note).  A summary taken with other kernel sources than the ones in
-    the tree is reported as stale: its figure is kept out of `traffic`."""
+    Returns (bytes or None, note).  The summary names the source files of the kernel it measured
+    (`kernel_sources`) and their hash (`kernel_source_sha`); if the files in the tree hash
+    differently the summary is reported as stale and its figure is kept out of `traffic`."""
     path = os.path.join(ROOT, "profiles", f"traffic_{workload_name}.txt")
     if not os.path.exists(path):
         return None, "no counter summary committed for this workload"
@@ -59,9 +60,14 @@ def read_traffic(workload_name):
         traffic = float(vals["hbm_bytes_per_launch"])
     except (KeyError, ValueError):
         return None, "counter summary has no hbm_bytes_per_launch"
+    names = vals.get("kernel_sources", "").split() or None
+    try:
+        now = kernel_source_sha(names)
+    except OSError:
+        now = "unreadable"
     sha = vals.get("kernel_source_sha")
-    if sha != kernel_source_sha():
-        return None, (f"stale: summary taken with kernel sources {sha}, tree has {kernel_source_sha()} "
+    if sha != now:
+        return None, (f"stale: summary taken with kernel sources {sha}, tree has {now} "
                       f"(stored figure {traffic:.4g} B)")
     return traffic, f"profiles/{os.path.basename(path)} at commit {vals.get('commit', '?')}"
 

@@ -232,8 +232,8 @@ int echokv_decode_attn_static(const echokv_shape *shape, const echokv_layer_cach
  * already rotated to its own position.  The tables are the caller's:
  *   rope_cos, rope_sin : device [rope_positions, d/2] fp32; rope_positions >= every seq_len.
  *
- * Uncompressed window (Sec. "Experimental Setup": 4 sink tokens and a local
- * window of 128 tokens stay uncompressed).  With win_k / win_v set, the first
+ * Uncompressed window (Sec. "Experimental Setting", paragraph "Implement details":
+ * the paper exempts the first 4 and the most recent 128 tokens from compression).  With win_k / win_v set, the first
  * n_sink and the latest n_recent positions of every sequence take their keys
  * and values from these full-width rows of the TARGET layer instead of the
  * compressed cache; all other positions are rebuilt as usual.

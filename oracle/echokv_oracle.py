@@ -26,7 +26,8 @@ Readings taken where the paper is silent (each also listed in the design notes):
     cache holds keys from before the rotary embedding (Sec. "Network
     Architecture"), so the embedding is applied to the rebuilt keys, by token
     position, just before Eq. 7; and the first 4 / latest 128 tokens of the
-    target layer are kept uncompressed (Sec. "Experimental Setup").  The
+    target layer are kept uncompressed (Sec. "Experimental Setting", paragraph
+    "Implement details").  The
     pairing of rotated features (i with i + d/2) and the ring placement of the
     latest tokens are this build's readings: the paper fixes neither;
   * the one-hidden-layer predictor of Appendix "Prediction Network Architecture"
@@ -281,8 +282,9 @@ def brute_force_decode(q, K_a, V_a, K_r, V_r, W_K, W_V, n_kv_heads: int,
 # --------------------------------------------------------------------------
 # paper-faithful decode: rotary embedding after reconstruction, and a window
 # of uncompressed tokens (Sec. "Network Architecture": predictor inputs are
-# the keys BEFORE the rotary embedding; Sec. "Experimental Setup": 4 sink
-# tokens and a local window of 128 tokens stay at full precision)
+# the keys BEFORE the rotary embedding; Sec. "Experimental Setting", paragraph
+# "Implement details": the first 4 tokens and the most recent 128 tokens of a
+# sequence are exempt from compression)
 # --------------------------------------------------------------------------
 def rope_rotate(X: np.ndarray, positions: Sequence[int], cos: np.ndarray, sin: np.ndarray,
                 n_heads: int) -> np.ndarray:

@@ -1,4 +1,4 @@
-"""Build libechokv.so (HIP, gfx950) and the C oracle helpers, in-tree."""
+"""Build libechokv.so (HIP, gfx950) in-tree.  (The oracle is NumPy: there is no C to compile for it.)"""
 from __future__ import annotations
 
 import os

@@ -37,7 +37,7 @@ __global__ __launch_bounds__(256) void append_rows_kernel(CopyArgs a, SeqMeta me
 
 // ---------------------------------------------------------------------------
 // Uncompressed window of the target layer (the first n_sink positions and a
-// ring of the n_recent latest, Sec. "Experimental Setup"): position p lives in
+// ring of the n_recent latest, Sec. "Experimental Setting", paragraph "Implement details"): position p lives in
 // row p (p < n_sink) or n_sink + (p - n_sink) % n_recent.
 // ---------------------------------------------------------------------------
 struct Window {
