@@ -79,4 +79,25 @@ __device__ __forceinline__ float wave_sum(float v, int width) {
   return v;
 }
 
+// Sum over aligned groups of W consecutive lanes (every lane gets its group's total).  The steps
+// inside a row of 16 lanes are data-parallel-primitive moves folded into the add (no trip through
+// the LDS crossbar, which is what a generic lane shuffle costs): swap neighbours, swap pairs,
+// mirror inside 8 lanes, mirror inside 16 lanes -- after each step both halves of the next larger
+// group hold their own total, so a mirror pairs them as well as a rotation would.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+template <int W>
+__device__ __forceinline__ float row_sum(float v) {
+  static_assert(W == 1 || W == 2 || W == 4 || W == 8 || W == 16 || W == 32 || W == 64, "power of two");
+  if constexpr (W >= 2) v += dpp_move<0xB1>(v);      // quad_perm [1, 0, 3, 2]
+  if constexpr (W >= 4) v += dpp_move<0x4E>(v);      // quad_perm [2, 3, 0, 1]
+  if constexpr (W >= 8) v += dpp_move<0x141>(v);     // row_half_mirror
+  if constexpr (W >= 16) v += dpp_move<0x140>(v);    // row_mirror
+  if constexpr (W >= 32) v += __shfl_xor(v, 16, 64);
+  if constexpr (W >= 64) v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
 }  // namespace echokv

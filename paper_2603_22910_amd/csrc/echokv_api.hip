@@ -278,7 +278,14 @@ int merge_launch(const Dims& dm, const float* po, const float* pml, void* out, f
   ma.H_q = dm.H_q; ma.G = dm.G; ma.d = dm.d;
   ma.n_stream_kv_heads = n_stream; ma.stream_step = stream_step; ma.fused_step = fused_step;
   ma.out_seq0 = out_seq0; ma.win_slot0 = win_slot0;
-  hipLaunchKernelGGL((merge_kernel<TO>), dim3(dm.H_q, mt.n), dim3(256), 0, st, ma, mt);
+  // few (sequence, head) pairs with many partials each: four workgroups of 1024 threads per pair,
+  // 32 head dims each (the merge is bound by the latency of its reads: more of them in flight)
+  int max_slots = 0;
+  for (int b = 0; b < mt.n; ++b) max_slots = std::max(max_slots, mt.sbase[b + 1] - mt.sbase[b]);
+  if (dm.H_q * mt.n <= 256 && max_slots >= 256)
+    hipLaunchKernelGGL((merge_kernel<TO, 4, 1024>), dim3(dm.H_q, mt.n, (dm.d + 31) / 32), dim3(1024), 0, st, ma, mt);
+  else
+    hipLaunchKernelGGL((merge_kernel<TO, 1, 256>), dim3(dm.H_q, mt.n, 1), dim3(256), 0, st, ma, mt);
   LAUNCH_CHECK();
   return ECHOKV_OK;
 }

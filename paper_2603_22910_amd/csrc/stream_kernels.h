@@ -387,24 +387,36 @@ __global__ __launch_bounds__(256) void attn_split_kernel(AttnArgs<T> a, SeqMeta 
         }
       }
     }
+    // scores of the round's UN rows, then ONE change of the softmax reference per query head and
+    // round (one correction factor instead of one per row)
 #pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      const bool live = (j + u * NRG) < jend && pos[u] >= 0;
+    for (int g = 0; g < GT; ++g) {
+      float sc[UN];
+      float mn = mx[g];
 #pragma unroll
-      for (int g = 0; g < GT; ++g) {
-        float s = 0.f;
+      for (int u = 0; u < UN; ++u) {
+        const bool live = (j + u * NRG) < jend && pos[u] >= 0;
+        float t = 0.f;
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) s = fmaf(qv[g][i], kv[u][i], s);
-        s = wave_sum(s, LPR);
-        if (live) {
-          const float mn = fmaxf(mx[g], s);
-          const float corr = __expf(mx[g] - mn);
-          const float p = __expf(s - mn);
-          sm[g] = sm[g] * corr + p;
+        for (int i = 0; i < VEC; ++i) t = fmaf(qv[g][i], kv[u][i], t);
+        t = row_sum<LPR>(t);
+        sc[u] = live ? t : -INFINITY;
+        mn = fmaxf(mn, sc[u]);
+      }
+      if (mn != -INFINITY) {                       // (uniform over the lanes of a row)
+        const float corr = __expf(mx[g] - mn);     // mx = -inf at the start: 0, and o, sm are 0
+        float p[UN];
 #pragma unroll
-          for (int i = 0; i < VEC; ++i) o[g][i] = fmaf(p, vv[u][i], o[g][i] * corr);
-          mx[g] = mn;
+        for (int u = 0; u < UN; ++u) p[u] = __expf(sc[u] - mn);     // a dead row: exp(-inf) = 0
+        sm[g] = sm[g] * corr + ((p[0] + p[1]) + (p[2] + p[3]));
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) {
+          float t = o[g][i] * corr;
+#pragma unroll
+          for (int u = 0; u < UN; ++u) t = fmaf(p[u], vv[u][i], t);
+          o[g][i] = t;
         }
+        mx[g] = mn;
       }
     }
   }
@@ -512,7 +524,7 @@ __global__ __launch_bounds__(256) void row_scores_kernel(AttnArgs<T> a, float* s
         float sc = 0.f;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) sc = fmaf(qv[g][i], kv[u][i], sc);
-        sc = wave_sum(sc, LPR);
+        sc = row_sum<LPR>(sc);
         if (li == 0 && jj < jend) dst[(int64_t)g * s_ld + jj] = sc;
       }
     }
@@ -523,7 +535,10 @@ __global__ __launch_bounds__(256) void row_scores_kernel(AttnArgs<T> a, float* s
 // Merge of the split partials of one (sequence, query head): exact
 // re-association of the softmax-weighted sum.  Heads below `n_stream_heads`
 // (in KV-head units) were written every `stream_step` slots, the others every
-// `fused_step` slots.  grid = (H_q, nseq), 256 threads.
+// `fused_step` slots.  grid = (H_q, nseq, DS), 256 threads.  DS = 1: a workgroup covers all d
+// head dims (4 per thread); DS = 4: a quarter of them (1 per thread), for launches with few
+// (sequence, head) pairs and long sequences, where 4 x as many workgroups share the reading.
+// Each dim's sum runs over the partials in the same order either way: same bits.
 // ---------------------------------------------------------------------------
 template <typename TO>
 struct MergeArgs {
@@ -535,9 +550,12 @@ struct MergeArgs {
   int32_t win_slot0 = -1;   // >= 0: one more partial per sequence (its window tokens) at slot win_slot0 + b
 };
 
-template <typename TO>
-__global__ __launch_bounds__(256) void merge_kernel(MergeArgs<TO> a, SeqMeta meta) {
+template <typename TO, int DS, int NT>       // NT threads: 256, or 1024 where sequences are long
+__global__ __launch_bounds__(NT) void merge_kernel(MergeArgs<TO> a, SeqMeta meta) {
+  constexpr int EPT = DS == 1 ? 4 : 1;          // head dims per thread
+  constexpr int NW = NT / 64, NG = NT / 32;      // waves, groups of 32 threads
   const int h = blockIdx.x, b = blockIdx.y;
+  const int dim0 = blockIdx.z * 32;              // DS == 4: this workgroup's 32 dims
   const int step = (h / a.G < a.n_stream_kv_heads) ? a.stream_step : a.fused_step;
   const int nreg = (meta.sbase[b + 1] - meta.sbase[b] + step - 1) / step;   // regular partials of this head
   const int n = nreg + (a.win_slot0 >= 0 ? 1 : 0);
@@ -548,25 +566,33 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs<TO> a, SeqMeta met
     const int64_t slot = i < nreg ? slot0 + (int64_t)i * step : (int64_t)a.win_slot0 + b;
     return slot * a.H_q + h;
   };
-  __shared__ float s_red[4];
-  __shared__ float s_w[256];
-  __shared__ float s_acc[8][128];
+  __shared__ float s_red[NW];
+  __shared__ float s_w[NT];
+  __shared__ float s_acc[NG][128];
+  auto block_reduce = [&](float v, bool is_max) -> float {    // fixed order: same bits every run
+    v = is_max ? wave_max(v, 64) : wave_sum(v, 64);
+    __syncthreads();                // s_red may still be read from the previous reduction
+    if (lane == 0) s_red[wave] = v;
+    __syncthreads();
+    float r = s_red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) r = is_max ? fmaxf(r, s_red[w]) : r + s_red[w];
+    return r;
+  };
   // 1. global max of the partial maxima (a partial that covers no token has -inf and weight 0;
   //    at least one partial of every sequence covers a token)
   float M = -INFINITY;
-  for (int i = tid; i < n; i += 256) M = fmaxf(M, a.part_ml[ph_of(i) * 2]);
-  M = wave_max(M, 64);
-  if (lane == 0) s_red[wave] = M;
-  __syncthreads();
-  M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-  // 2. weighted sums, 256 partials at a time: weights exp(m_s - M) go to LDS, then
-  //    8 groups of 32 threads (4 head dims each) add up the weighted o rows with
-  //    independent, coalesced loads
-  const int grp = tid >> 5, q4 = (tid & 31) * 4;
+  for (int i = tid; i < n; i += NT) M = fmaxf(M, a.part_ml[ph_of(i) * 2]);
+  M = block_reduce(M, true);
+  // 2. weighted sums, NT partials at a time: weights exp(m_s - M) go to LDS, then the groups of
+  //    32 threads add up the weighted o rows with independent, coalesced loads
+  const int grp = tid >> 5, q4 = DS == 1 ? (tid & 31) * 4 : dim0 + (tid & 31);
   const bool dim_ok = q4 < a.d;
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float acc[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) acc[e] = 0.f;
   float lsum = 0.f;
-  for (int c0 = 0; c0 < n; c0 += 256) {
+  for (int c0 = 0; c0 < n; c0 += NT) {
     const int i = c0 + tid;
     float w = 0.f;
     if (i < n) {
@@ -577,32 +603,49 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs<TO> a, SeqMeta met
     __syncthreads();            // previous chunk's weights are no longer read
     s_w[tid] = w;
     __syncthreads();
-    const int cn = min(256, n - c0);
+    const int cn = min(NT, n - c0);
     if (dim_ok) {
-#pragma unroll 4
-      for (int j = grp; j < cn; j += 8) {
-        const float4 o = *reinterpret_cast<const float4*>(a.part_o + ph_of(c0 + j) * a.d + q4);
-        const float wj = s_w[j];
-        acc.x = fmaf(wj, o.x, acc.x); acc.y = fmaf(wj, o.y, acc.y);
-        acc.z = fmaf(wj, o.z, acc.z); acc.w = fmaf(wj, o.w, acc.w);
+      // 16 partial rows per round, all loads issued before the first is used (the loop is bound
+      // by memory latency, not by volume); rows past the end repeat the last one with weight 0
+      constexpr int NB = 16;
+      for (int j0 = grp; j0 < cn; j0 += NG * NB) {
+        float ov[NB][EPT], wv[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+          const int j = j0 + NG * u;
+          const float* src = a.part_o + ph_of(c0 + min(j, cn - 1)) * a.d + q4;
+          if constexpr (DS == 1) {
+            const float4 o = *reinterpret_cast<const float4*>(src);
+            ov[u][0] = o.x; ov[u][1] = o.y; ov[u][2] = o.z; ov[u][3] = o.w;
+          } else {
+            ov[u][0] = *src;
+          }
+          wv[u] = j < cn ? s_w[min(j, NT - 1)] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u)
+#pragma unroll
+          for (int e = 0; e < EPT; ++e) acc[e] = fmaf(wv[u], ov[u][e], acc[e]);
       }
     }
   }
-  lsum = wave_sum(lsum, 64);
+  const float ll = block_reduce(lsum, false);
+  if (dim_ok) {
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) s_acc[grp][(DS == 1 ? q4 : (tid & 31)) + e] = acc[e];
+  }
   __syncthreads();
-  if (lane == 0) s_red[wave] = lsum;
-  if (dim_ok) *reinterpret_cast<float4*>(&s_acc[grp][q4]) = acc;
-  __syncthreads();
-  if (tid < a.d) {
-    const float ll = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+  const int nd = DS == 1 ? a.d : min(32, a.d - dim0);
+  if (tid < nd) {
     float r = 0.f;
 #pragma unroll
-    for (int g = 0; g < 8; ++g) r += s_acc[g][tid];
+    for (int g = 0; g < NG; ++g) r += s_acc[g][tid];
     r /= ll;
     const int64_t oh = (a.out_seq0 + b) * a.H_q + h;
-    if constexpr (sizeof(TO) == 2) a.out[oh * a.d + tid] = f32_to_bf16(r);
-    else a.out[oh * a.d + tid] = r;
-    if (tid == 0 && a.lse) a.lse[oh] = M + __logf(ll);
+    const int dim = DS == 1 ? tid : dim0 + tid;
+    if constexpr (sizeof(TO) == 2) a.out[oh * a.d + dim] = f32_to_bf16(r);
+    else a.out[oh * a.d + dim] = r;
+    if (dim == 0 && a.lse) a.lse[oh] = M + __logf(ll);
   }
 }
 
