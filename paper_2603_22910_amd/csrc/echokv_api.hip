@@ -262,10 +262,14 @@ int launch_recon_fma(const Dims& dm, GemmArgs<T> g, SeqMeta& mt, hipStream_t st)
   return ECHOKV_OK;
 }
 
+#ifndef ECHOKV_MIN_STREAM_BLOCKS
+#define ECHOKV_MIN_STREAM_BLOCKS 2048
+#endif
+constexpr int kMinStreamBlocks = ECHOKV_MIN_STREAM_BLOCKS;
 int pick_split_tokens(int64_t total_tokens, int n_heads_blocks) {
   // enough chunks to fill 256 CUs a few times over, but few partials
   int st = 2048;
-  while (st > kSlotTokens && (total_tokens / st) * n_heads_blocks < 2048) st >>= 1;
+  while (st > kSlotTokens && (total_tokens / st) * n_heads_blocks < kMinStreamBlocks) st >>= 1;
   return st;
 }
 

@@ -62,9 +62,12 @@ __global__ __launch_bounds__(NTHREADS, 2) void prefill_attn_kernel(Args a) {
   __shared__ __attribute__((aligned(16))) char sv[2][C::VTILE_BYTES];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, lh = lane >> 5;
-  const int h = blockIdx.y;
+  // grid = (heads, query blocks): workgroups are handed out x first, so every head's longest
+  // (latest) query block starts before any shorter one -- a causal chunk's work per block grows
+  // linearly, and with the heads outermost the last head's longest blocks would start last
+  const int h = blockIdx.x;
   const int nqb = (a.T_q + BQ - 1) / BQ;
-  const int qb = nqb - 1 - blockIdx.x;            // longest (latest) query blocks first
+  const int qb = nqb - 1 - blockIdx.y;
   const int i0 = qb * BQ;
   const int Ltot = a.q_pos0 + a.T_q;
   const int kvh = h / a.G;
@@ -370,9 +373,12 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   const int lr = lane & 31, lh = lane >> 5;
-  const int h = blockIdx.y;
-  const int nqb = (a.T_q + BQ - 1) / BQ;
-  const int i0 = (nqb - 1 - blockIdx.x) * BQ;     // longest (latest) query blocks first
+  const int h = blockIdx.x;                       // grid = (heads, query blocks), longest blocks of all heads first
+  // Query blocks are counted from the END of the chunk: block y covers queries
+  // [T_q - (y + 1) BQ, T_q - y BQ).  If T_q is not a multiple of BQ the block that is only partly
+  // filled is then the first (shortest, cheapest) one and not the last (longest) one; its queries
+  // below 0 repeat query 0 and are not written back.
+  const int i0 = a.T_q - ((int)blockIdx.y + 1) * BQ;
   const int Ltot = a.q_pos0 + a.T_q;
   const int kvh = h / a.G;
   const bf16_t* kbase; const bf16_t* vbase; uint32_t ld2;
@@ -388,8 +394,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
 
   // ---- this lane's query (clamped; clamped duplicates are not written back)
   const int qi = i0 + wave_u * 32 + lr;
-  const int qic = min(qi, a.T_q - 1);
-  const int qpos = a.q_pos0 + qic;
+  const int qic = max(qi, 0);                     // (qi < T_q always: blocks end at T_q - y BQ)
   bf16x8_t qf[C::KSTEPS];
   {
     const bf16_t* qp = a.q + ((int64_t)qic * a.H_q + h) * HD + lh * 8;
@@ -406,9 +411,9 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
     for (int r = 0; r < 16; ++r) oacc[cb][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
   const float scale2 = a.scale * 1.44269504088896340736f;    // softmax in base 2
-  const int qpos_min = a.q_pos0 + min(i0 + wave_u * 32, a.T_q - 1);
-  const int qpos_max = a.q_pos0 + min(i0 + wave_u * 32 + 31, a.T_q - 1);
-  const int kv_end = min(Ltot, a.q_pos0 + min(i0 + BQ, a.T_q));   // keys any query of the block sees
+  const int qpos_min = a.q_pos0 + max(i0 + wave_u * 32, 0);
+  const int qpos_max = a.q_pos0 + max(i0 + wave_u * 32 + 31, 0);
+  const int kv_end = min(Ltot, a.q_pos0 + i0 + BQ);   // keys any query of the block sees (i0 + BQ <= T_q)
   const int ntiles = (kv_end + BKV - 1) / BKV;
 
   // ---- fragment addresses inside a stage
@@ -455,7 +460,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
     // ---- online softmax, lane-local (keys: mb*32 + 8*(r/4) + 4*lh + r%4), base 2, scale folded in
     if (kv0 + BKV - 1 > qpos_min) {   // rare (diagonal tiles): the lane's query position is worked out afresh
       const int ln = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-      const int qp = a.q_pos0 + min(i0 + wave_u * 32 + (ln & 31), a.T_q - 1);
+      const int qp = a.q_pos0 + max(i0 + wave_u * 32 + (ln & 31), 0);
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -524,7 +529,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
   const int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
   const int lh_e = lane_e >> 5;
   const int qi_e = i0 + wave_u * 32 + (lane_e & 31);
-  if (qi_e >= a.T_q) return;
+  if (qi_e < 0) return;
   const float inv = 1.0f / l_tot;
   const int64_t ob = ((int64_t)qi_e * a.H_q + h) * HD;
 #pragma unroll
@@ -642,10 +647,10 @@ inline int launch_prefill_mfma(int H_q, int H_kv, int d, int m, int d_out, int n
     // long chunks take the twelve-wave kernel with the LDS ring (its 32-bit row offsets must fit)
     const int64_t span = (int64_t)(q_pos0 + T_q) * (m > d_out ? m : d_out) * 2;
     if (T_q >= prefill::dma::kMinQueries && span < (int64_t)1 << 31) {
-      const dim3 grid((T_q + prefill::dma::BQ - 1) / prefill::dma::BQ, H_q), blk(prefill::dma::NTHREADS);
+      const dim3 grid(H_q, (T_q + prefill::dma::BQ - 1) / prefill::dma::BQ), blk(prefill::dma::NTHREADS);
       return d == 128 ? prefill::dma::launch<128>(grid, blk, st, a) : prefill::dma::launch<64>(grid, blk, st, a);
     }
-    dim3 grid((T_q + prefill::BQ - 1) / prefill::BQ, H_q);
+    dim3 grid(H_q, (T_q + prefill::BQ - 1) / prefill::BQ);
     if (d == 128) hipLaunchKernelGGL((prefill::prefill_attn_kernel<128>), grid, dim3(prefill::NTHREADS), 0, st, a);
     else hipLaunchKernelGGL((prefill::prefill_attn_kernel<64>), grid, dim3(prefill::NTHREADS), 0, st, a);
     if (hipGetLastError() != hipSuccess) return 7;
