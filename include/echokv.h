@@ -161,8 +161,14 @@ int echokv_pack_weights(const echokv_shape *shape, const void *w, void *w_packed
                         void *hip_stream);
 
 /* Bytes of workspace that echokv_decode_attn (batch sequences holding
- * total_tokens cached tokens in all) or echokv_prefill_attn (one sequence with
- * total_tokens cached tokens, max_q queries) need.  Returns 0 on a bad shape. */
+ * total_tokens cached tokens in all) needs and, when max_q >= 1, that
+ * echokv_prefill_attn needs for chunks of up to max_q queries of one sequence
+ * whose visible context (q_pos0 + T_q) is at most total_tokens.  max_q == 0:
+ * decode only.  The prefill part holds the predicted dims of the whole visible
+ * context (2 (D - m) values per token), a rotated copy of the retained keys,
+ * and, for chunks under 1024 queries in front of a long context, the fp32
+ * partial results of the launch split over the keys (at most 8 shares of
+ * d + 2 words per query and head).  Returns 0 on a bad shape. */
 size_t echokv_workspace_bytes(const echokv_shape *shape, int32_t batch,
                               int64_t total_tokens, int32_t max_q);
 

@@ -221,7 +221,7 @@ def _check(rc: int, where: str):
         raise EchoKVError(rc, where)
 
 
-def workspace_bytes(shape: Shape, batch: int, total_tokens: int, max_q: int = 1) -> int:
+def workspace_bytes(shape: Shape, batch: int, total_tokens: int, max_q: int = 0) -> int:
     return int(load().echokv_workspace_bytes(C.byref(shape), batch, total_tokens, max_q))
 
 

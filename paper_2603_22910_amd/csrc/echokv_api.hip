@@ -454,6 +454,10 @@ int64_t prefill_part_slots(const Dims& dm, int64_t Ltot, int max_q) {
   const bool mfma = dm.bf16 && prefill_mfma_supported<bf16_t>(dm.d);
   return mfma ? 0 : (int64_t)std::min(max_q, kPrefillQChunk) * slots_for(Ltot);
 }
+// MFMA prefill path: [plan][rotated copy of the retained keys][partials of a launch split over the keys]
+size_t prefill_split_offset(const Dims& dm, int64_t Ltot, int max_q) {
+  return prefill_krot_offset(dm, Ltot, max_q) + align_up((size_t)Ltot * dm.m * dm.es);
+}
 // Prefill: predicted dims of the whole visible context are rebuilt once into
 // the workspace (every query tile reuses them), then causal attention runs
 // over retained heads (from the cache) and predicted heads (from the workspace).
@@ -513,9 +517,11 @@ int prefill_impl(const Dims& dm, const echokv_layer_cache* an, const echokv_laye
         if (n_ret_heads > 0) k_ret = krot;
       }
     }
+    float* sp_o = (float*)(ws + prefill_split_offset(dm, Ltot, T_q));
+    float* sp_ml = sp_o + (size_t)T_q * dm.H_q * prefill_kv_splits(T_q, Ltot, dm.H_q) * dm.d;
     rcp = launch_prefill_mfma<T>(dm.H_q, dm.H_kv, dm.d, dm.m, dm.d_out_v, dm.g0, dm.scale, dm.out_bf16,
                                  k_ret, (const T*)tg->v + row0 * dm.m,
-                                 kh, vh, (const T*)q, T_q, q_pos0, out, lse, st);
+                                 kh, vh, (const T*)q, T_q, q_pos0, out, lse, st, sp_o, sp_ml);
     if (rcp) return rcp;
     return prof.end();
   }
@@ -835,9 +841,17 @@ size_t decode_ws_bytes(const Dims& dm, int batch, int64_t total_tokens, bool unf
   const int64_t slots = total_tokens / kSlotTokens + 2 * (int64_t)batch;   // + one window partial per sequence
   return plan_ws(dm, slots, unfused ? slots * kSlotTokens : 0).total;
 }
+// MFMA prefill path: [plan][rotated copy of the retained keys][partials of a launch split over the keys]
 size_t prefill_ws_bytes(const Dims& dm, int64_t Ltot, int max_q) {
   const bool mfma = dm.bf16 && prefill_mfma_supported<bf16_t>(dm.d);
-  return prefill_krot_offset(dm, Ltot, max_q) + (mfma ? align_up((size_t)Ltot * dm.m * dm.es) : 0);
+  if (!mfma) return prefill_krot_offset(dm, Ltot, max_q);
+  // the partials of the largest split launch any chunk of up to max_q queries can take: the
+  // number of shares only changes where the number of query blocks does
+  size_t split = 0;
+  // (chunks of kMinQueries queries and more are not split)
+  for (int tq : {std::min(max_q, prefill::dma::kMinQueries - 1), prefill::dma::BQ, 2 * prefill::dma::BQ})
+    if (tq <= max_q) split = std::max(split, prefill_split_floats(tq, Ltot, dm.H_q, dm.d) * 4);
+  return prefill_split_offset(dm, Ltot, max_q) + align_up(split);
 }
 
 }  // namespace
@@ -866,7 +880,7 @@ size_t echokv_workspace_bytes(const echokv_shape* shape, int32_t batch, int64_t 
   size_t need = decode_ws_bytes(dm, batch, total_tokens, true);
   if ((shape->flags & kAbsModes) && absorbed_supported(dm, shape->flags))
     need = std::max(need, absorbed_ws_bytes(dm, batch, total_tokens));
-  if (max_q > 1) need = std::max(need, prefill_ws_bytes(dm, total_tokens, max_q));
+  if (max_q >= 1) need = std::max(need, prefill_ws_bytes(dm, total_tokens, max_q));
   return need;
 }
 

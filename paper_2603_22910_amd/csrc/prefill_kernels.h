@@ -18,6 +18,8 @@
 #include "common.h"
 #include "fused_decode.h"
 
+#include <algorithm>
+
 namespace echokv {
 namespace prefill {
 
@@ -30,6 +32,12 @@ struct Args {
   void* out; float* lse;                      // [T_q, H_q, d], [T_q, H_q]
   int32_t H_q, G, m, d_out, n_ret_heads, T_q, q_pos0, out_bf16;
   float scale;
+  // split over the keys (long-chunk kernel only; kv_splits == 1: off): workgroup z of a (head,
+  // query block) takes one share of the block's key tiles and writes its unnormalised partial
+  // instead of the output; prefill_merge_kernel joins the shares.
+  int32_t kv_splits;
+  float* part_o;                              // [T_q, H_q, kv_splits, d]
+  float* part_ml;                             // [T_q, H_q, kv_splits, 2]: (max in base-2 units, sum)
 };
 
 template <int HD> struct Cfg {
@@ -269,7 +277,8 @@ typedef short short4_t __attribute__((ext_vector_type(4)));
 
 // the first NCOPY waves issue the copies (a tile is 16 or 32 one-KB copies per operand)
 constexpr int NST = 4, NCOPY = 8, NWAVES = 12, NTHREADS = 64 * NWAVES, BQ = 32 * NWAVES;
-constexpr int kMinQueries = 1024;      // shorter chunks keep the four-wave kernel (more workgroups)
+constexpr int kMinQueries = 1024;      // shorter chunks: split over the keys if the context is long, else the four-wave kernel
+constexpr int kMaxSplits = 8;
 
 template <int HD> struct Cfg {
   static constexpr int ROWB = HD * 2;                   // bytes per key row
@@ -307,7 +316,10 @@ template <int HD> struct CopyPlan {
 // Issue this wave's copies of key tile t into ring stage t % NST.  Rows past the last key
 // repeat it: finite values, masked by causality.  (A device function of its own: the copy
 // builtin is not accepted inside a kernel body by the host pass.)
-template <int HD>
+// (TAG: every kernel instantiation uses a specialisation of its own.  The host pass cannot compile
+// the copy builtin; it lets that pass for the first kernel that uses a specialisation and then
+// refuses the same specialisation to a second one.)
+template <int HD, int TAG>
 __device__ __forceinline__ void dma_tile(char* smem, const CopyPlan<HD>& cp, int t) {
   using C = Cfg<HD>;
   static_assert(C::NL == 1 || (C::CH == 16 && C::ROWS_PER_COPY == 4), "swizzle relation between a wave's copies");
@@ -366,7 +378,7 @@ __device__ __forceinline__ void wait_v(VFrag& f) {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(f.lo[0]), "+v"(f.lo[1]), "+v"(f.hi[0]), "+v"(f.hi[1]) : "n"(N));
 }
 
-template <int HD>
+template <int HD, bool SPLIT>
 __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
   using C = Cfg<HD>;
   extern __shared__ __attribute__((aligned(1024))) char smem[];      // NST stages of [K tile | V tile]
@@ -414,7 +426,14 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
   const int qpos_min = a.q_pos0 + max(i0 + wave_u * 32, 0);
   const int qpos_max = a.q_pos0 + max(i0 + wave_u * 32 + 31, 0);
   const int kv_end = min(Ltot, a.q_pos0 + i0 + BQ);   // keys any query of the block sees (i0 + BQ <= T_q)
-  const int ntiles = (kv_end + BKV - 1) / BKV;
+  const int ntiles_blk = (kv_end + BKV - 1) / BKV;
+  // SPLIT: this workgroup's share [t_first, ntiles) of the block's key tiles
+  int t_first = 0, ntiles = ntiles_blk;
+  if constexpr (SPLIT) {
+    const int per = (ntiles_blk + a.kv_splits - 1) / a.kv_splits;
+    t_first = min((int)blockIdx.z * per, ntiles_blk);
+    ntiles = min(ntiles_blk, t_first + per);
+  }
 
   // ---- fragment addresses inside a stage
   // K: row mb*32 + lr, chunk (2 kk + lh) ^ kswz(row)
@@ -433,11 +452,11 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
   // wave only keeps copying and meeting the others) instead of a skip inside one: no values
   // to merge between the paths.
   const int nact = min(ntiles, qpos_max / BKV + 1);
-  dma_tile<HD>(smem, cp, 0); dma_tile<HD>(smem, cp, 1); dma_tile<HD>(smem, cp, 2);
-  int t = 0;
+  dma_tile<HD, SPLIT ? 1 : 0>(smem, cp, t_first); dma_tile<HD, SPLIT ? 1 : 0>(smem, cp, t_first + 1); dma_tile<HD, SPLIT ? 1 : 0>(smem, cp, t_first + 2);
+  int t = t_first;
   for (; t < nact; ++t) {
     wait_loads_and_barrier<2 * 2 * C::NL>();     // tile t has landed for every wave; stage (t-1)%NST is free
-    dma_tile<HD>(smem, cp, t + 3);
+    dma_tile<HD, SPLIT ? 1 : 0>(smem, cp, t + 3);
     const int kv0 = t * BKV;
     const char* sk = smem + (t & (NST - 1)) * C::STAGE;
     const char* sv = sk + C::TILE;
@@ -475,9 +494,13 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[mb][r]);
     mx = max_over_halves(mx);
-    const float m_new = fmaxf(m_run, mx);      // finite from the first tile on (key 0 is visible)
+    // !SPLIT: finite from the first tile on (key 0 is visible to every query).  SPLIT: a share
+    // that starts on the diagonal can leave a query with no visible key yet (-inf): its factor
+    // is 1 and its probabilities are exp2(-inf + 0) = 0
+    const float m_new = fmaxf(m_run, mx);
     if (__any((m_new - m_run) * scale2 > kSlack)) {      // see kSlack
-      const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
+      float corr = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
+      if constexpr (SPLIT) corr = (m_new == -INFINITY) ? 1.f : corr;
       l_run *= corr;
 #pragma unroll
       for (int cb = 0; cb < C::CB; ++cb)
@@ -485,7 +508,8 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
         for (int r = 0; r < 16; ++r) oacc[cb][r] *= corr;
       m_run = m_new;
     }
-    const float mneg = -m_run * scale2;
+    float mneg = -m_run * scale2;
+    if constexpr (SPLIT) mneg = (m_run == -INFINITY) ? 0.f : mneg;
     float lsum = 0.f;
     bf16x8_t pf[4];
 #pragma unroll
@@ -520,7 +544,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
   }
   for (; t < ntiles; ++t) {
     wait_loads_and_barrier<2 * 2 * C::NL>();
-    dma_tile<HD>(smem, cp, t + 3);
+    dma_tile<HD, SPLIT ? 1 : 0>(smem, cp, t + 3);
   }
   wait_loads_and_barrier<0>();         // the ring's last copies have landed before the workgroup ends
   // ---- finish: this lane holds query qi, head dims cb*32 + 8*(r/4) + 4*lh + r%4
@@ -530,6 +554,17 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
   const int lh_e = lane_e >> 5;
   const int qi_e = i0 + wave_u * 32 + (lane_e & 31);
   if (qi_e < 0) return;
+  if constexpr (SPLIT) {        // unnormalised partial of this share: (max, sum, O)
+    const int64_t pr = ((int64_t)qi_e * a.H_q + h) * a.kv_splits + blockIdx.z;
+#pragma unroll
+    for (int cb = 0; cb < C::CB; ++cb)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4)
+        *reinterpret_cast<float4*>(a.part_o + pr * HD + cb * 32 + r4 * 8 + lh_e * 4) =
+            make_float4(oacc[cb][r4 * 4], oacc[cb][r4 * 4 + 1], oacc[cb][r4 * 4 + 2], oacc[cb][r4 * 4 + 3]);
+    if (lh_e == 0) { a.part_ml[pr * 2] = m_run * scale2; a.part_ml[pr * 2 + 1] = l_tot; }
+    return;
+  }
   const float inv = 1.0f / l_tot;
   const int64_t ob = ((int64_t)qi_e * a.H_q + h) * HD;
 #pragma unroll
@@ -552,10 +587,44 @@ __global__ __launch_bounds__(NTHREADS) void prefill_attn_dma_kernel(Args a) {
     a.lse[(int64_t)qi_e * a.H_q + h] = (m_run * scale2 + __log2f(l_tot)) * 0.69314718055994530942f;
 }
 
-template <int HD>
+// Joins the key shares of a split launch: exact re-association of the softmax-weighted sums.
+// One thread per (query, head, 4 head dims).
+template <typename TO>
+__global__ __launch_bounds__(256) void prefill_merge_kernel(Args a, int HD) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int q4 = HD / 4;
+  const int64_t row = idx / q4;                    // query * H_q + head
+  if (row >= (int64_t)a.T_q * a.H_q) return;
+  const int c = (int)(idx % q4) * 4;
+  const float* ml = a.part_ml + row * a.kv_splits * 2;
+  float M = -INFINITY;
+  for (int s = 0; s < a.kv_splits; ++s) M = fmaxf(M, ml[2 * s]);     // share 0 holds key 0: finite
+  float l = 0.f;
+  float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int s = 0; s < a.kv_splits; ++s) {
+    const float ms = ml[2 * s];
+    const float w = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - M);
+    l = fmaf(w, ml[2 * s + 1], l);
+    const float4 v = *reinterpret_cast<const float4*>(a.part_o + (row * a.kv_splits + s) * HD + c);
+    o.x = fmaf(w, v.x, o.x); o.y = fmaf(w, v.y, o.y); o.z = fmaf(w, v.z, o.z); o.w = fmaf(w, v.w, o.w);
+  }
+  const float inv = 1.0f / l;
+  TO* out = reinterpret_cast<TO*>(a.out) + row * HD + c;
+  if constexpr (sizeof(TO) == 2) {
+    uint2 w2;
+    w2.x = (uint32_t)f32_to_bf16(o.x * inv) | ((uint32_t)f32_to_bf16(o.y * inv) << 16);
+    w2.y = (uint32_t)f32_to_bf16(o.z * inv) | ((uint32_t)f32_to_bf16(o.w * inv) << 16);
+    *reinterpret_cast<uint2*>(out) = w2;
+  } else {
+    *reinterpret_cast<float4*>(out) = make_float4(o.x * inv, o.y * inv, o.z * inv, o.w * inv);
+  }
+  if (a.lse && c == 0) a.lse[row] = (M + __log2f(l)) * 0.69314718055994530942f;
+}
+
+template <int HD, bool SPLIT>
 inline int launch(dim3 grid, dim3 blk, hipStream_t st, const Args& a) {
   constexpr int lds = NST * Cfg<HD>::STAGE;          // 128 KB (d = 128) or 64 KB of dynamic LDS
-  void (*fn)(Args) = prefill_attn_dma_kernel<HD>;
+  void (*fn)(Args) = prefill_attn_dma_kernel<HD, SPLIT>;
   static bool allowed[64] = {};                      // per device: the attribute is set once
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 7;
@@ -628,6 +697,24 @@ template <typename T> inline bool prefill_mfma_supported(int d) {
   return sizeof(T) == 2 && (d == 64 || d == 128);
 }
 
+// Key shares for a chunk of T_q queries over Ltot cached tokens (1 = no split).  Chunks of
+// kMinQueries queries and more fill the chip by themselves.  A shorter chunk has at most three query
+// blocks per head; with a long context in front of it each (head, block) is cut into shares of at
+// least 8 key tiles until about three workgroups per compute unit exist.
+inline int prefill_kv_splits(int T_q, int64_t Ltot, int H_q) {
+  if (T_q >= prefill::dma::kMinQueries) return 1;
+  const int wgs = (T_q + prefill::dma::BQ - 1) / prefill::dma::BQ * H_q;
+  const int64_t tiles = (Ltot + prefill::BKV - 1) / prefill::BKV;
+  int S = (int)std::min<int64_t>(prefill::dma::kMaxSplits, tiles / 8);
+  S = std::min(S, (768 + wgs - 1) / wgs);
+  return std::max(S, 1);
+}
+// fp32 words the partials of such a launch take: (d + 2) per (query, head, share)
+inline size_t prefill_split_floats(int T_q, int64_t Ltot, int H_q, int d) {
+  const int S = prefill_kv_splits(T_q, Ltot, H_q);
+  return S > 1 ? (size_t)T_q * H_q * S * (d + 2) : 0;
+}
+
 // k_ret / v_ret: retained cache at the sequence's first row (stride m);
 // k_hat / v_hat: predicted dims of tokens 0 .. q_pos0+T_q-1 (stride d_out).
 template <typename T>
@@ -635,7 +722,7 @@ inline int launch_prefill_mfma(int H_q, int H_kv, int d, int m, int d_out, int n
                                float scale, bool out_bf16,
                                const T* k_ret, const T* v_ret, const T* k_hat, const T* v_hat,
                                const T* q, int T_q, int q_pos0, void* out, float* lse,
-                               hipStream_t st) {
+                               hipStream_t st, float* part_o = nullptr, float* part_ml = nullptr) {
   if constexpr (sizeof(T) != 2) {
     return 6;
   } else {
@@ -644,11 +731,26 @@ inline int launch_prefill_mfma(int H_q, int H_kv, int d, int m, int d_out, int n
     a.out = out; a.lse = lse;
     a.H_q = H_q; a.G = H_q / H_kv; a.m = m; a.d_out = d_out; a.n_ret_heads = n_ret_heads;
     a.T_q = T_q; a.q_pos0 = q_pos0; a.out_bf16 = out_bf16 ? 1 : 0; a.scale = scale;
-    // long chunks take the twelve-wave kernel with the LDS ring (its 32-bit row offsets must fit)
+    a.kv_splits = 1; a.part_o = nullptr; a.part_ml = nullptr;
+    // long chunks take the twelve-wave kernel with the LDS ring (its 32-bit row offsets must fit);
+    // so do short chunks in front of a long context, split over the keys so that the grid still
+    // fills the chip
     const int64_t span = (int64_t)(q_pos0 + T_q) * (m > d_out ? m : d_out) * 2;
+    const int S = span < (int64_t)1 << 31 ? prefill_kv_splits(T_q, q_pos0 + T_q, H_q) : 1;
+    if (S > 1) {
+      if (!part_o || !part_ml) return 5;
+      a.kv_splits = S; a.part_o = part_o; a.part_ml = part_ml;
+      const dim3 grid(H_q, (T_q + prefill::dma::BQ - 1) / prefill::dma::BQ, S), blk(prefill::dma::NTHREADS);
+      int rc = d == 128 ? prefill::dma::launch<128, true>(grid, blk, st, a) : prefill::dma::launch<64, true>(grid, blk, st, a);
+      if (rc) return rc;
+      const unsigned mb = (unsigned)(((int64_t)T_q * H_q * (d / 4) + 255) / 256);
+      if (out_bf16) hipLaunchKernelGGL((prefill::dma::prefill_merge_kernel<bf16_t>), dim3(mb), dim3(256), 0, st, a, d);
+      else hipLaunchKernelGGL((prefill::dma::prefill_merge_kernel<float>), dim3(mb), dim3(256), 0, st, a, d);
+      return hipGetLastError() != hipSuccess ? 7 : 0;
+    }
     if (T_q >= prefill::dma::kMinQueries && span < (int64_t)1 << 31) {
       const dim3 grid(H_q, (T_q + prefill::dma::BQ - 1) / prefill::dma::BQ), blk(prefill::dma::NTHREADS);
-      return d == 128 ? prefill::dma::launch<128>(grid, blk, st, a) : prefill::dma::launch<64>(grid, blk, st, a);
+      return d == 128 ? prefill::dma::launch<128, false>(grid, blk, st, a) : prefill::dma::launch<64, false>(grid, blk, st, a);
     }
     dim3 grid(H_q, (T_q + prefill::BQ - 1) / prefill::BQ);
     if (d == 128) hipLaunchKernelGGL((prefill::prefill_attn_kernel<128>), grid, dim3(prefill::NTHREADS), 0, st, a);

@@ -41,7 +41,7 @@ class DeviceWorkload:
         tdt = {"bf16": torch.bfloat16, "f32": torch.float32}[self.out_dtype]
         self.out = torch.empty(inp.n_decode, w.n_q_heads, w.head_dim, dtype=tdt, device=self.dev)
         self.lse = torch.empty(inp.n_decode, w.n_q_heads, dtype=torch.float32, device=self.dev)
-        need = ek.workspace_bytes(self.shape, inp.n_decode, inp.total_decode_tokens, 1)
+        need = ek.workspace_bytes(self.shape, inp.n_decode, inp.total_decode_tokens, 0)
         self.out_prefill = self.lse_prefill = None
         if self.q_prefill is not None:
             T_q = int(self.q_prefill.shape[0])

@@ -72,6 +72,21 @@ def test_shape_validation(lib):
     assert code(ek.decode_attn, bad_dtype, *args[:-1], _Ws(big), stream=0) == ek.ERR_DTYPE
     assert ek.workspace_bytes(ok, 1, 100, 1) > 0
     assert ek.workspace_bytes(ok, 0, 100, 1) == 0
+    assert ek.workspace_bytes(ok, 1, 100, -1) == 0
+
+
+def test_workspace_covers_a_prefill_chunk_only_when_asked():
+    sh = ek.make_shape(32, 8, 128, 128, "bf16")
+    dec = ek.workspace_bytes(sh, 1, 20000, 0)
+    one = ek.workspace_bytes(sh, 1, 20000, 1)
+    short = ek.workspace_bytes(sh, 1, 20000, 500)
+    long_ = ek.workspace_bytes(sh, 1, 20000, 8192)
+    assert 0 < dec <= one <= short
+    # a short chunk in front of a long context is split over the keys: room for 8 shares of
+    # (d + 2) fp32 words per query and head on top of what one query needs
+    assert short - one >= 499 * 32 * 8 * 130 * 4 * 0.9
+    # chunks of 1024 queries and more are not split, but a caller may still pass shorter ones
+    assert long_ - one >= 1023 * 32 * 8 * 130 * 4 * 0.9
 
 
 class _Ws:

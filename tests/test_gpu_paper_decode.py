@@ -177,6 +177,8 @@ def test_decode_extras_full_size_sampled():
     (4, 4, 128, 512, "bf16", 260, 200),       # everything retained
     (32, 8, 128, 64, "bf16", 330, 300),       # half a head retained (the paper's m = 64 preset)
     (8, 8, 64, 256, "f32", 200, 150),         # fp32: the streaming path rotates in the kernel
+    (8, 2, 128, 128, "bf16", 4300, 333),      # short chunk in front of a long context: keys cut into shares
+    (32, 8, 128, 64, "bf16", 2100, 130),      # the same with the paper's m = 64 preset
 ])
 def test_prefill_rope(H_q, H_kv, d, m, dtype, plen, pq):
     w = synth.Workload(f"ppx_{H_q}_{H_kv}_{d}_{m}_{dtype}", dtype, H_q, H_kv, d, m, seed=700 + H_q + m,
