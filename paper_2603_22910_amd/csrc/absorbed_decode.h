@@ -286,10 +286,24 @@ __global__ __launch_bounds__(256, NST == 2 ? 2 : 1) void scores_kernel(Args a, S
 }
 
 // ---------------------------------------------------------------------------
-// (max, sum of 2^(S - max)) of one (token split, head) piece of a row of S^T.
-// grid = (H_q, splits), 256 threads.
+// (max, sum of 2^(S - max)) of one (token split, head) piece of a row of S^T, in one pass over
+// the scores: every thread keeps a running (max, sum) pair over its elements, four independent
+// chains per thread, and the pairs are merged exactly (sum' = sum 2^(max - max')).
+// grid = (H_q, splits), NT threads.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void softmax_stats_kernel(Args a, SeqMeta meta) {
+__device__ __forceinline__ void ml_push(float& M, float& l, float x) {
+  const float Mn = fmaxf(M, x);                 // x is finite: Mn is finite from the first element on
+  l = l * exp2f(M - Mn) + exp2f(x - Mn);        // (M = -inf: the old sum, 0, is scaled by 0)
+  M = Mn;
+}
+__device__ __forceinline__ void ml_merge(float& M, float& l, float M2, float l2) {
+  const float Mn = fmaxf(M, M2);
+  const float w1 = M == -INFINITY ? 0.f : exp2f(M - Mn), w2 = M2 == -INFINITY ? 0.f : exp2f(M2 - Mn);
+  l = l * w1 + l2 * w2;
+  M = Mn;
+}
+template <int NT>
+__global__ __launch_bounds__(NT) void softmax_stats_kernel(Args a, SeqMeta meta) {
   const int h = blockIdx.x, sp = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int b = find_seq(meta.tbase, meta.n, sp);
   const int t_begin = (sp - meta.tbase[b]) * a.split_tokens;
@@ -297,22 +311,33 @@ __global__ __launch_bounds__(256) void softmax_stats_kernel(Args a, SeqMeta meta
   const int j0 = max(0, a.win.lo(L) - t_begin);                       // window tokens are left out
   const int n = min(min(L, a.win.hi(L)) - t_begin, a.split_tokens);   // (an empty piece gets (-inf, 0))
   const float* row = a.s + (int64_t)h * a.s_ld + (int64_t)meta.sbase[b] * kSlotTokens + t_begin;
-  __shared__ float s_red[4];
-  float M = -INFINITY;
-  for (int j = j0 + tid; j < n; j += 256) M = fmaxf(M, row[j]);
-  M = wave_max(M, 64);
-  if (lane == 0) s_red[wave] = M;
-  __syncthreads();
-  M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
-  float l = 0.f;
-  for (int j = j0 + tid; j < n; j += 256) l += exp2f(row[j] - M);
-  l = wave_sum(l, 64);
-  __syncthreads();
-  if (lane == 0) s_red[wave] = l;
+  __shared__ float s_m[NT / 64], s_l[NT / 64];
+  float M[4], l[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) { M[c] = -INFINITY; l[c] = 0.f; }
+  int j = j0 + tid;
+  for (; j + 3 * NT < n; j += 4 * NT) {
+    float x[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) x[c] = row[j + c * NT];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) ml_push(M[c], l[c], x[c]);
+  }
+  for (; j < n; j += NT) ml_push(M[0], l[0], row[j]);
+#pragma unroll
+  for (int c = 1; c < 4; ++c) ml_merge(M[0], l[0], M[c], l[c]);
+  // over the wave, then over the waves
+  const float Mw = wave_max(M[0], 64);
+  float lw = M[0] == -INFINITY ? 0.f : l[0] * exp2f(M[0] - Mw);
+  lw = wave_sum(lw, 64);
+  if (lane == 0) { s_m[wave] = Mw; s_l[wave] = lw; }
   __syncthreads();
   if (tid == 0) {
+    float Mt = s_m[0], lt = s_l[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) ml_merge(Mt, lt, s_m[w], s_l[w]);
     float* ml = a.ml + ((int64_t)sp * a.H_pad + h) * 2;
-    ml[0] = M; ml[1] = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+    ml[0] = Mt; ml[1] = lt;
   }
 }
 

@@ -823,7 +823,9 @@ int absorbed_impl(const Dims& dm, bool value_only, const echokv_layer_cache* an,
         if (rc) return rc;
       }
     }
-    hipLaunchKernelGGL(absorbed::softmax_stats_kernel, dim3(dm.H_q, splits), dim3(256), 0, st, a, mt);
+    // few long pieces: more threads on each
+    if ((int64_t)dm.H_q * splits < 1024 && ts >= 2048) hipLaunchKernelGGL(absorbed::softmax_stats_kernel<1024>, dim3(dm.H_q, splits), dim3(1024), 0, st, a, mt);
+    else hipLaunchKernelGGL(absorbed::softmax_stats_kernel<256>, dim3(dm.H_q, splits), dim3(256), 0, st, a, mt);
     LAUNCH_CHECK();
     hipLaunchKernelGGL(absorbed::pv_kernel, dim3(splits * pl.n_col_tiles, nhb), dim3(absorbed::kPvWaves * 64), 0, st, a, mt);
     LAUNCH_CHECK();
