@@ -23,6 +23,12 @@
  *  - Work is enqueued on `hip_stream` (a hipStream_t, NULL = default stream);
  *    results are valid once that stream has been synchronised.  Two calls that
  *    share a workspace must be ordered on one stream.
+ *  - Threads: calls from several host threads are fine as long as they share no
+ *    workspace (or order their use of it) -- the library keeps no state per call.
+ *    Exceptions: the first launch of the long-chunk prefill kernels on a device
+ *    sets a kernel attribute through an unguarded per-device flag (make the first
+ *    echokv_prefill_attn call of a process from one thread), the profiling aids
+ *    at the end of this header, and echokv_decode_attn_static.
  *  - Flattening is head-major: flattened dim g*d + i is feature i of KV head g.
  *    Query head h reads KV head h / (H_q / H_kv).
  *  - Row-major everywhere; a "row" is one token.
@@ -75,6 +81,16 @@ typedef enum { ECHOKV_BF16 = 0, ECHOKV_F32 = 1 } echokv_dtype;
                                   of predictor inputs is multiplied by W_V afterwards,
                                   which halves the matrix work.  Same conditions as
                                   ECHOKV_FLAG_ABSORBED; the two exclude each other */
+#define ECHOKV_FLAG_W_AUGMENTED 32u /* w_k / w_v point at weights extended once by
+                                  echokv_augment_weights.  Only a layer whose m splits
+                                  a head (m % d != 0, e.g. the paper's m = 64 with
+                                  d = 128) has such an extension; without the flag every
+                                  decode / prefill call builds it in its workspace.
+                                  Honoured by echokv_decode_attn(_ex, _static) and
+                                  echokv_prefill_attn(_ex) on the fused and unfused
+                                  paths; with an absorbed mode, and in every other
+                                  entry point that takes weights,
+                                  ECHOKV_ERR_UNSUPPORTED */
 
 /* One (anchor, target) layer pair. */
 typedef struct {
@@ -159,6 +175,22 @@ int echokv_reconstruct(const echokv_shape *shape, const echokv_layer_cache *anch
  *   w_packed : device [D - m, D + m], same dtype, must not overlap w */
 int echokv_pack_weights(const echokv_shape *shape, const void *w, void *w_packed,
                         void *hip_stream);
+
+/* One-time extension of the predictor weights of a layer whose retained width
+ * splits a head (Eq. 2 with m % d = r > 0; Eq. 6 puts the r retained dims of that
+ * head in front of its predicted ones).  The kernels treat the split head as
+ * fully predicted: w_aug = [S | w] with r selector columns S in front, column v
+ * of S being 1 at input row D + (m - r) + v (that retained dim of the target
+ * layer) and 0 elsewhere, so the product copies those dims exactly.  The
+ * weights of a layer are constant while serving: extend them once at load time
+ * and pass the extended pointers with ECHOKV_FLAG_W_AUGMENTED set.
+ *   w_k, w_v         : device [D + m, D - m] row-major
+ *   w_k_aug, w_v_aug : device [D + m, D - m + r], same dtype, four distinct buffers
+ * With r == 0 the extension is a plain copy (and the flag changes nothing).
+ * echokv_augmented_weight_elems: elements of one extended matrix, 0 on a bad shape. */
+size_t echokv_augmented_weight_elems(const echokv_shape *shape);
+int echokv_augment_weights(const echokv_shape *shape, const void *w_k, const void *w_v,
+                           void *w_k_aug, void *w_v_aug, void *hip_stream);
 
 /* Bytes of workspace that echokv_decode_attn (batch sequences holding
  * total_tokens cached tokens in all) needs and, when max_q >= 1, that

@@ -23,6 +23,7 @@ FLAG_W_PACKED = 2
 FLAG_STAGED = 4
 FLAG_ABSORBED = 8
 FLAG_ABSORB_V = 16
+FLAG_W_AUGMENTED = 32
 
 EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_workspace_bytes", "echokv_decode_attn", "echokv_prefill_attn",
@@ -30,7 +31,8 @@ EXPORTS = ("echokv_status_string", "echokv_cache_append", "echokv_reconstruct",
            "echokv_cache_compress", "echokv_decode_attn_ex", "echokv_window_append",
            "echokv_mlp_workspace_bytes", "echokv_decode_attn_mlp", "echokv_profile_stream_read",
            "echokv_fit_workspace_bytes", "echokv_fit_linear", "echokv_prefill_attn_ex",
-           "echokv_decode_attn_static", "echokv_profile_read_channel", "echokv_decode_path")
+           "echokv_decode_attn_static", "echokv_profile_read_channel", "echokv_decode_path",
+           "echokv_augmented_weight_elems", "echokv_augment_weights")
 ACT_RELU, ACT_SILU = 1, 2
 PATH_FUSED, PATH_FUSED_DIRECT, PATH_UNFUSED, PATH_ABSORBED, PATH_ABSORB_V, PATH_RETAINED_ONLY = range(6)
 
@@ -130,6 +132,11 @@ def load() -> C.CDLL:
                                           C.POINTER(LayerCacheC), C.c_void_p]
     lib.echokv_pack_weights.restype = C.c_int
     lib.echokv_pack_weights.argtypes = [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.echokv_augmented_weight_elems.restype = C.c_size_t
+    lib.echokv_augmented_weight_elems.argtypes = [C.POINTER(Shape)]
+    lib.echokv_augment_weights.restype = C.c_int
+    lib.echokv_augment_weights.argtypes = [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_void_p]
     lib.echokv_profile_enable.restype = C.c_int
     lib.echokv_profile_enable.argtypes = [C.c_int]
     lib.echokv_profile_read.restype = C.c_int
@@ -357,6 +364,15 @@ def prefill_attn_ex(shape: Shape, anchor: LayerCache, target: LayerCache, w_k, w
 def pack_weights(shape: Shape, w, w_packed, stream=None):
     _check(load().echokv_pack_weights(C.byref(shape), _ptr(w), _ptr(w_packed), _stream(stream)),
            "echokv_pack_weights")
+
+
+def augmented_weight_elems(shape: Shape) -> int:
+    return int(load().echokv_augmented_weight_elems(C.byref(shape)))
+
+
+def augment_weights(shape: Shape, w_k, w_v, w_k_aug, w_v_aug, stream=None):
+    _check(load().echokv_augment_weights(C.byref(shape), _ptr(w_k), _ptr(w_v), _ptr(w_k_aug), _ptr(w_v_aug),
+                                         _stream(stream)), "echokv_augment_weights")
 
 
 def profile_stream_read(buf, repeats: int = 5) -> float:

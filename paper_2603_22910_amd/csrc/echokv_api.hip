@@ -30,6 +30,7 @@ struct Dims {
   // columns that copy the split head's retained dims, so that head looks fully predicted to them.
   int g0, r, d_out_v;
   bool bf16, out_bf16;
+  bool w_aug;      // ECHOKV_FLAG_W_AUGMENTED: the caller's weights carry the selector columns already
   float scale;
 };
 
@@ -52,6 +53,7 @@ int check_shape(const echokv_shape* s, Dims* o) {
   o->G = o->H_q / o->H_kv;
   o->g0 = o->m / o->d; o->r = o->m % o->d; o->d_out_v = o->d_out + o->r;
   o->bf16 = s->dtype == ECHOKV_BF16; o->out_bf16 = s->out_dtype == ECHOKV_BF16;
+  o->w_aug = (s->flags & ECHOKV_FLAG_W_AUGMENTED) != 0;
   o->es = o->bf16 ? 2 : 4; o->oes = o->out_bf16 ? 2 : 4;
   o->scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / std::sqrt((float)o->d);
   return ECHOKV_OK;
@@ -195,7 +197,7 @@ template <typename T>
 int effective_weights(const Dims& dm, const void* w_k, const void* w_v, char* ws, const WsPlan& wp,
                       const T** wk, const T** wv, hipStream_t st) {
   *wk = (const T*)w_k; *wv = (const T*)w_v;
-  if (dm.r == 0 || dm.d_out == 0) return ECHOKV_OK;
+  if (dm.r == 0 || dm.d_out == 0 || dm.w_aug) return ECHOKV_OK;
   T* ak = (T*)(ws + wp.off_wk);
   T* av = (T*)(ws + wp.off_wv);
   AugArgs<T> a;
@@ -701,7 +703,7 @@ size_t absorbed_ws_bytes(const Dims& dm, int batch, int64_t total_tokens) {
 }
 constexpr uint32_t kAbsModes = ECHOKV_FLAG_ABSORBED | ECHOKV_FLAG_ABSORB_V;
 bool absorbed_supported(const Dims& dm, uint32_t flags) {
-  if (!dm.bf16 || (flags & (ECHOKV_FLAG_UNFUSED | ECHOKV_FLAG_W_PACKED | ECHOKV_FLAG_STAGED))) return false;
+  if (!dm.bf16 || (flags & (ECHOKV_FLAG_UNFUSED | ECHOKV_FLAG_W_PACKED | ECHOKV_FLAG_STAGED | ECHOKV_FLAG_W_AUGMENTED))) return false;
   if ((flags & kAbsModes) == kAbsModes) return false;
   if ((flags & ECHOKV_FLAG_ABSORB_V) && !fused_decode_supported<bf16_t>(dm.d, dm.G)) return false;
   return true;
@@ -911,6 +913,36 @@ int echokv_pack_weights(const echokv_shape* shape, const void* w, void* w_packed
   return ECHOKV_OK;
 }
 
+size_t echokv_augmented_weight_elems(const echokv_shape* shape) {
+  Dims dm;
+  if (check_shape(shape, &dm) != ECHOKV_OK) return 0;
+  return (size_t)dm.d_in * dm.d_out_v;
+}
+
+int echokv_augment_weights(const echokv_shape* shape, const void* w_k, const void* w_v,
+                           void* w_k_aug, void* w_v_aug, void* hip_stream) {
+  Dims dm;
+  int rc = check_shape(shape, &dm);
+  if (rc) return rc;
+  if (dm.d_out == 0) return ECHOKV_OK;
+  if (!w_k || !w_v || !w_k_aug || !w_v_aug) return ECHOKV_ERR_NULL;
+  if (w_k == w_k_aug || w_v == w_v_aug || w_k_aug == w_v_aug) return ECHOKV_ERR_SHAPE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (dm.bf16) {
+    AugArgs<bf16_t> a;
+    a.w[0] = (const bf16_t*)w_k; a.w[1] = (const bf16_t*)w_v; a.out[0] = (bf16_t*)w_k_aug; a.out[1] = (bf16_t*)w_v_aug;
+    a.d_in = dm.d_in; a.d_out = dm.d_out; a.r = dm.r; a.sel0 = dm.D + dm.g0 * dm.d;
+    hipLaunchKernelGGL((augment_weights_kernel<bf16_t>), dim3(dm.d_in, 2), dim3(256), 0, st, a);
+  } else {
+    AugArgs<float> a;
+    a.w[0] = (const float*)w_k; a.w[1] = (const float*)w_v; a.out[0] = (float*)w_k_aug; a.out[1] = (float*)w_v_aug;
+    a.d_in = dm.d_in; a.d_out = dm.d_out; a.r = dm.r; a.sel0 = dm.D + dm.g0 * dm.d;
+    hipLaunchKernelGGL((augment_weights_kernel<float>), dim3(dm.d_in, 2), dim3(256), 0, st, a);
+  }
+  LAUNCH_CHECK();
+  return ECHOKV_OK;
+}
+
 int echokv_profile_enable(int on) {
   g_prof.on = on != 0;
   return ECHOKV_OK;
@@ -1110,7 +1142,7 @@ int echokv_reconstruct(const echokv_shape* shape, const echokv_layer_cache* anch
   if (rc) return rc;
   rc = check_pair(dm, anchor, target);
   if (rc) return rc;
-  if (shape->flags & ECHOKV_FLAG_W_PACKED) return ECHOKV_ERR_UNSUPPORTED;
+  if (shape->flags & (ECHOKV_FLAG_W_PACKED | ECHOKV_FLAG_W_AUGMENTED)) return ECHOKV_ERR_UNSUPPORTED;
   if (seq < 0 || seq >= anchor->batch) return ECHOKV_ERR_SHAPE;
   if (tok_begin < 0 || tok_end < tok_begin || tok_end > anchor->seq_len[seq]) return ECHOKV_ERR_SHAPE;
   if (dm.d_out > 0 && (!w_k || !w_v)) return ECHOKV_ERR_NULL;

@@ -182,6 +182,25 @@ def test_compress_and_pack_argument_errors(lib):
     assert code(ek.pack_weights, full_ret, None, None, stream=0) == ek.OK      # nothing to pack
 
 
+def test_augmented_weights_argument_rules():
+    split = ek.make_shape(32, 8, 128, 64, "bf16")                     # m = 64 cuts head 0 in two: r = 64
+    whole = ek.make_shape(32, 8, 128, 128, "bf16")
+    assert ek.augmented_weight_elems(split) == (1024 + 64) * (1024 - 64 + 64)
+    assert ek.augmented_weight_elems(whole) == (1024 + 128) * (1024 - 128)        # r = 0: the plain size
+    assert ek.augmented_weight_elems(ek.make_shape(8, 3, 64, 256, "f32")) == 0
+    assert code(ek.augment_weights, split, None, FAKE, FAKE, FAKE, stream=0) == ek.ERR_NULL
+    assert code(ek.augment_weights, split, FAKE, FAKE, FAKE, FAKE, stream=0) == ek.ERR_SHAPE     # in place
+    assert code(ek.augment_weights, ek.make_shape(8, 8, 64, 512, "f32"), None, None, None, None, stream=0) == ek.OK
+    # entry points that do not take extended weights say so
+    a = ek.LayerCache(FAKE, FAKE, 1024, 512, [0], [100], [256])
+    t = ek.LayerCache(FAKE, FAKE, 64, 512, [0], [100], [256])
+    aug = ek.make_shape(32, 8, 128, 64, "bf16"); aug.flags = ek.FLAG_W_AUGMENTED
+    assert code(ek.reconstruct, aug, a, t, FAKE, FAKE, 0, 0, 10, FAKE, FAKE, stream=0) == ek.ERR_UNSUPPORTED
+    for mode in (ek.FLAG_ABSORBED, ek.FLAG_ABSORB_V):
+        sh = ek.make_shape(32, 8, 128, 64, "bf16"); sh.flags = ek.FLAG_W_AUGMENTED | mode
+        assert code(ek.decode_attn, sh, a, t, FAKE, FAKE, FAKE, FAKE, None, _Ws(1 << 30), stream=0) == ek.ERR_UNSUPPORTED
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(ek, "_LIB", None)
     monkeypatch.setattr(ek, "LIB_PATH", str(tmp_path / "libechokv.so"))

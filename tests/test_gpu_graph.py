@@ -43,16 +43,19 @@ def test_decode_in_a_captured_graph_matches_eager_on_every_replay(flags):
         assert float(got.float().abs().sum()) > 0
 
 
-@pytest.mark.parametrize("pq,use_rope", [pytest.param(300, False, id="short"), pytest.param(1100, False, id="long"),
-                                         pytest.param(1100, True, id="long+rope")])
-def test_prefill_in_a_captured_graph_matches_eager_on_every_replay(pq, use_rope):
-    """Both prefill attention kernels (and the key rotation ahead of them).  The first call on
+@pytest.mark.parametrize("pq,use_rope,ctx", [
+    pytest.param(300, False, 211, id="short"), pytest.param(1100, False, 211, id="long"),
+    pytest.param(1100, True, 211, id="long+rope"),
+    pytest.param(300, False, 2500, id="short-behind-long-context"),       # split over the keys + merge kernel
+    pytest.param(300, True, 2500, id="short-behind-long-context+rope")])
+def test_prefill_in_a_captured_graph_matches_eager_on_every_replay(pq, use_rope, ctx):
+    """The prefill attention kernels (and the key rotation ahead of them).  The first call on
     a device sets a function attribute of the long-chunk kernel: it runs before the capture."""
-    w = synth.Workload("graph_pf", "bf16", 8, 4, 128, 256, seed=62, seq_lens=(5,), prefill_len=pq + 211,
+    w = synth.Workload("graph_pf", "bf16", 8, 4, 128, 256, seed=62, seq_lens=(5,), prefill_len=pq + ctx,
                        prefill_q=pq)
     inp = synth.generate(w)
     dw = DeviceWorkload(inp)
-    rope = tuple(t.to(dw.dev) for t in synth.rope_tables(128, pq + 300)) if use_rope else None
+    rope = tuple(t.to(dw.dev) for t in synth.rope_tables(128, pq + ctx + 89)) if use_rope else None
     run = (lambda st=None: dw.prefill_ex(rope, stream=st)) if use_rope else (lambda st=None: dw.prefill(stream=st))
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):

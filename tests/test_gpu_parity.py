@@ -535,6 +535,42 @@ def test_decode_paper_presets(m, flags):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_split_head_weights_extended_once(dtype):
+    """echokv_augment_weights + ECHOKV_FLAG_W_AUGMENTED: the same kernels on the same extended
+    weights as the per-call extension -> bit-equal decode (fused and unfused) and prefill."""
+    w = synth.Workload("preset_m64_aug", dtype, 8, 4, 128, 64, seed=63, seq_lens=(300, 77),
+                       prefill_len=260, prefill_q=200)
+    inp = synth.generate(w)
+    dw = DeviceWorkload(inp)
+    tdt = dw.W_K.dtype
+    n = ek.augmented_weight_elems(dw.shape)
+    assert n == (512 + 64) * (512 - 64 + 64)
+    wk_aug = torch.empty(n, dtype=tdt, device=dw.dev); wv_aug = torch.empty(n, dtype=tdt, device=dw.dev)
+    ek.augment_weights(dw.shape, dw.W_K, dw.W_V, wk_aug, wv_aug); torch.cuda.synchronize()
+    aug = wk_aug.view(512 + 64, 512).float().cpu().numpy()
+    np.testing.assert_array_equal(aug[:, 64:], dw.W_K.float().cpu().numpy().reshape(512 + 64, 448))
+    sel = np.zeros((512 + 64, 64), dtype=np.float32); sel[512 + np.arange(64), np.arange(64)] = 1.0
+    np.testing.assert_array_equal(aug[:, :64], sel)
+    for flags in (0, ek.FLAG_UNFUSED):
+        dw.shape.flags = flags
+        o0, l0 = dw.decode(); torch.cuda.synchronize()
+        o0, l0 = host(o0).copy(), host(l0).copy()
+        dw.shape.flags = flags | ek.FLAG_W_AUGMENTED
+        ek.decode_attn(dw.shape, dw.anchor, dw.target, wk_aug, wv_aug, dw.q, dw.out, dw.lse, dw.workspace)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(host(dw.out), o0); np.testing.assert_array_equal(host(dw.lse), l0)
+    dw.shape.flags = 0
+    p0, pl0 = dw.prefill(); torch.cuda.synchronize()
+    p0, pl0 = host(p0).copy(), host(pl0).copy()
+    dw.shape.flags = ek.FLAG_W_AUGMENTED
+    ek.prefill_attn(dw.shape, dw.anchor_all, dw.target_all, wk_aug, wv_aug, inp.n_decode, dw.q_prefill, 200,
+                    inp.q_pos0, dw.out_prefill, dw.lse_prefill, dw.workspace)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(host(dw.out_prefill), p0); np.testing.assert_array_equal(host(dw.lse_prefill), pl0)
+    dw.shape.flags = 0
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_split_head_prefill_and_reconstruct(dtype):
     w = synth.Workload("preset_m64_pf", dtype, 8, 4, 128, 64, seed=61, seq_lens=(300,),
                        prefill_len=260, prefill_q=200)
