@@ -87,6 +87,12 @@ def test_workspace_covers_a_prefill_chunk_only_when_asked():
     assert short - one >= 499 * 32 * 8 * 130 * 4 * 0.9
     # chunks of 1024 queries and more are not split, but a caller may still pass shorter ones
     assert long_ - one >= 1023 * 32 * 8 * 130 * 4 * 0.9
+    # a prefill call checks the size it needs for its own chunk: a decode-sized workspace is refused
+    a = ek.LayerCache(FAKE, FAKE, 1024, 32768, [0], [20000], [32768])
+    t = ek.LayerCache(FAKE, FAKE, 128, 32768, [0], [20000], [32768])
+    args = (sh, a, t, FAKE, FAKE, 0, FAKE, 500, 19500, FAKE, None)
+    assert code(ek.prefill_attn, *args, _Ws(dec), stream=0) == ek.ERR_WORKSPACE
+    assert code(ek.prefill_attn, *args, _Ws(short - 256), stream=0) == ek.ERR_WORKSPACE
 
 
 class _Ws:
