@@ -60,6 +60,7 @@ struct Args {
   int64_t out_seq0;
   int32_t D, m, d_in, d_out, H_q, H_pad, G, d;
   int32_t s_ld, split_tokens, n_col_a, n_col_tiles, k_slices, k_slice;
+  int32_t single_split;  // every sequence is one token split: the value pass writes y and y_ml itself
   float qscale;          // softmax scale * log2(e)
 };
 
@@ -478,7 +479,13 @@ __global__ __launch_bounds__(kPvWaves * 64, 2) void pv_kernel(Args a, SeqMeta me
       for (int r = 0; r < 16; ++r) red[0][i * 16 + r][lane] = acc[i][r];
   }
   __syncthreads();
-  if (wave != 0 || !col_ok) return;
+  if (wave != 0) return;
+  if (a.single_split && ct == 0 && lh == 0 && head < a.H_q) {     // the split is the sequence: its (max, sum) is final
+    const float* ml = a.ml + ((int64_t)sp * a.H_pad + head) * 2;
+    a.y_ml[((int64_t)b * a.H_q + head) * 2] = ml[0];
+    a.y_ml[((int64_t)b * a.H_q + head) * 2 + 1] = ml[1];
+  }
+  if (!col_ok) return;
   float* yp = a.ypart + ((int64_t)sp * a.H_pad + hb * kHB) * a.d_in + (anchor ? 0 : a.D) + col;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -489,6 +496,14 @@ __global__ __launch_bounds__(kPvWaves * 64, 2) void pv_kernel(Args a, SeqMeta me
     hi.x = acc[4][r] + red[0][4 * 16 + r][lane]; hi.y = acc[5][r] + red[0][5 * 16 + r][lane];
     hi.z = acc[6][r] + red[0][6 * 16 + r][lane]; hi.w = acc[7][r] + red[0][7 * 16 + r][lane];
     float* dst = yp + (int64_t)hr * a.d_in;
+    if (a.single_split) {       // normalised, straight into y (what y_sum would make of one split)
+      const int ha = hb * kHB + hr;
+      if (ha >= a.H_q) continue;
+      const float l = a.ml[((int64_t)sp * a.H_pad + ha) * 2 + 1];
+      const float inv = l > 0.f ? 1.f / l : 0.f;        // l == 0: every counted token sits in the window
+      lo.x *= inv; lo.y *= inv; lo.z *= inv; lo.w *= inv; hi.x *= inv; hi.y *= inv; hi.z *= inv; hi.w *= inv;
+      dst = a.y + ((int64_t)b * a.H_q + ha) * a.d_in + (anchor ? 0 : a.D) + col;
+    }
     *reinterpret_cast<float4*>(dst) = lo;
     *reinterpret_cast<float4*>(dst + 4) = hi;
   }

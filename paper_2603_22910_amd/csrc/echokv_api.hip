@@ -829,11 +829,14 @@ int absorbed_impl(const Dims& dm, bool value_only, const echokv_layer_cache* an,
     if ((int64_t)dm.H_q * splits < 1024 && ts >= 2048) hipLaunchKernelGGL(absorbed::softmax_stats_kernel<1024>, dim3(dm.H_q, splits), dim3(1024), 0, st, a, mt);
     else hipLaunchKernelGGL(absorbed::softmax_stats_kernel<256>, dim3(dm.H_q, splits), dim3(256), 0, st, a, mt);
     LAUNCH_CHECK();
-    hipLaunchKernelGGL(absorbed::pv_kernel, dim3(splits * pl.n_col_tiles, nhb), dim3(absorbed::kPvWaves * 64), 0, st, a, mt);
-    LAUNCH_CHECK();
     int max_splits = 0;
     for (int b = 0; b < n; ++b) max_splits = std::max(max_splits, mt.tbase[b + 1] - mt.tbase[b]);
-    if (max_splits > 8) hipLaunchKernelGGL(absorbed::y_sum_kernel<4>, dim3((dm.d_in + 255) / 256, dm.H_q, n), dim3(256), 0, st, a, mt);
+    a.single_split = max_splits == 1 ? 1 : 0;
+    hipLaunchKernelGGL(absorbed::pv_kernel, dim3(splits * pl.n_col_tiles, nhb), dim3(absorbed::kPvWaves * 64), 0, st, a, mt);
+    LAUNCH_CHECK();
+    if (max_splits == 1) {
+      // (the value pass has written y and its (max, sum) itself)
+    } else if (max_splits > 8) hipLaunchKernelGGL(absorbed::y_sum_kernel<4>, dim3((dm.d_in + 255) / 256, dm.H_q, n), dim3(256), 0, st, a, mt);
     else hipLaunchKernelGGL(absorbed::y_sum_kernel<1>, dim3((dm.d_in + 1023) / 1024, dm.H_q, n), dim3(256), 0, st, a, mt);
     LAUNCH_CHECK();
     const dim3 og(dm.H_kv, pl.k_slices, (n * dm.G + 31) / 32);
