@@ -30,6 +30,33 @@ def test_exports_match_header(lib):
         assert getattr(lib, name) is not None
 
 
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """The boundary is a C ABI: the header compiles as strict C99 and as C++, and a C program that
+    names every declared entry point links against the built library (no compute call is made)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    hdr = open(os.path.join(ROOT, "include", "echokv.h")).read()
+    names = sorted(set(re.findall(r"\b(echokv_[a-z_]+)\s*\(", re.sub(r"/\*.*?\*/", "", hdr, flags=re.S))))
+    src = tmp_path / "use.c"
+    src.write_text('#include "echokv.h"\n#include <stdio.h>\nint main(void) {\n  const void *fn[] = {\n'
+                   + "".join(f"    (const void *)(size_t)&{n},\n" for n in names)
+                   + '  };\n  printf("%d %s\\n", (int)(sizeof fn / sizeof fn[0]), echokv_status_string(ECHOKV_OK));\n'
+                     "  return 0;\n}\n")
+    inc = os.path.join(ROOT, "include")
+    libdir = os.path.join(ROOT, "paper_2603_22910_amd")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", inc, "-c", str(src),
+                    "-o", str(tmp_path / "use.o")], check=True, capture_output=True)
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-I", inc, "-x", "c++", "-c", str(src),
+                    "-o", str(tmp_path / "use_cpp.o")], check=True, capture_output=True)
+    exe = tmp_path / "use"
+    subprocess.run(["gcc", str(tmp_path / "use.o"), "-o", str(exe), f"-L{libdir}", "-l:libechokv.so",
+                    f"-Wl,-rpath,{libdir}"], check=True, capture_output=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert out == [str(len(names)), "ok"]
+
+
 def test_status_strings(lib):
     seen = {ek.status_string(c) for c in range(9)}
     assert len(seen) == 9 and ek.status_string(0) == "ok"
